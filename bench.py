@@ -1,0 +1,161 @@
+"""Benchmark of the MoE dispatch/combine shuffle on one MI355X.
+
+A step is one pass of the whole hot path (layout, dispatch_send, dispatch_recv,
+combine_send, combine_reduce) over one synthetic batch that is already resident
+in HBM.  Prints ONE JSON line.  `value` is the achieved rate in GB/s: the
+algorithmic bytes of the staged data flow divided by the step time.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload dsv3_decode]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def algorithmic_bytes(wl, ttot, D, P, sizes):
+    """Bytes the staged method itself has to move (reads + writes), per kernel."""
+    Bx, Bw, Be, Bc = (sizes.x_row_bytes, sizes.wire_row_bytes,
+                      sizes.expert_x_row_bytes + 4 * sizes.scales_per_row, sizes.combine_row_bytes)
+    k = {
+        "dispatch_pack_kernel": ttot * Bx + D * Bw,
+        "fabric_copy_kernel(dispatch)": 2 * D * Bw,
+        "dispatch_unpack_kernel": D * Bw + P * Be,
+        "combine_pack_kernel": 2 * P * Bc,
+        "fabric_copy_kernel(combine)": 2 * P * Bc,
+        "combine_reduce_kernel": P * Bc + ttot * Bc,
+    }
+    if wl.dispatch_dtype != "bf16":
+        k["dispatch_pack_e4m3_kernel"] = k.pop("dispatch_pack_kernel")
+    dispatch = sum(v for n, v in k.items() if n.startswith(("dispatch", "fabric_copy_kernel(d")))
+    combine = sum(v for n, v in k.items() if n.startswith(("combine", "fabric_copy_kernel(c")))
+    return k, dispatch, combine
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="dsv3_decode")
+    ap.add_argument("--capacity-factor", type=float, default=1.5,
+                    help="per-rank buffer capacity as a multiple of the mean load (0 = worst case)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--profile-steps", type=int, default=30)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs the whole simulated expert-parallel group on ONE GPU; "
+              "--gpus above 1 is not supported", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2510_27656_amd import flmoe, harness, workloads
+
+    wl = workloads.WORKLOADS[args.workload]
+    inp = workloads.make_inputs(wl)
+    stats = workloads.describe(inp)
+    dev = harness.to_device(inp, "cuda:0")
+    cf = args.capacity_factor if args.capacity_factor > 0 else None
+    if wl.zipf_alpha > 0:
+        cf = None                       # skewed routing: size for the worst case
+    sh = harness.make_shuffle(inp, capacity_factor=cf)
+    ttot, D, P = stats["tokens_total"], stats["dedup_rows"], stats["pairs"]
+    per_kernel, bytes_dispatch, bytes_combine = algorithmic_bytes(wl, ttot, D, P, sh.sizes)
+    bytes_step = bytes_dispatch + bytes_combine
+
+    def step():
+        harness.run_hot_path(sh, dev)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    assert sh.status() == 0, "device status not clean after warm-up"
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    assert sh.status() == 0
+
+    # per-call split with events on the stream the library launches on
+    calls = ["layout", "dispatch_send", "dispatch_recv", "combine_send", "combine_reduce"]
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(args.profile_steps)]
+    for i in range(args.profile_steps):
+        ev[i][0].record()
+        sh.layout(dev["indices"], dev["num_tokens"]); ev[i][1].record()
+        sh.dispatch_send(dev["x"]); ev[i][2].record()
+        sh.dispatch_recv(); ev[i][3].record()
+        sh.combine_send(sh.expert_x); ev[i][4].record()
+        sh.combine_reduce(dev["weights"]); ev[i][5].record()
+    torch.cuda.synchronize()
+    call_us = {c: float(np.median([ev[i][j].elapsed_time(ev[i][j + 1]) for i in range(args.profile_steps)])) * 1e3
+               for j, c in enumerate(calls)}
+    dispatch_us = call_us["layout"] + call_us["dispatch_send"] + call_us["dispatch_recv"]
+    combine_us = call_us["combine_send"] + call_us["combine_reduce"]
+
+    # per-kernel durations (HIP events inside the library, on the same stream)
+    flmoe.fl_moe_profile_enable(sh.ctx, 1)
+    for _ in range(args.profile_steps):
+        step()
+        flmoe.fl_moe_profile_collect(sh.ctx)
+    flmoe.fl_moe_profile_enable(sh.ctx, 0)
+    prof = flmoe.fl_moe_profile_read(sh.ctx)
+    kern_us = {n: ms / cnt * 1e3 for n, (ms, cnt) in prof.items() if cnt}
+    dominant = max((n for n in kern_us if n in per_kernel), key=lambda n: kern_us[n])
+    achieved = per_kernel[dominant] / (kern_us[dominant] * 1e-6) / 1e9
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(tpath):
+        traffic = json.load(open(tpath)).get(args.workload, {}).get(dominant)
+    roofline = {"bound": "hbm", "kernel": dominant, "achieved": round(achieved, 1),
+                "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
+                "traffic": traffic, "algorithmic_bytes": per_kernel[dominant],
+                "avg_us": round(kern_us[dominant], 2)}
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle.reference_step import oracle_step
+        c0 = time.perf_counter()
+        oracle_step(inp)
+        c1 = time.perf_counter()
+        cpu = {"value": round(bytes_step / (c1 - c0) / 1e9, 3), "unit": "GB/s", "cores": 1,
+               "kind": "oracle", "seconds": round(c1 - c0, 2),
+               "sample": f"one full {wl.name} step (all {wl.n_ranks} ranks, {ttot} tokens), "
+                         "same algorithmic byte count, single thread"}
+
+    value = bytes_step / (ms_per_step * 1e-3) / 1e9
+    line = {
+        "metric": "dispatch+combine achieved HBM GB/s (algorithmic bytes / step time), "
+                  "T=128 H=7168 top-8, 256 experts" if args.workload == "dsv3_decode"
+                  else f"dispatch+combine achieved HBM GB/s, workload {args.workload}",
+        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if wl.dispatch_dtype == "bf16" else "e4m3+bf16",
+        "data": "synthetic",
+        "config": {"workload": wl.name, "ranks_simulated": wl.n_ranks, "experts": wl.n_experts,
+                   "tokens_per_rank": wl.tokens, "hidden": wl.hidden, "top_k": wl.top_k,
+                   "dedup_rows": D, "pairs": P, "capacity_factor": cf,
+                   "expert_stage": "identity (expert_y aliases expert_x)"},
+        "frac_of_hbm_peak": round(value / HBM_PEAK_GBPS, 4),
+        "algorithmic_bytes": {"dispatch": bytes_dispatch, "combine": bytes_combine},
+        "dispatch_us": round(dispatch_us, 1), "combine_us": round(combine_us, 1),
+        "call_us": {k: round(v, 1) for k, v in call_us.items()},
+        "kernel_us": {k: round(v, 2) for k, v in kern_us.items()},
+        "kernel_gbps": {k: round(per_kernel[k] / (kern_us[k] * 1e-6) / 1e9, 1)
+                        for k in kern_us if k in per_kernel},
+        "roofline": roofline, "cpu_baseline": cpu,
+    }
+    sh.close()
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,211 @@
+/*
+ * flmoe - MoE expert-parallel dispatch/combine token shuffle for MI355X (gfx950).
+ *
+ * C ABI of the shared library.  One GPU hosts the whole expert-parallel group as
+ * simulated ranks; the "fabric" between ranks is a device-side copy whose
+ * completion is signalled only through per-source arrival counters (the
+ * paper's ImmCounter idea, section TransferEngine / Completion Notification:
+ * a counter is bumped once a payload is fully delivered, and nothing else
+ * orders transfers).
+ *
+ * Problem statement (section MoE Dispatch/Combine, Architecture): N ranks host E
+ * experts (expert e lives on rank e / (E/N)); every rank holds up to T tokens of
+ * H hidden values and routes each to K distinct experts (the paper's R).
+ *
+ * Conventions for every entry point
+ *   - All tensor arguments are DEVICE pointers unless marked "host".  The library
+ *     never allocates or frees device memory: inputs, outputs and the workspace
+ *     belong to the caller and must stay valid until fl_moe_destroy.
+ *   - Device pointers must be 16-byte aligned, hidden*2 must be a multiple of 16,
+ *     the e4m3 dispatch needs hidden % 128 == 0.
+ *   - Tensors are rank-major: element [r] of the leading dimension belongs to
+ *     simulated rank r.  Each call acts for ranks [rank_begin, rank_begin +
+ *     rank_count); code acting for rank r reads only rank r's tensors and
+ *     receive buffers, and writes other ranks' memory only through the fabric
+ *     copy and its counters.  A real deployment would pass rank_count = 1.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  The
+ *     five shuffle calls only enqueue kernels: they never synchronise, never
+ *     allocate, and can be captured in a HIP graph.
+ *   - Return value: FL_OK or a negative FL_ERR_* for errors the host can see
+ *     (nothing is enqueued then).  Errors found on the device (bad expert id,
+ *     capacity overflow, arrival time-out) make the affected step a no-op on every
+ *     rank and latch a bit that fl_moe_status reports; they never cause an
+ *     out-of-bounds access or an unbounded wait.
+ */
+#ifndef FLMOE_H
+#define FLMOE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define FL_OK 0
+#define FL_ERR_INVALID_ARG (-1)
+#define FL_ERR_ALIGNMENT (-2)
+#define FL_ERR_WORKSPACE (-3)
+#define FL_ERR_HIP (-4)
+
+/* bits of the device status word */
+#define FL_STATUS_BAD_INDEX 1 /* expert id outside [0,E) or repeated inside a token */
+#define FL_STATUS_CAPACITY 2  /* a rank would receive more rows than its capacity    */
+#define FL_STATUS_TIMEOUT 4   /* an arrival counter did not reach its expectation     */
+
+#define FL_DTYPE_BF16 0
+/* OCP E4M3 (finite-only) bytes plus one fp32 scale per 128 elements, quantised
+ * by dispatch_send (workload of section Kernel Microbenchmarks: 7168 fp8 values
+ * and 56 fp32 scaling factors per token) */
+#define FL_DTYPE_E4M3_BLOCK128 1
+
+#define FL_FLAG_ZERO_PAD 1 /* dispatch_recv writes zeros into the padding rows between experts */
+
+#define FL_MAX_RANKS 64
+#define FL_MAX_EXPERTS 1024
+#define FL_MAX_TOPK 16
+#define FL_MAX_EXPERTS_PER_RANK 256
+
+typedef struct fl_moe_ctx fl_moe_ctx;
+
+typedef struct fl_moe_config {
+    int32_t n_ranks;        /* N, 1..FL_MAX_RANKS                                        */
+    int32_t n_experts;      /* E, multiple of N, <= FL_MAX_EXPERTS                       */
+    int32_t max_tokens;     /* T, upper bound of tokens per rank                         */
+    int32_t top_k;          /* K, 1..min(E, FL_MAX_TOPK)                                 */
+    int32_t hidden;         /* H                                                          */
+    int32_t dispatch_dtype; /* FL_DTYPE_*: payload type of dispatch; combine is bf16      */
+    int32_t expert_align;   /* every local expert but the first starts on a multiple of
+                               this many rows ("optional padding between experts",
+                               section Dispatch); >= 1                                    */
+    int32_t flags;          /* FL_FLAG_*                                                  */
+    int64_t recv_capacity_rows;   /* per rank: deduplicated rows it can receive; 0 = N*T  */
+    int64_t expert_capacity_rows; /* per rank: rows of its expert-major layout, padding
+                                     included; 0 = N*T*min(K, E/N) + padding              */
+    int64_t spin_limit;     /* polls of an arrival counter before FL_STATUS_TIMEOUT; 0 = default */
+} fl_moe_config;
+
+typedef struct fl_moe_sizes {
+    size_t workspace_bytes;       /* device bytes fl_moe_create needs (256-byte aligned)  */
+    int64_t recv_capacity_rows;   /* resolved capacities                                  */
+    int64_t expert_capacity_rows; /* also the rank stride, in rows, of expert_x/expert_y  */
+    int64_t send_capacity_rows;   /* T * min(K, N)                                        */
+    int64_t x_row_bytes;          /* 2*H                                                  */
+    int64_t wire_row_bytes;       /* bytes of one dispatched row in the send/receive
+                                     buffers: 2*H, or H + 4*H/128 for e4m3                */
+    int64_t expert_x_row_bytes;   /* 2*H or H                                             */
+    int64_t scales_per_row;       /* 0 or H/128                                           */
+    int64_t combine_row_bytes;    /* 2*H                                                  */
+} fl_moe_sizes;
+
+/* Device pointers into the workspace, valid until fl_moe_destroy; contents are
+ * those of the last fl_moe_layout on the stream.  All int32. */
+typedef struct fl_moe_layout_view {
+    const int32_t *counts;            /* C [N][E]    pairs per (source rank, expert)                 */
+    const int32_t *dedup_counts;      /* M [N][N]    distinct tokens per (source, destination rank)   */
+    const int32_t *tokens_per_expert; /* G [N][E/N]                                                   */
+    const int32_t *send_off;          /* [N][N+1]  exclusive scan of M[s][.]                          */
+    const int32_t *recv_off;          /* [N][N+1]  exclusive scan of M[.][d]: source s owns rows
+                                         [recv_off[d][s], recv_off[d][s+1]) of d's receive buffer     */
+    const int32_t *expert_off;        /* [N][E/N+1] first row of each local expert; last = end of rows */
+    const int32_t *comb_off;          /* [N][N+1]  start of each peer's reply in the combine receive
+                                         buffer of rank s                                              */
+    const int32_t *comb_pos;          /* [N][T][K] row of pair (s,t,k) in that buffer                  */
+    const int32_t *plan_ok;           /* [N] 1 when the step is valid for the rank                     */
+} fl_moe_layout_view;
+
+/* Test/diagnostic view of internal buffers (layouts are the library's own). */
+typedef struct fl_moe_debug_view {
+    void *buf_a;              /* per rank: dispatch send buffer / combine receive buffer  */
+    void *buf_b;              /* per rank: dispatch receive buffer / combine send buffer  */
+    int64_t buf_a_rank_bytes;
+    int64_t buf_b_rank_bytes;
+    uint32_t *arrive_route;   /* [N][N] monotone arrival counters, [destination][source]  */
+    uint32_t *arrive_disp;
+    uint32_t *arrive_comb;
+    uint32_t *epoch_route;    /* [N] number of layout / dispatch_send / combine_send calls */
+    uint32_t *epoch_disp;
+    uint32_t *epoch_comb;
+    int32_t *status;          /* the device status word                                    */
+} fl_moe_debug_view;
+
+/* Sizes and strides implied by a configuration.  Host only; no GPU needed. */
+int fl_moe_query_sizes(const fl_moe_config *cfg /*host*/, fl_moe_sizes *out /*host*/);
+
+/* Binds a context to a caller-owned device workspace of at least
+ * sizes.workspace_bytes bytes and clears its counters (this call synchronises;
+ * it is set-up, not part of the hot path). */
+int fl_moe_create(const fl_moe_config *cfg /*host*/, void *workspace, size_t workspace_bytes,
+                  fl_moe_ctx **out /*host*/);
+int fl_moe_destroy(fl_moe_ctx *ctx);
+
+/* Step 1 (section Dispatch: count tokens per expert; section Architecture: peers
+ * exchange per-expert counts to find a unique range in each contiguous receive
+ * buffer).  indices [N][T][K] int32 expert ids, distinct within a token;
+ * num_tokens [N] int32 (<= T).  For every rank in the range it counts pairs per
+ * expert and distinct tokens per destination rank with LDS bit matrices and
+ * popcount prefix scans (deterministic, no ticket atomics), pushes the counts to
+ * every peer, and derives all offsets of the step from the counts it received.
+ * Both arrays must stay unchanged until the step's combine_reduce has run.
+ * `view` (host, may be NULL) receives pointers to the resulting tables. */
+int fl_moe_layout(fl_moe_ctx *ctx, int rank_begin, int rank_count, const int32_t *indices,
+                  const int32_t *num_tokens, fl_moe_layout_view *view /*host*/, void *stream);
+
+/* Step 2 (section Dispatch: tokens are copied into send buffers, a contiguous
+ * source per peer, then scattered).  x [N][T][H] bf16.  Packs one copy of each
+ * token per distinct destination rank (quantising to e4m3 when configured),
+ * copies every (source, destination) segment into the destination's receive
+ * buffer and bumps arrive_disp[destination][source] once the segment is whole;
+ * empty segments still notify. */
+int fl_moe_dispatch_send(fl_moe_ctx *ctx, int rank_begin, int rank_count, const void *x,
+                         void *stream);
+
+/* Step 3 (section Dispatch: wait for all transfers, then reorder tokens with
+ * optional padding into a layout suitable for grouped GEMM).  expert_x
+ * [N][expert_capacity_rows][H] (bf16 or e4m3 bytes): rows of rank d ordered by
+ * (local expert, source rank, token index).  expert_scales
+ * [N][expert_capacity_rows][H/128] fp32, e4m3 only (else NULL).
+ * tokens_per_expert [N][E/N] int32 out. */
+int fl_moe_dispatch_recv(fl_moe_ctx *ctx, int rank_begin, int rank_count, void *expert_x,
+                         float *expert_scales, int32_t *tokens_per_expert, void *stream);
+
+/* Step 4 (section Combine: a single scatter per peer re-using the routing
+ * information).  expert_y [N][expert_capacity_rows][H] bf16, same row layout as
+ * expert_x.  Packs each peer's rows contiguously, copies them into the peer's
+ * combine receive buffer and bumps arrive_comb[peer][this rank]. */
+int fl_moe_combine_send(fl_moe_ctx *ctx, int rank_begin, int rank_count, const void *expert_y,
+                        void *stream);
+
+/* Step 5 (section Combine: weighted average computed locally; fp32 accumulation
+ * in a fixed order, section Comparison with DeepEP).  weights [N][T][K] fp32,
+ * out [N][T][H] bf16:
+ *   out[s][t] = bf16( sum_{k=0..K-1} weights[s][t][k] * float(y of pair (s,t,k)) )
+ * fp32 accumulator starting at +0, fused multiply-add, k ascending, one final
+ * round-to-nearest-even; no division by the weight sum.  Rows t >= num_tokens[s]
+ * are not written. */
+int fl_moe_combine_reduce(fl_moe_ctx *ctx, int rank_begin, int rank_count, const float *weights,
+                          void *out, void *stream);
+
+/* Reads and clears the device status word (synchronises the stream). */
+int fl_moe_status(fl_moe_ctx *ctx, int32_t *host_out /*host*/, void *stream);
+
+const char *fl_moe_strerror(int code);
+
+int fl_moe_debug_views(fl_moe_ctx *ctx, fl_moe_debug_view *out /*host*/);
+
+/* Per-kernel timing with HIP events on the caller's stream.  While enabled,
+ * every kernel launch of the shuffle calls is bracketed by an event pair;
+ * fl_moe_profile_collect synchronises, adds the elapsed times of the launches
+ * since the last collect to per-kernel totals, and fl_moe_profile_read returns
+ * totals (ms) and launch counts for kernel ids 0..FL_KERNEL_COUNT-1. */
+#define FL_KERNEL_COUNT 9
+int fl_moe_profile_enable(fl_moe_ctx *ctx, int on);
+int fl_moe_profile_collect(fl_moe_ctx *ctx, void *stream);
+int fl_moe_profile_read(fl_moe_ctx *ctx, double *total_ms /*host [FL_KERNEL_COUNT]*/,
+                        int64_t *launches /*host [FL_KERNEL_COUNT]*/);
+const char *fl_moe_kernel_name(int kernel_id);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FLMOE_H */

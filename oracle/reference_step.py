@@ -1,0 +1,34 @@
+"""One full step through the CPU oracle (test infrastructure)."""
+from dataclasses import dataclass
+
+import numpy as np
+
+from . import oracle as orc
+
+
+@dataclass
+class OracleStep:
+    lay: orc.Layout
+    comb_pos: np.ndarray
+    expert_rows: list          # per rank: [rows][H] uint16 (dispatched payload)
+    expert_y: np.ndarray       # [N][stride][H] uint16 (after the stand-in expert)
+    stride: int
+    out: np.ndarray            # [N][T][H] uint16
+
+
+def oracle_step(inp, align=1, zero_pad=True) -> OracleStep:
+    wl = inp.wl
+    N, E, K, H = wl.n_ranks, wl.n_experts, wl.top_k, wl.hidden
+    nt = inp.num_tokens
+    lay = orc.layout(N, E, K, nt, inp.indices, align)
+    stride = max(int(lay.expert_off[:, -1].max()), 1)
+    rows = []
+    Y = np.zeros((N, stride, H), np.uint16)
+    for d in range(N):
+        r = orc.dispatch_rank(d, N, E, K, nt, inp.indices, inp.x, align, zero_pad=zero_pad)
+        rows.append(r)
+        Y[d, :r.shape[0]] = r
+        if wl.expert != "identity":
+            orc.expert_scale_rank(d, N, E, lay, inp.expert_gain, H, Y[d])
+    out = orc.combine(N, E, K, nt, inp.indices, lay.slot, inp.weights, Y, stride, H)
+    return OracleStep(lay, orc.comb_pos(N, E, K, nt, inp.indices), rows, Y, stride, out)

@@ -1,0 +1,156 @@
+// Shared device-side definitions of the flmoe kernels (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/flmoe.h"
+
+namespace flmoe {
+
+constexpr int kWave = 64;
+
+// Shapes and strides of one context; passed to every kernel by value.
+struct Dims {
+    int N, E, El, T, K, H;
+    int dtype, align, flags;
+    int TT;               // tokens per LDS tile of route_count_kernel (multiple of 32)
+    int route_len;        // ints one rank pushes to every peer: C[E] | M[N] | comb_off[N] | valid
+    int scales_per_row;   // 0 or H/128
+    long long recv_cap, expert_cap, send_cap;   // rows per rank
+    long long Bx, Bw, Be, Bc;                   // row bytes: input, wire, expert_x, combine
+    long long bufA_rank_bytes, bufB_rank_bytes;
+    long long spin_limit;
+};
+
+// Device pointers into the caller's workspace.
+struct Tables {
+    int *status;
+    unsigned *epoch_route, *epoch_disp, *epoch_comb;          // [N]
+    unsigned *arrive_route, *arrive_disp, *arrive_comb;       // [N dst][N src], monotone
+    unsigned *seg_done_disp, *seg_done_comb;                  // [N src][N dst] rows delivered so far
+    int *routes;          // [N receiver][N source][route_len]
+    // written by the source side of the layout step
+    int *C;               // [N][E]
+    int *M;               // [N][N]
+    int *send_off;        // [N][N+1]
+    int *comb_off;        // [N][N+1]
+    int *send_row;        // [N][T][K]  row in the send buffer for the first slot of each destination, else -1
+    unsigned *pair_meta;  // [N][T][K]  (local expert << 24) | rank of the token among the source's tokens of that expert
+    int *comb_pos;        // [N][T][K]
+    // written by the receiving side of the layout step
+    int *G;               // [N][El]
+    int *expert_off;      // [N][El+1]
+    int *recv_off;        // [N][N+1]
+    int *dst_off;         // [N src][N dst]   row in dst's receive buffer where src's segment starts
+    int *base_x;          // [N][El][N]       first expert-major row of (local expert, source)
+    int *cs_base;         // [N][N][El]       first combine-send row of (source, local expert)
+    int *cs_off;          // [N][N+1]         first combine-send row of each source
+    int *comb_dst_off;    // [N d][N s]       row in s's combine receive buffer where d's reply starts
+    int *plan_ok;         // [N]
+    unsigned *send_meta;  // [N][send_cap][K]
+    unsigned *recv_meta;  // [N][recv_cap][K]
+    char *bufA;           // [N][bufA_rank_bytes]  dispatch send / combine receive
+    char *bufB;           // [N][bufB_rank_bytes]  dispatch receive / combine send
+};
+
+constexpr unsigned kNoEntry = 0xFFFFFFFFu;
+
+// ---------------------------------------------------------------- atomics
+__device__ inline unsigned ld_acquire(const unsigned *p) {
+    return __hip_atomic_load(p, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ inline void add_release(unsigned *p, unsigned v) {
+    __hip_atomic_fetch_add(p, v, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ inline void latch_status(int *status, int bit) {
+    __hip_atomic_fetch_or(status, bit, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Bounded wait of one wavefront: lane i (< n) polls ctr[i] until it has reached
+// `expect` (wrap-safe comparison).  Returns true when all n counters arrived,
+// false when the poll budget ran out.  Every lane of the wave must call it.
+__device__ inline bool wave_wait_counters(const unsigned *ctr, int n, unsigned expect,
+                                          long long spin_limit) {
+    const int lane = threadIdx.x & (kWave - 1);
+    for (int base = 0; base < n; base += kWave) {
+        const int i = base + lane;
+        long long spins = 0;
+        for (;;) {
+            bool ok = true;
+            if (i < n) ok = (int)(ld_acquire(ctr + i) - expect) >= 0;
+            if (__all(ok)) break;
+            if (++spins > spin_limit) return false;
+            __builtin_amdgcn_s_sleep(2);
+        }
+    }
+    return true;
+}
+
+// ---------------------------------------------------------------- scans / search
+__device__ inline int wave_incl_scan(int v) {
+    const int lane = threadIdx.x & (kWave - 1);
+#pragma unroll
+    for (int o = 1; o < kWave; o <<= 1) {
+        int n = __shfl_up(v, o);
+        if (lane >= o) v += n;
+    }
+    return v;
+}
+
+// Exclusive scan over the block (one value per thread, blockDim <= 1024).
+// tmp: LDS int[17].  *total receives the block sum.  Contains barriers.
+__device__ inline int block_excl_scan(int v, int *tmp, int *total) {
+    const int lane = threadIdx.x & (kWave - 1), wid = threadIdx.x / kWave;
+    const int nw = (blockDim.x + kWave - 1) / kWave;
+    int inc = wave_incl_scan(v);
+    __syncthreads();
+    if (lane == kWave - 1) tmp[wid] = inc;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int acc = 0;
+        for (int w = 0; w < nw; ++w) { int t = tmp[w]; tmp[w] = acc; acc += t; }
+        tmp[16] = acc;
+    }
+    __syncthreads();
+    *total = tmp[16];
+    return inc - v + tmp[wid];
+}
+
+// Largest i in [0, n) with off[i] <= x; needs off[0] <= x.  With equal
+// neighbours (empty segments) this is the segment that really contains x.
+__device__ inline int seg_of(const int *off, int n, int x) {
+    int lo = 0, hi = n;
+    while (hi - lo > 1) {
+        int mid = (lo + hi) >> 1;
+        if (off[mid] <= x) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+// ---------------------------------------------------------------- row copies
+// Cooperative copy of nvec 16-byte vectors by NT threads, four loads in flight.
+template <int NT>
+__device__ inline void copy_row(uint4 *__restrict__ dst, const uint4 *__restrict__ src, int nvec,
+                                int tid) {
+    int v = tid;
+    for (; v + 3 * NT < nvec; v += 4 * NT) {
+        uint4 a = src[v], b = src[v + NT], c = src[v + 2 * NT], d = src[v + 3 * NT];
+        dst[v] = a; dst[v + NT] = b; dst[v + 2 * NT] = c; dst[v + 3 * NT] = d;
+    }
+    for (; v < nvec; v += NT) dst[v] = src[v];
+}
+
+// ---------------------------------------------------------------- bf16
+__device__ inline float bf16_lo(unsigned u) { return __uint_as_float(u << 16); }
+__device__ inline float bf16_hi(unsigned u) { return __uint_as_float(u & 0xffff0000u); }
+__device__ inline unsigned f32_to_bf16_bits(float f) {
+    unsigned u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;   // NaN stays a quiet NaN
+    u += 0x7fffu + ((u >> 16) & 1u);                                  // ties to even
+    return u >> 16;
+}
+__device__ inline unsigned pack_bf16x2(float lo, float hi) {
+    return f32_to_bf16_bits(lo) | (f32_to_bf16_bits(hi) << 16);
+}
+
+}  // namespace flmoe

@@ -1,0 +1,453 @@
+// Host side of the flmoe C ABI: argument checks, workspace partition, launches.
+// Every shuffle call only enqueues kernels on the caller's stream.
+#include <hip/hip_runtime.h>
+
+#include <cstdlib>
+#include <cstring>
+#include <new>
+
+#include "../../include/flmoe.h"
+#include "common.h"
+#include "kernels_layout.h"
+#include "kernels_shuffle.h"
+
+using namespace flmoe;
+
+namespace {
+
+enum KernelId {
+    KID_ROUTE_COUNT = 0, KID_ROUTE_PLAN, KID_DISPATCH_PACK, KID_DISPATCH_FABRIC,
+    KID_DISPATCH_UNPACK, KID_COMBINE_PACK, KID_COMBINE_FABRIC, KID_COMBINE_REDUCE,
+    KID_DISPATCH_PACK_E4M3
+};
+const char *kKernelNames[FL_KERNEL_COUNT] = {
+    "route_count_kernel", "route_plan_kernel", "dispatch_pack_kernel", "fabric_copy_kernel(dispatch)",
+    "dispatch_unpack_kernel", "combine_pack_kernel", "fabric_copy_kernel(combine)",
+    "combine_reduce_kernel", "dispatch_pack_e4m3_kernel"};
+
+constexpr int kEventPool = 64;
+constexpr long long kDefaultSpin = 1 << 22;
+
+size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// Walks the workspace; with base == nullptr it only measures.
+struct Carver {
+    char *base; size_t cur = 0;
+    explicit Carver(void *b) : base((char *)b) {}
+    template <class T> T *take(size_t count) {
+        cur = align_up(cur, 256);
+        T *p = base ? (T *)(base + cur) : nullptr;
+        cur += count * sizeof(T);
+        return p;
+    }
+};
+
+int resolve(const fl_moe_config *c, Dims *D) {
+    if (!c) return FL_ERR_INVALID_ARG;
+    if (c->n_ranks < 1 || c->n_ranks > FL_MAX_RANKS) return FL_ERR_INVALID_ARG;
+    if (c->n_experts < c->n_ranks || c->n_experts > FL_MAX_EXPERTS ||
+        c->n_experts % c->n_ranks != 0) return FL_ERR_INVALID_ARG;
+    const int El = c->n_experts / c->n_ranks;
+    if (El > FL_MAX_EXPERTS_PER_RANK) return FL_ERR_INVALID_ARG;
+    if (c->top_k < 1 || c->top_k > FL_MAX_TOPK || c->top_k > c->n_experts) return FL_ERR_INVALID_ARG;
+    if (c->max_tokens < 1 || c->max_tokens >= (1 << 24)) return FL_ERR_INVALID_ARG;
+    if (c->hidden < 8) return FL_ERR_INVALID_ARG;
+    if ((c->hidden * 2) % 16 != 0) return FL_ERR_ALIGNMENT;
+    if (c->dispatch_dtype != FL_DTYPE_BF16 && c->dispatch_dtype != FL_DTYPE_E4M3_BLOCK128)
+        return FL_ERR_INVALID_ARG;
+    if (c->dispatch_dtype == FL_DTYPE_E4M3_BLOCK128 && c->hidden % 128 != 0) return FL_ERR_ALIGNMENT;
+    if (c->expert_align < 1 || c->expert_align > (1 << 16)) return FL_ERR_INVALID_ARG;
+    if (c->flags & ~FL_FLAG_ZERO_PAD) return FL_ERR_INVALID_ARG;
+    if (c->recv_capacity_rows < 0 || c->expert_capacity_rows < 0 || c->spin_limit < 0)
+        return FL_ERR_INVALID_ARG;
+
+    D->N = c->n_ranks; D->E = c->n_experts; D->El = El; D->T = c->max_tokens; D->K = c->top_k;
+    D->H = c->hidden; D->dtype = c->dispatch_dtype; D->align = c->expert_align; D->flags = c->flags;
+    D->route_len = D->E + 2 * D->N + 1;
+    const long long NT = (long long)D->N * D->T;
+    const long long minKEl = D->K < El ? D->K : El;
+    const long long worst_recv = NT;
+    const long long worst_expert = NT * minKEl + (long long)(El - 1) * (D->align - 1);
+    D->recv_cap = c->recv_capacity_rows ? c->recv_capacity_rows : worst_recv;
+    D->expert_cap = c->expert_capacity_rows ? c->expert_capacity_rows : worst_expert;
+    if (D->recv_cap > worst_recv) D->recv_cap = worst_recv;
+    if (D->expert_cap > worst_expert) D->expert_cap = worst_expert;
+    if (D->recv_cap >= (1ll << 31) || D->expert_cap >= (1ll << 31)) return FL_ERR_INVALID_ARG;
+    D->send_cap = (long long)D->T * (D->K < D->N ? D->K : D->N);
+    D->Bx = 2ll * D->H;
+    D->Bc = 2ll * D->H;
+    if (D->dtype == FL_DTYPE_BF16) {
+        D->Bw = D->Bx; D->Be = D->Bx; D->scales_per_row = 0;
+    } else {
+        D->scales_per_row = D->H / 128;
+        D->Be = D->H;
+        D->Bw = D->H + 4ll * D->scales_per_row;
+        if (D->Bw % 16 != 0) return FL_ERR_ALIGNMENT;
+    }
+    const long long a1 = D->send_cap * D->Bw, a2 = (long long)D->T * D->K * D->Bc;
+    const long long b1 = D->recv_cap * D->Bw, b2 = D->expert_cap * D->Bc;
+    D->bufA_rank_bytes = (long long)align_up((size_t)(a1 > a2 ? a1 : a2), 256);
+    D->bufB_rank_bytes = (long long)align_up((size_t)(b1 > b2 ? b1 : b2), 256);
+    D->spin_limit = c->spin_limit ? c->spin_limit : kDefaultSpin;
+    // Largest LDS tile of the counting kernel that stays under 60 KB.
+    int tt = 32;
+    while (tt < 1024 && route_count_lds_bytes(D->E, D->N, tt * 2) <= 60 * 1024) tt *= 2;
+    const int need = (D->T + 31) / 32 * 32;
+    D->TT = need < tt ? need : tt;
+    return FL_OK;
+}
+
+// Returns the number of bytes of the small-table prefix (cleared at create).
+size_t carve(const Dims &D, void *base, Tables *W, size_t *total) {
+    Carver c(base);
+    const size_t N = D.N, E = D.E, El = D.El, T = D.T, K = D.K;
+    W->status = c.take<int>(64);
+    W->epoch_route = c.take<unsigned>(N);
+    W->epoch_disp = c.take<unsigned>(N);
+    W->epoch_comb = c.take<unsigned>(N);
+    W->arrive_route = c.take<unsigned>(N * N);
+    W->arrive_disp = c.take<unsigned>(N * N);
+    W->arrive_comb = c.take<unsigned>(N * N);
+    W->seg_done_disp = c.take<unsigned>(N * N);
+    W->seg_done_comb = c.take<unsigned>(N * N);
+    W->plan_ok = c.take<int>(N);
+    W->routes = c.take<int>(N * N * D.route_len);
+    W->C = c.take<int>(N * E);
+    W->M = c.take<int>(N * N);
+    W->send_off = c.take<int>(N * (N + 1));
+    W->comb_off = c.take<int>(N * (N + 1));
+    W->G = c.take<int>(N * El);
+    W->expert_off = c.take<int>(N * (El + 1));
+    W->recv_off = c.take<int>(N * (N + 1));
+    W->dst_off = c.take<int>(N * N);
+    W->base_x = c.take<int>(N * El * N);
+    W->cs_base = c.take<int>(N * N * El);
+    W->cs_off = c.take<int>(N * (N + 1));
+    W->comb_dst_off = c.take<int>(N * N);
+    const size_t small = align_up(c.cur, 256);
+    W->send_row = c.take<int>(N * T * K);
+    W->pair_meta = c.take<unsigned>(N * T * K);
+    W->comb_pos = c.take<int>(N * T * K);
+    W->send_meta = c.take<unsigned>(N * (size_t)D.send_cap * K);
+    W->recv_meta = c.take<unsigned>(N * (size_t)D.recv_cap * K);
+    W->bufA = c.take<char>(N * (size_t)D.bufA_rank_bytes);
+    W->bufB = c.take<char>(N * (size_t)D.bufB_rank_bytes);
+    *total = align_up(c.cur, 256);
+    return small;
+}
+
+bool aligned16(const void *p) { return ((uintptr_t)p & 15) == 0; }
+
+int rows_per_block(long long row_bytes) {
+    long long rb = 49152 / row_bytes;
+    if (rb < 1) rb = 1;
+    if (rb > kMaxRowsPerBlock) rb = kMaxRowsPerBlock;
+    return (int)rb;
+}
+
+}  // namespace
+
+struct fl_moe_ctx {
+    fl_moe_config cfg;
+    Dims D;
+    Tables W;
+    size_t workspace_bytes;
+    const int32_t *indices = nullptr;
+    const int32_t *num_tokens = nullptr;
+    // profiling
+    int profile = 0;
+    hipEvent_t ev_start[kEventPool], ev_stop[kEventPool];
+    int ev_kernel[kEventPool];
+    int ev_used = 0;
+    double total_ms[FL_KERNEL_COUNT];
+    int64_t launches[FL_KERNEL_COUNT];
+};
+
+namespace {
+
+struct LaunchTimer {
+    fl_moe_ctx *ctx; hipStream_t st; int slot = -1;
+    LaunchTimer(fl_moe_ctx *c, int kid, hipStream_t s) : ctx(c), st(s) {
+        if (c->profile && c->ev_used < kEventPool) {
+            slot = c->ev_used++;
+            c->ev_kernel[slot] = kid;
+            (void)hipEventRecord(c->ev_start[slot], st);
+        }
+    }
+    ~LaunchTimer() { if (slot >= 0) (void)hipEventRecord(ctx->ev_stop[slot], st); }
+};
+
+int check_ranks(const fl_moe_ctx *ctx, int rb, int rc) {
+    if (!ctx) return FL_ERR_INVALID_ARG;
+    if (rb < 0 || rc < 1 || rb + rc > ctx->D.N) return FL_ERR_INVALID_ARG;
+    return FL_OK;
+}
+
+int launch_status() { return hipGetLastError() == hipSuccess ? FL_OK : FL_ERR_HIP; }
+
+}  // namespace
+
+extern "C" {
+
+int fl_moe_query_sizes(const fl_moe_config *cfg, fl_moe_sizes *out) {
+    if (!out) return FL_ERR_INVALID_ARG;
+    Dims D;
+    int rc = resolve(cfg, &D);
+    if (rc != FL_OK) return rc;
+    Tables W;
+    size_t total;
+    carve(D, nullptr, &W, &total);
+    out->workspace_bytes = total;
+    out->recv_capacity_rows = D.recv_cap;
+    out->expert_capacity_rows = D.expert_cap;
+    out->send_capacity_rows = D.send_cap;
+    out->x_row_bytes = D.Bx;
+    out->wire_row_bytes = D.Bw;
+    out->expert_x_row_bytes = D.Be;
+    out->scales_per_row = D.scales_per_row;
+    out->combine_row_bytes = D.Bc;
+    return FL_OK;
+}
+
+int fl_moe_create(const fl_moe_config *cfg, void *workspace, size_t workspace_bytes,
+                  fl_moe_ctx **out) {
+    if (!out || !workspace) return FL_ERR_INVALID_ARG;
+    if (((uintptr_t)workspace & 255) != 0) return FL_ERR_ALIGNMENT;
+    Dims D;
+    int rc = resolve(cfg, &D);
+    if (rc != FL_OK) return rc;
+    Tables W;
+    size_t total;
+    carve(D, nullptr, &W, &total);
+    if (workspace_bytes < total) return FL_ERR_WORKSPACE;
+    fl_moe_ctx *ctx = new (std::nothrow) fl_moe_ctx();
+    if (!ctx) return FL_ERR_INVALID_ARG;
+    ctx->cfg = *cfg;
+    ctx->D = D;
+    const size_t small = carve(D, workspace, &ctx->W, &total);
+    ctx->workspace_bytes = total;
+    if (hipMemset(workspace, 0, small) != hipSuccess || hipDeviceSynchronize() != hipSuccess) {
+        delete ctx;
+        return FL_ERR_HIP;
+    }
+    for (int i = 0; i < kEventPool; ++i) {
+        if (hipEventCreate(&ctx->ev_start[i]) != hipSuccess ||
+            hipEventCreate(&ctx->ev_stop[i]) != hipSuccess) {
+            delete ctx;
+            return FL_ERR_HIP;
+        }
+    }
+    memset(ctx->total_ms, 0, sizeof(ctx->total_ms));
+    memset(ctx->launches, 0, sizeof(ctx->launches));
+    *out = ctx;
+    return FL_OK;
+}
+
+int fl_moe_destroy(fl_moe_ctx *ctx) {
+    if (!ctx) return FL_ERR_INVALID_ARG;
+    for (int i = 0; i < kEventPool; ++i) {
+        (void)hipEventDestroy(ctx->ev_start[i]);
+        (void)hipEventDestroy(ctx->ev_stop[i]);
+    }
+    delete ctx;
+    return FL_OK;
+}
+
+int fl_moe_layout(fl_moe_ctx *ctx, int rb, int rc, const int32_t *indices,
+                  const int32_t *num_tokens, fl_moe_layout_view *view, void *stream) {
+    int e = check_ranks(ctx, rb, rc);
+    if (e != FL_OK) return e;
+    if (!indices || !num_tokens) return FL_ERR_INVALID_ARG;
+    if (((uintptr_t)indices & 3) || ((uintptr_t)num_tokens & 3)) return FL_ERR_ALIGNMENT;
+    hipStream_t st = (hipStream_t)stream;
+    const Dims &D = ctx->D;
+    ctx->indices = indices;
+    ctx->num_tokens = num_tokens;
+    {
+        LaunchTimer t(ctx, KID_ROUTE_COUNT, st);
+        route_count_kernel<<<dim3(rc), dim3(kRouteThreads), route_count_lds_bytes(D.E, D.N, D.TT),
+                             st>>>(D, ctx->W, rb, indices, num_tokens);
+    }
+    {
+        LaunchTimer t(ctx, KID_ROUTE_PLAN, st);
+        route_plan_kernel<<<dim3(rc), dim3(kPlanThreads), (D.E + D.El + 1) * sizeof(int), st>>>(
+            D, ctx->W, rb);
+    }
+    if (view) {
+        const Tables &W = ctx->W;
+        view->counts = W.C; view->dedup_counts = W.M; view->tokens_per_expert = W.G;
+        view->send_off = W.send_off; view->recv_off = W.recv_off; view->expert_off = W.expert_off;
+        view->comb_off = W.comb_off; view->comb_pos = W.comb_pos; view->plan_ok = W.plan_ok;
+    }
+    return launch_status();
+}
+
+int fl_moe_dispatch_send(fl_moe_ctx *ctx, int rb, int rc, const void *x, void *stream) {
+    int e = check_ranks(ctx, rb, rc);
+    if (e != FL_OK) return e;
+    if (!x || !ctx->indices) return FL_ERR_INVALID_ARG;
+    if (!aligned16(x)) return FL_ERR_ALIGNMENT;
+    hipStream_t st = (hipStream_t)stream;
+    const Dims &D = ctx->D;
+    const Tables &W = ctx->W;
+    if (D.dtype != FL_DTYPE_BF16) return FL_ERR_INVALID_ARG;   // e4m3 pack: not built yet
+    {
+        LaunchTimer t(ctx, KID_DISPATCH_PACK, st);
+        dispatch_pack_kernel<<<dim3(D.T, rc), dim3(kCopyThreads), 0, st>>>(
+            D, W, rb, (const char *)x, ctx->indices, ctx->num_tokens);
+    }
+    FabricArgs A;
+    A.src_base = W.bufA; A.src_rank_stride = D.bufA_rank_bytes;
+    A.dst_base = W.bufB; A.dst_rank_stride = D.bufB_rank_bytes;
+    A.seg_off = W.send_off; A.dst_off = W.dst_off;
+    A.src_meta = W.send_meta; A.src_meta_rank_stride = D.send_cap * D.K;
+    A.dst_meta = W.recv_meta; A.dst_meta_rank_stride = D.recv_cap * D.K;
+    A.arrive = W.arrive_disp; A.seg_done = W.seg_done_disp;
+    A.row_bytes = D.Bw; A.rows_per_block = rows_per_block(D.Bw);
+    const unsigned gx = (unsigned)((D.send_cap + A.rows_per_block - 1) / A.rows_per_block);
+    {
+        LaunchTimer t(ctx, KID_DISPATCH_FABRIC, st);
+        fabric_copy_kernel<<<dim3(gx, rc), dim3(kCopyThreads), 0, st>>>(D, W, A, rb);
+    }
+    return launch_status();
+}
+
+int fl_moe_dispatch_recv(fl_moe_ctx *ctx, int rb, int rc, void *expert_x, float *expert_scales,
+                         int32_t *tokens_per_expert, void *stream) {
+    int e = check_ranks(ctx, rb, rc);
+    if (e != FL_OK) return e;
+    const Dims &D = ctx->D;
+    if (!expert_x || !tokens_per_expert) return FL_ERR_INVALID_ARG;
+    if ((D.scales_per_row != 0) != (expert_scales != nullptr)) return FL_ERR_INVALID_ARG;
+    if (!aligned16(expert_x) || ((uintptr_t)expert_scales & 3) || ((uintptr_t)tokens_per_expert & 3))
+        return FL_ERR_ALIGNMENT;
+    hipStream_t st = (hipStream_t)stream;
+    const int rbk = rows_per_block(D.Bw);
+    unsigned gx = (unsigned)((D.recv_cap + rbk - 1) / rbk);
+    if (gx < (unsigned)D.El) gx = D.El;      // the first El-1 blocks also clear padding rows
+    {
+        LaunchTimer t(ctx, KID_DISPATCH_UNPACK, st);
+        dispatch_unpack_kernel<<<dim3(gx, rc), dim3(kCopyThreads), 0, st>>>(
+            D, ctx->W, rb, (char *)expert_x, expert_scales, tokens_per_expert, rbk);
+    }
+    return launch_status();
+}
+
+int fl_moe_combine_send(fl_moe_ctx *ctx, int rb, int rc, const void *expert_y, void *stream) {
+    int e = check_ranks(ctx, rb, rc);
+    if (e != FL_OK) return e;
+    if (!expert_y) return FL_ERR_INVALID_ARG;
+    if (!aligned16(expert_y)) return FL_ERR_ALIGNMENT;
+    hipStream_t st = (hipStream_t)stream;
+    const Dims &D = ctx->D;
+    const Tables &W = ctx->W;
+    const int rbk = rows_per_block(D.Bc);
+    const unsigned gx = (unsigned)((D.expert_cap + rbk - 1) / rbk);
+    {
+        LaunchTimer t(ctx, KID_COMBINE_PACK, st);
+        combine_pack_kernel<<<dim3(gx, rc), dim3(kCopyThreads), 0, st>>>(
+            D, W, rb, (const char *)expert_y, rbk);
+    }
+    FabricArgs A;
+    A.src_base = W.bufB; A.src_rank_stride = D.bufB_rank_bytes;
+    A.dst_base = W.bufA; A.dst_rank_stride = D.bufA_rank_bytes;
+    A.seg_off = W.cs_off; A.dst_off = W.comb_dst_off;
+    A.src_meta = nullptr; A.src_meta_rank_stride = 0;
+    A.dst_meta = nullptr; A.dst_meta_rank_stride = 0;
+    A.arrive = W.arrive_comb; A.seg_done = W.seg_done_comb;
+    A.row_bytes = D.Bc; A.rows_per_block = rbk;
+    {
+        LaunchTimer t(ctx, KID_COMBINE_FABRIC, st);
+        fabric_copy_kernel<<<dim3(gx, rc), dim3(kCopyThreads), 0, st>>>(D, W, A, rb);
+    }
+    return launch_status();
+}
+
+int fl_moe_combine_reduce(fl_moe_ctx *ctx, int rb, int rc, const float *weights, void *out,
+                          void *stream) {
+    int e = check_ranks(ctx, rb, rc);
+    if (e != FL_OK) return e;
+    if (!weights || !out || !ctx->indices) return FL_ERR_INVALID_ARG;
+    if (!aligned16(out) || ((uintptr_t)weights & 3)) return FL_ERR_ALIGNMENT;
+    hipStream_t st = (hipStream_t)stream;
+    const Dims &D = ctx->D;
+    {
+        LaunchTimer t(ctx, KID_COMBINE_REDUCE, st);
+        combine_reduce_kernel<<<dim3(D.T, rc), dim3(kCopyThreads), 0, st>>>(
+            D, ctx->W, rb, weights, (char *)out, ctx->num_tokens);
+    }
+    return launch_status();
+}
+
+int fl_moe_status(fl_moe_ctx *ctx, int32_t *host_out, void *stream) {
+    if (!ctx || !host_out) return FL_ERR_INVALID_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    if (hipMemcpyAsync(host_out, ctx->W.status, sizeof(int32_t), hipMemcpyDeviceToHost, st) !=
+        hipSuccess) return FL_ERR_HIP;
+    if (hipStreamSynchronize(st) != hipSuccess) return FL_ERR_HIP;
+    if (*host_out != 0) {
+        if (hipMemsetAsync(ctx->W.status, 0, sizeof(int32_t), st) != hipSuccess) return FL_ERR_HIP;
+        if (hipStreamSynchronize(st) != hipSuccess) return FL_ERR_HIP;
+    }
+    return FL_OK;
+}
+
+const char *fl_moe_strerror(int code) {
+    switch (code) {
+        case FL_OK: return "ok";
+        case FL_ERR_INVALID_ARG: return "invalid argument";
+        case FL_ERR_ALIGNMENT: return "pointer or size not aligned as required";
+        case FL_ERR_WORKSPACE: return "workspace too small";
+        case FL_ERR_HIP: return "HIP runtime error";
+        default: return "unknown error";
+    }
+}
+
+int fl_moe_debug_views(fl_moe_ctx *ctx, fl_moe_debug_view *out) {
+    if (!ctx || !out) return FL_ERR_INVALID_ARG;
+    const Tables &W = ctx->W;
+    out->buf_a = W.bufA; out->buf_b = W.bufB;
+    out->buf_a_rank_bytes = ctx->D.bufA_rank_bytes; out->buf_b_rank_bytes = ctx->D.bufB_rank_bytes;
+    out->arrive_route = W.arrive_route; out->arrive_disp = W.arrive_disp;
+    out->arrive_comb = W.arrive_comb;
+    out->epoch_route = W.epoch_route; out->epoch_disp = W.epoch_disp; out->epoch_comb = W.epoch_comb;
+    out->status = W.status;
+    return FL_OK;
+}
+
+int fl_moe_profile_enable(fl_moe_ctx *ctx, int on) {
+    if (!ctx) return FL_ERR_INVALID_ARG;
+    ctx->profile = on ? 1 : 0;
+    ctx->ev_used = 0;
+    return FL_OK;
+}
+
+int fl_moe_profile_collect(fl_moe_ctx *ctx, void *stream) {
+    if (!ctx) return FL_ERR_INVALID_ARG;
+    if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return FL_ERR_HIP;
+    for (int i = 0; i < ctx->ev_used; ++i) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, ctx->ev_start[i], ctx->ev_stop[i]) != hipSuccess)
+            return FL_ERR_HIP;
+        ctx->total_ms[ctx->ev_kernel[i]] += ms;
+        ctx->launches[ctx->ev_kernel[i]] += 1;
+    }
+    ctx->ev_used = 0;
+    return FL_OK;
+}
+
+int fl_moe_profile_read(fl_moe_ctx *ctx, double *total_ms, int64_t *launches) {
+    if (!ctx || !total_ms || !launches) return FL_ERR_INVALID_ARG;
+    for (int i = 0; i < FL_KERNEL_COUNT; ++i) {
+        total_ms[i] = ctx->total_ms[i];
+        launches[i] = ctx->launches[i];
+    }
+    return FL_OK;
+}
+
+const char *fl_moe_kernel_name(int kernel_id) {
+    if (kernel_id < 0 || kernel_id >= FL_KERNEL_COUNT) return "";
+    return kKernelNames[kernel_id];
+}
+
+}  // extern "C"

@@ -1,0 +1,78 @@
+"""Driver around the five C calls for tests, smoke and bench: uploads a drawn
+workload, runs one step, applies the stand-in expert between dispatch and
+combine.  The stand-in expert (a per-expert gain) is harness work done with
+torch ops on the GPU; it is not part of the shuffle."""
+import numpy as np
+import torch
+
+from . import flmoe
+from .workloads import Inputs
+
+
+def to_device(inp: Inputs, device="cuda:0"):
+    x = torch.from_numpy(inp.x.view(np.int16)).to(device).view(torch.bfloat16)
+    return {
+        "x": x,
+        "indices": torch.from_numpy(inp.indices).to(device),
+        "weights": torch.from_numpy(inp.weights).to(device),
+        "num_tokens": torch.from_numpy(inp.num_tokens).to(device),
+        "gain": torch.from_numpy(inp.expert_gain).to(device),
+    }
+
+
+def make_shuffle(inp: Inputs, expert_align=1, zero_pad=False, capacity_factor=None,
+                 spin_limit=0, device="cuda:0"):
+    """capacity_factor None = worst-case capacities, else factor x the mean rows per rank."""
+    wl = inp.wl
+    recv_cap = expert_cap = 0
+    if capacity_factor is not None:
+        mean_rows = wl.tokens * wl.top_k
+        expert_cap = int(mean_rows * capacity_factor) + (wl.experts_per_rank - 1) * (expert_align - 1)
+        recv_cap = int(min(mean_rows, wl.n_ranks * wl.tokens) * capacity_factor)
+    return flmoe.MoEShuffle(wl.n_ranks, wl.n_experts, wl.tokens, wl.top_k, wl.hidden,
+                            dispatch_dtype=wl.dispatch_dtype, expert_align=expert_align,
+                            zero_pad=zero_pad, recv_capacity_rows=recv_cap,
+                            expert_capacity_rows=expert_cap, spin_limit=spin_limit, device=device)
+
+
+def row_gain(sh: flmoe.MoEShuffle, gain: torch.Tensor):
+    """Per-row gain [N][cap] of the stand-in expert, from the library's own offsets."""
+    tabs = sh.layout_tables()
+    off = tabs["expert_off"].long()                       # [N][El+1]
+    rows = torch.arange(sh.expert_capacity_rows, device=gain.device)
+    j = (torch.searchsorted(off[:, 1:-1].contiguous(), rows.expand(sh.N, -1).contiguous(),
+                            right=True))                   # local expert of each row
+    e = j + (torch.arange(sh.N, device=gain.device) * sh.El)[:, None]
+    return gain[e]
+
+
+def expert_stage(sh: flmoe.MoEShuffle, gain: torch.Tensor, identity=False):
+    """y = bf16(float(x) * gain[e]) on every row; in place on a copy of expert_x."""
+    if identity:
+        return sh.expert_x
+    g = row_gain(sh, gain)
+    if sh.expert_scales is None:
+        xf = sh.expert_x.float()
+    else:   # e4m3 payload: dequantise first, y = bf16(bf16(float(q) * scale) * gain)
+        q = sh.expert_x.view(torch.float8_e4m3fn).float()
+        sc = sh.expert_scales.repeat_interleave(128, dim=-1)
+        xf = (q * sc).to(torch.bfloat16).float()
+    return (xf * g[..., None]).to(torch.bfloat16)
+
+
+def run_step(sh: flmoe.MoEShuffle, dev, identity=False, ranks=None):
+    sh.layout(dev["indices"], dev["num_tokens"], ranks)
+    sh.dispatch_send(dev["x"], ranks)
+    sh.dispatch_recv(ranks)
+    y = expert_stage(sh, dev["gain"], identity)
+    sh.combine_send(y, ranks)
+    return sh.combine_reduce(dev["weights"], ranks)
+
+
+def run_hot_path(sh: flmoe.MoEShuffle, dev):
+    """The five calls back to back (identity expert: expert_y aliases expert_x)."""
+    sh.layout(dev["indices"], dev["num_tokens"])
+    sh.dispatch_send(dev["x"])
+    sh.dispatch_recv()
+    sh.combine_send(sh.expert_x)
+    return sh.combine_reduce(dev["weights"])

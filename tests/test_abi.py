@@ -1,0 +1,87 @@
+"""Host-side checks of the C ABI: the library loads, exports every symbol that
+include/flmoe.h declares, and its host-only entry points validate arguments.
+No kernel is launched here."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2510_27656_amd import flmoe
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "flmoe.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(fl_moe_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_symbols()
+    assert "fl_moe_layout" in names and "fl_moe_combine_reduce" in names and len(names) >= 12
+    L = flmoe.lib()
+    for n in names:
+        assert hasattr(L, n), n
+    assert sorted(flmoe.EXPORTS) == names
+
+
+def cfg(**kw):
+    base = dict(n_ranks=32, n_experts=256, max_tokens=128, top_k=8, hidden=7168,
+                dispatch_dtype=0, expert_align=1, flags=0, recv_capacity_rows=0,
+                expert_capacity_rows=0, spin_limit=0)
+    base.update(kw)
+    return flmoe.fl_moe_config(**base)
+
+
+def test_query_sizes_decode_shape():
+    s = flmoe.fl_moe_query_sizes(cfg())
+    assert s.x_row_bytes == 14336 and s.wire_row_bytes == 14336 and s.combine_row_bytes == 14336
+    assert s.recv_capacity_rows == 32 * 128
+    assert s.expert_capacity_rows == 32 * 128 * 8
+    assert s.send_capacity_rows == 128 * 8
+    assert s.workspace_bytes % 256 == 0
+    # the two staging buffers dominate: send/combine-receive and receive/combine-send
+    assert s.workspace_bytes >= 32 * (1024 * 14336 + 32768 * 14336)
+    s8 = flmoe.fl_moe_query_sizes(cfg(dispatch_dtype=1))
+    assert s8.wire_row_bytes == 7168 + 4 * 56 and s8.scales_per_row == 56
+    assert s8.expert_x_row_bytes == 7168
+
+
+def test_capacities_are_clamped_and_padding_counted():
+    s = flmoe.fl_moe_query_sizes(cfg(expert_align=16, expert_capacity_rows=0))
+    assert s.expert_capacity_rows == 32 * 128 * 8 + 7 * 15
+    s = flmoe.fl_moe_query_sizes(cfg(recv_capacity_rows=10 ** 9, expert_capacity_rows=2000))
+    assert s.recv_capacity_rows == 32 * 128 and s.expert_capacity_rows == 2000
+
+
+@pytest.mark.parametrize("bad,code", [
+    (dict(n_ranks=0), flmoe.FL_ERR_INVALID_ARG),
+    (dict(n_ranks=65, n_experts=65), flmoe.FL_ERR_INVALID_ARG),
+    (dict(n_experts=250), flmoe.FL_ERR_INVALID_ARG),
+    (dict(top_k=17), flmoe.FL_ERR_INVALID_ARG),
+    (dict(top_k=0), flmoe.FL_ERR_INVALID_ARG),
+    (dict(hidden=100), flmoe.FL_ERR_ALIGNMENT),
+    (dict(hidden=192, dispatch_dtype=1), flmoe.FL_ERR_ALIGNMENT),
+    (dict(dispatch_dtype=7), flmoe.FL_ERR_INVALID_ARG),
+    (dict(expert_align=0), flmoe.FL_ERR_INVALID_ARG),
+    (dict(flags=8), flmoe.FL_ERR_INVALID_ARG),
+    (dict(max_tokens=0), flmoe.FL_ERR_INVALID_ARG),
+])
+def test_query_sizes_rejects_bad_configs(bad, code):
+    with pytest.raises(flmoe.FlMoeError) as ei:
+        flmoe.fl_moe_query_sizes(cfg(**bad))
+    assert ei.value.code == code
+
+
+def test_null_arguments_are_errors_not_crashes():
+    L = flmoe.lib()
+    assert L.fl_moe_query_sizes(None, None) == flmoe.FL_ERR_INVALID_ARG
+    assert L.fl_moe_destroy(None) == flmoe.FL_ERR_INVALID_ARG
+    assert L.fl_moe_layout(None, 0, 1, None, None, None, None) == flmoe.FL_ERR_INVALID_ARG
+    assert L.fl_moe_dispatch_send(None, 0, 1, None, None) == flmoe.FL_ERR_INVALID_ARG
+    assert L.fl_moe_status(None, None, None) == flmoe.FL_ERR_INVALID_ARG
+    assert L.fl_moe_strerror(flmoe.FL_ERR_WORKSPACE) == b"workspace too small"
+    names = [L.fl_moe_kernel_name(i).decode() for i in range(flmoe.FL_KERNEL_COUNT)]
+    assert all(names) and len(set(names)) == flmoe.FL_KERNEL_COUNT

@@ -1,0 +1,309 @@
+"""Parity of the HIP path (through the C ABI) against the CPU oracle, element by
+element, on the same seeded inputs.
+
+Bars: bit-exact for counts, offsets, positions and dispatched rows; combined
+output within 1 bf16 step of the oracle (fp32 fused multiply-add in k order on
+both sides, so bit-equality is expected and its fraction is reported).
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle as orc
+from oracle.reference_step import oracle_step
+from paper_2510_27656_amd import flmoe, harness
+from paper_2510_27656_amd import workloads as wlmod
+
+pytestmark = pytest.mark.gpu
+
+POISON = 0x7FC1          # a bf16 NaN pattern no computation here produces
+
+
+def bits(t):
+    return t.detach().contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+def ulp_distance(a_bits, b_bits):
+    def key(b):
+        b = b.astype(np.int32)
+        return np.where(b & 0x8000, -(b & 0x7fff), b & 0x7fff)
+    return np.abs(key(a_bits) - key(b_bits))
+
+
+def check_tables(sh, ref, N):
+    tabs = {k: v.cpu().numpy() for k, v in sh.layout_tables().items()}
+    assert (tabs["plan_ok"] == 1).all()
+    assert (tabs["C"] == ref.lay.C).all()
+    assert (tabs["M"] == ref.lay.M).all()
+    assert (tabs["G"] == ref.lay.G).all()
+    assert (tabs["send_off"] == ref.lay.send_off).all()
+    assert (tabs["recv_off"] == ref.lay.recv_off).all()
+    assert (tabs["expert_off"] == ref.lay.expert_off).all()
+    assert (tabs["comb_off"] == ref.lay.comb_off).all()
+    return tabs
+
+
+def run_and_compare(inp, align=1, zero_pad=False, capacity_factor=None, ranks_split=False):
+    wl = inp.wl
+    N, T = wl.n_ranks, wl.tokens
+    ref = oracle_step(inp, align, zero_pad=True)
+    dev = harness.to_device(inp)
+    sh = harness.make_shuffle(inp, expert_align=align, zero_pad=zero_pad,
+                              capacity_factor=capacity_factor)
+    try:
+        sh.expert_x.view(torch.int16).fill_(POISON)
+        sh.out.view(torch.int16).fill_(POISON)
+        identity = wl.expert == "identity"
+        if not ranks_split:
+            out = harness.run_step(sh, dev, identity)
+        else:
+            h = N // 2
+            sh.layout(dev["indices"], dev["num_tokens"])
+            for rg in [(h, N - h), (0, h)]:
+                sh.dispatch_send(dev["x"], rg)
+            for rg in [(0, h), (h, N - h)]:
+                sh.dispatch_recv(rg)
+            y = harness.expert_stage(sh, dev["gain"], identity)
+            for rg in [(h, N - h), (0, h)]:
+                sh.combine_send(y, rg)
+            for rg in [(0, h), (h, N - h)]:
+                sh.combine_reduce(dev["weights"], rg)
+            out = sh.out
+        torch.cuda.synchronize()
+        assert sh.status() == 0
+        tabs = check_tables(sh, ref, N)
+        assert (sh.tokens_per_expert.cpu().numpy() == ref.lay.G).all()
+        # combine-receive positions of valid tokens
+        cp = tabs["comb_pos"]
+        for s in range(N):
+            n = inp.num_tokens[s]
+            assert (cp[s, :n] == ref.comb_pos[s, :n]).all()
+        # dispatched rows, bit for bit; padding and unused capacity as specified
+        ex = bits(sh.expert_x[:, :ref.stride])
+        exi = sh.expert_x.view(torch.int16)
+        for d in range(N):
+            rows = ref.expert_rows[d]
+            n = rows.shape[0]
+            if zero_pad:
+                assert (ex[d, :n] == rows).all(), f"rank {d}"
+            else:
+                for j in range(wl.experts_per_rank):
+                    lo = ref.lay.expert_off[d, j]
+                    hi = lo + ref.lay.G[d, j]
+                    assert (ex[d, lo:hi] == rows[lo:hi]).all(), f"rank {d} expert {j}"
+                    if j + 1 < wl.experts_per_rank:
+                        assert (ex[d, hi:ref.lay.expert_off[d, j + 1]] == POISON).all()
+            assert bool((exi[d, n:] == POISON).all()), "rows beyond the layout were written"
+        # combined output
+        ob = bits(out)
+        worst, exact, total = 0, 0, 0
+        for s in range(N):
+            n = inp.num_tokens[s]
+            dist = ulp_distance(ob[s, :n], ref.out[s, :n])
+            if dist.size:
+                worst = max(worst, int(dist.max()))
+                exact += int((dist == 0).sum())
+                total += dist.size
+            assert (ob[s, n:] == POISON).all(), "rows of absent tokens were written"
+        assert worst <= 1, f"max bf16 ulp distance {worst}"
+        print(f"[{wl.name}] combine: max ulp {worst}, bit-exact {exact}/{total}")
+        assert exact == total          # same arithmetic on both sides: expected identical
+        return sh, dev, ob
+    except Exception:
+        sh.close()
+        raise
+
+
+CASES = {
+    "tiny": lambda: wlmod.WORKLOADS["tiny"],
+    "ragged_520": lambda: wlmod.custom("ragged_520", 4, 32, 100, 520, 4, seed=11, ragged=True),
+    "one_expert_per_rank": lambda: wlmod.custom("el1", 8, 8, 33, 264, 5, seed=12, ragged=True),
+    "k_lt_el": lambda: wlmod.custom("el32", 2, 64, 50, 128, 8, seed=13),
+    "single_rank": lambda: wlmod.custom("n1", 1, 16, 77, 256, 4, seed=14),
+    "top1": lambda: wlmod.custom("k1", 4, 16, 64, 256, 1, seed=15),
+    "multi_tile": lambda: wlmod.custom("tiles", 4, 32, 2500, 64, 4, seed=16, ragged=True),
+    "k16": lambda: wlmod.custom("k16", 4, 64, 40, 128, 16, seed=17),
+}
+
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_parity_small(name):
+    inp = wlmod.make_inputs(CASES[name]())
+    sh, _, _ = run_and_compare(inp)
+    sh.close()
+
+
+@pytest.mark.parametrize("align,zero_pad", [(16, True), (16, False), (3, True)])
+def test_parity_with_padding(align, zero_pad):
+    inp = wlmod.make_inputs(CASES["ragged_520"]())
+    sh, _, _ = run_and_compare(inp, align=align, zero_pad=zero_pad)
+    sh.close()
+
+
+def test_rank_subsets_give_the_same_result():
+    inp = wlmod.make_inputs(CASES["ragged_520"]())
+    sh, _, _ = run_and_compare(inp, ranks_split=True)
+    sh.close()
+
+
+def test_repeated_steps_are_deterministic_and_counters_monotone():
+    inp = wlmod.make_inputs(CASES["ragged_520"]())
+    sh, dev, first = run_and_compare(inp)
+    try:
+        for it in range(3):
+            out = harness.run_step(sh, dev, identity=False)
+            torch.cuda.synchronize()
+            assert (bits(out) == first).all()
+        dbg = sh.debug()
+        assert (dbg["epoch_route"].cpu().numpy() == 4).all()
+        assert (dbg["arrive_disp"].cpu().numpy() == 4).all()
+        assert (dbg["arrive_comb"].cpu().numpy() == 4).all()
+        assert sh.status() == 0
+    finally:
+        sh.close()
+
+
+def test_round_trip_identity_returns_input():
+    wl = wlmod.custom("rt", 8, 64, 48, 512, 8, seed=21, expert="identity")
+    inp = wlmod.make_inputs(wl)
+    sh, dev, ob = run_and_compare(inp)
+    try:
+        assert (ob == inp.x).all()
+    finally:
+        sh.close()
+
+
+@pytest.mark.parametrize("name", ["qwen3_skew", "dsv3_decode"])
+def test_parity_named_workloads(name):
+    inp = wlmod.make_inputs(wlmod.WORKLOADS[name])
+    sh, _, _ = run_and_compare(inp)
+    sh.close()
+
+
+def test_decode_with_practical_capacity():
+    """Same decode workload with capacity 1.5x the mean instead of the worst case."""
+    inp = wlmod.make_inputs(wlmod.WORKLOADS["dsv3_decode"])
+    sh, _, _ = run_and_compare(inp, capacity_factor=1.5)
+    sh.close()
+
+
+# ------------------------------------------------------------------ failure handling
+def small_shuffle(spin_limit=0, **kw):
+    inp = wlmod.make_inputs(CASES["ragged_520"]())
+    dev = harness.to_device(inp)
+    sh = harness.make_shuffle(inp, spin_limit=spin_limit, **kw)
+    return inp, dev, sh
+
+
+def test_bad_expert_id_skips_the_step_everywhere():
+    inp, dev, sh = small_shuffle()
+    try:
+        bad = dev["indices"].clone()
+        bad[1, 3, 2] = inp.wl.n_experts + 5
+        sh.expert_x.view(torch.int16).fill_(POISON)
+        sh.out.view(torch.int16).fill_(POISON)
+        sh.layout(bad, dev["num_tokens"])
+        sh.dispatch_send(dev["x"])
+        sh.dispatch_recv()
+        sh.combine_send(sh.expert_x)
+        sh.combine_reduce(dev["weights"])
+        torch.cuda.synchronize()
+        assert sh.status() == flmoe.FL_STATUS_BAD_INDEX
+        assert (sh.layout_tables()["plan_ok"].cpu().numpy() == 0).all()
+        assert (bits(sh.expert_x) == POISON).all() and (bits(sh.out) == POISON).all()
+        # duplicate expert inside a token is rejected too
+        dup = dev["indices"].clone()
+        dup[0, 0, 1] = dup[0, 0, 0]
+        sh.layout(dup, dev["num_tokens"])
+        sh.dispatch_send(dev["x"])
+        torch.cuda.synchronize()
+        assert sh.status() == flmoe.FL_STATUS_BAD_INDEX
+        sh.dispatch_recv()
+        sh.combine_send(sh.expert_x)
+        sh.combine_reduce(dev["weights"])
+        # the next good step works and the counters are still in step
+        ref = oracle_step(inp)
+        out = harness.run_step(sh, dev)
+        torch.cuda.synchronize()
+        assert sh.status() == 0
+        for s in range(inp.wl.n_ranks):
+            n = inp.num_tokens[s]
+            assert (bits(out)[s, :n] == ref.out[s, :n]).all()
+    finally:
+        sh.close()
+
+
+def test_capacity_overflow_is_reported_not_written():
+    inp = wlmod.make_inputs(CASES["ragged_520"]())
+    dev = harness.to_device(inp)
+    sh = harness.make_shuffle(inp, capacity_factor=0.25)
+    try:
+        sh.expert_x.view(torch.int16).fill_(POISON)
+        harness.run_hot_path(sh, dev)
+        torch.cuda.synchronize()
+        assert sh.status() == flmoe.FL_STATUS_CAPACITY
+        assert (bits(sh.expert_x) == POISON).all()
+    finally:
+        sh.close()
+
+
+def test_missing_peers_time_out_instead_of_hanging():
+    """Only half of the ranks take part: the others' counts never arrive, the
+    bounded wait gives up and the step is skipped on the ranks that did run."""
+    inp, dev, sh = small_shuffle(spin_limit=200)
+    try:
+        sh.layout(dev["indices"], dev["num_tokens"], ranks=(0, 2))
+        torch.cuda.synchronize()
+        assert sh.status() == flmoe.FL_STATUS_TIMEOUT
+        assert (sh.layout_tables()["plan_ok"].cpu().numpy()[:2] == 0).all()
+    finally:
+        sh.close()
+
+
+def test_withheld_arrival_counter_times_out_then_recovers():
+    inp, dev, sh = small_shuffle(spin_limit=200)
+    try:
+        ref = oracle_step(inp)
+        sh.layout(dev["indices"], dev["num_tokens"])
+        sh.dispatch_send(dev["x"])
+        torch.cuda.synchronize()
+        arrive = sh.debug()["arrive_disp"]
+        # find a non-empty segment and pretend its notification has not arrived yet
+        M = ref.lay.M
+        s, d = [(s, d) for s in range(4) for d in range(4) if M[s, d] > 0][0]
+        arrive[d, s] -= 1
+        sh.expert_x.view(torch.int16).fill_(POISON)
+        sh.dispatch_recv()
+        torch.cuda.synchronize()
+        assert sh.status() == flmoe.FL_STATUS_TIMEOUT
+        lo, hi = ref.lay.recv_off[d, s], ref.lay.recv_off[d, s + 1]
+        assert hi > lo
+        # deliver the notification: the same call now completes
+        arrive[d, s] += 1
+        sh.dispatch_recv()
+        y = harness.expert_stage(sh, dev["gain"])
+        sh.combine_send(y)
+        out = sh.combine_reduce(dev["weights"])
+        torch.cuda.synchronize()
+        assert sh.status() == 0
+        for r in range(inp.wl.n_ranks):
+            n = inp.num_tokens[r]
+            assert (bits(out)[r, :n] == ref.out[r, :n]).all()
+    finally:
+        sh.close()
+
+
+def test_host_visible_argument_errors():
+    inp, dev, sh = small_shuffle()
+    try:
+        with pytest.raises(flmoe.FlMoeError) as ei:
+            sh.layout(dev["indices"], dev["num_tokens"], ranks=(3, 2))
+        assert ei.value.code == flmoe.FL_ERR_INVALID_ARG
+        with pytest.raises(flmoe.FlMoeError):
+            flmoe.fl_moe_dispatch_send(sh.ctx, 0, 4, None)
+        small = torch.empty(1024, dtype=torch.uint8, device="cuda")
+        with pytest.raises(flmoe.FlMoeError) as ei:
+            flmoe.fl_moe_create(sh.cfg, small)
+        assert ei.value.code == flmoe.FL_ERR_WORKSPACE
+    finally:
+        sh.close()

@@ -47,6 +47,8 @@ def main():
     ap.add_argument("--capacity-factor", type=float, default=1.5,
                     help="per-rank buffer capacity as a multiple of the mean load (0 = worst case)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--unordered", action="store_true",
+                    help="run the fabric with release/acquire counters (FL_FLAG_UNORDERED_FABRIC)")
     ap.add_argument("--profile-steps", type=int, default=30)
     args = ap.parse_args()
     if args.gpus != 1:
@@ -65,7 +67,7 @@ def main():
     cf = args.capacity_factor if args.capacity_factor > 0 else None
     if wl.zipf_alpha > 0:
         cf = None                       # skewed routing: size for the worst case
-    sh = harness.make_shuffle(inp, capacity_factor=cf)
+    sh = harness.make_shuffle(inp, capacity_factor=cf, unordered_fabric=args.unordered)
     ttot, D, P = stats["tokens_total"], stats["dedup_rows"], stats["pairs"]
     per_kernel, bytes_dispatch, bytes_combine = algorithmic_bytes(wl, ttot, D, P, sh.sizes)
     bytes_step = bytes_dispatch + bytes_combine
@@ -142,7 +144,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": wl.name, "ranks_simulated": wl.n_ranks, "experts": wl.n_experts,
                    "tokens_per_rank": wl.tokens, "hidden": wl.hidden, "top_k": wl.top_k,
-                   "dedup_rows": D, "pairs": P, "capacity_factor": cf,
+                   "dedup_rows": D, "pairs": P, "capacity_factor": cf, "fabric": "unordered (release/acquire)" if args.unordered else "stream-ordered",
                    "expert_stage": "identity (expert_y aliases expert_x)"},
         "frac_of_hbm_peak": round(value / HBM_PEAK_GBPS, 4),
         "algorithmic_bytes": {"dispatch": bytes_dispatch, "combine": bytes_combine},

@@ -60,6 +60,15 @@ extern "C" {
 #define FL_DTYPE_E4M3_BLOCK128 1
 
 #define FL_FLAG_ZERO_PAD 1 /* dispatch_recv writes zeros into the padding rows between experts */
+/* Without this flag the caller keeps each send call before the matching receive
+ * call in stream order (one stream, or events between streams); the arrival
+ * counters are then bumped and checked with relaxed atomics and no cache
+ * maintenance.  With it, send and receive kernels may overlap in time (other
+ * streams, other orders): a sender releases its payload before it reports
+ * progress and a receiver acquires after its counters arrived, which is the
+ * ImmCounter contract with no ordering assumed; it costs one L2 write-back or
+ * invalidate per workgroup. */
+#define FL_FLAG_UNORDERED_FABRIC 2
 
 #define FL_MAX_RANKS 64
 #define FL_MAX_EXPERTS 1024

@@ -56,11 +56,32 @@ struct Tables {
 constexpr unsigned kNoEntry = 0xFFFFFFFFu;
 
 // ---------------------------------------------------------------- atomics
-__device__ inline unsigned ld_acquire(const unsigned *p) {
-    return __hip_atomic_load(p, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT);
+// Two ways to run the fabric.  Stream-ordered (FENCED = false): the caller keeps
+// every send kernel before the matching receive kernel in stream order, so the
+// kernel boundary already makes payloads visible; counters are bumped and polled
+// with relaxed atomics and no cache maintenance.  Unordered (FENCED = true):
+// senders and receivers may overlap in time, so a block releases (L2 write-back)
+// once before it reports progress and a receiver acquires (invalidate) once after
+// its counters arrived.  On gfx950 each XCD has its own L2, which is why the
+// fenced form costs a write-back/invalidate per block and is not the default.
+__device__ inline unsigned ld_relaxed(const unsigned *p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-__device__ inline void add_release(unsigned *p, unsigned v) {
-    __hip_atomic_fetch_add(p, v, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+template <bool FENCED>
+__device__ inline unsigned add_counter(unsigned *p, unsigned v) {
+    return FENCED ? __hip_atomic_fetch_add(p, v, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT)
+                  : __hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// Every thread calls this after its last payload store and before the barrier
+// that precedes add_counter<true> by one thread: waits until this wave's stores
+// have been acknowledged, without touching the caches.
+template <bool FENCED>
+__device__ inline void stores_done() {
+    if (FENCED) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+}
+template <bool FENCED>
+__device__ inline void acquire_payload() {
+    if (FENCED) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
 }
 __device__ inline void latch_status(int *status, int bit) {
     __hip_atomic_fetch_or(status, bit, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -77,7 +98,7 @@ __device__ inline bool wave_wait_counters(const unsigned *ctr, int n, unsigned e
         long long spins = 0;
         for (;;) {
             bool ok = true;
-            if (i < n) ok = (int)(ld_acquire(ctr + i) - expect) >= 0;
+            if (i < n) ok = (int)(ld_relaxed(ctr + i) - expect) >= 0;
             if (__all(ok)) break;
             if (++spins > spin_limit) return false;
             __builtin_amdgcn_s_sleep(2);

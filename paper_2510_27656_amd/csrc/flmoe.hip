@@ -57,7 +57,7 @@ int resolve(const fl_moe_config *c, Dims *D) {
         return FL_ERR_INVALID_ARG;
     if (c->dispatch_dtype == FL_DTYPE_E4M3_BLOCK128 && c->hidden % 128 != 0) return FL_ERR_ALIGNMENT;
     if (c->expert_align < 1 || c->expert_align > (1 << 16)) return FL_ERR_INVALID_ARG;
-    if (c->flags & ~FL_FLAG_ZERO_PAD) return FL_ERR_INVALID_ARG;
+    if (c->flags & ~(FL_FLAG_ZERO_PAD | FL_FLAG_UNORDERED_FABRIC)) return FL_ERR_INVALID_ARG;
     if (c->recv_capacity_rows < 0 || c->expert_capacity_rows < 0 || c->spin_limit < 0)
         return FL_ERR_INVALID_ARG;
 
@@ -263,15 +263,20 @@ int fl_moe_layout(fl_moe_ctx *ctx, int rb, int rc, const int32_t *indices,
     const Dims &D = ctx->D;
     ctx->indices = indices;
     ctx->num_tokens = num_tokens;
+    const bool fenced = D.flags & FL_FLAG_UNORDERED_FABRIC;
     {
         LaunchTimer t(ctx, KID_ROUTE_COUNT, st);
-        route_count_kernel<<<dim3(rc), dim3(kRouteThreads), route_count_lds_bytes(D.E, D.N, D.TT),
-                             st>>>(D, ctx->W, rb, indices, num_tokens);
+        const size_t lds = route_count_lds_bytes(D.E, D.N, D.TT);
+        if (fenced) route_count_kernel<true><<<dim3(rc), dim3(kRouteThreads), lds, st>>>(
+            D, ctx->W, rb, indices, num_tokens);
+        else route_count_kernel<false><<<dim3(rc), dim3(kRouteThreads), lds, st>>>(
+            D, ctx->W, rb, indices, num_tokens);
     }
     {
         LaunchTimer t(ctx, KID_ROUTE_PLAN, st);
-        route_plan_kernel<<<dim3(rc), dim3(kPlanThreads), (D.E + D.El + 1) * sizeof(int), st>>>(
-            D, ctx->W, rb);
+        const size_t lds = (D.E + D.El + 1) * sizeof(int);
+        if (fenced) route_plan_kernel<true><<<dim3(rc), dim3(kPlanThreads), lds, st>>>(D, ctx->W, rb);
+        else route_plan_kernel<false><<<dim3(rc), dim3(kPlanThreads), lds, st>>>(D, ctx->W, rb);
     }
     if (view) {
         const Tables &W = ctx->W;
@@ -307,7 +312,10 @@ int fl_moe_dispatch_send(fl_moe_ctx *ctx, int rb, int rc, const void *x, void *s
     const unsigned gx = (unsigned)((D.send_cap + A.rows_per_block - 1) / A.rows_per_block);
     {
         LaunchTimer t(ctx, KID_DISPATCH_FABRIC, st);
-        fabric_copy_kernel<<<dim3(gx, rc), dim3(kCopyThreads), 0, st>>>(D, W, A, rb);
+        if (D.flags & FL_FLAG_UNORDERED_FABRIC)
+            fabric_copy_kernel<true><<<dim3(gx, rc), dim3(kCopyThreads), 0, st>>>(D, W, A, rb);
+        else
+            fabric_copy_kernel<false><<<dim3(gx, rc), dim3(kCopyThreads), 0, st>>>(D, W, A, rb);
     }
     return launch_status();
 }
@@ -327,8 +335,12 @@ int fl_moe_dispatch_recv(fl_moe_ctx *ctx, int rb, int rc, void *expert_x, float 
     if (gx < (unsigned)D.El) gx = D.El;      // the first El-1 blocks also clear padding rows
     {
         LaunchTimer t(ctx, KID_DISPATCH_UNPACK, st);
-        dispatch_unpack_kernel<<<dim3(gx, rc), dim3(kCopyThreads), 0, st>>>(
-            D, ctx->W, rb, (char *)expert_x, expert_scales, tokens_per_expert, rbk);
+        if (D.flags & FL_FLAG_UNORDERED_FABRIC)
+            dispatch_unpack_kernel<true><<<dim3(gx, rc), dim3(kCopyThreads), 0, st>>>(
+                D, ctx->W, rb, (char *)expert_x, expert_scales, tokens_per_expert, rbk);
+        else
+            dispatch_unpack_kernel<false><<<dim3(gx, rc), dim3(kCopyThreads), 0, st>>>(
+                D, ctx->W, rb, (char *)expert_x, expert_scales, tokens_per_expert, rbk);
     }
     return launch_status();
 }
@@ -358,7 +370,10 @@ int fl_moe_combine_send(fl_moe_ctx *ctx, int rb, int rc, const void *expert_y, v
     A.row_bytes = D.Bc; A.rows_per_block = rbk;
     {
         LaunchTimer t(ctx, KID_COMBINE_FABRIC, st);
-        fabric_copy_kernel<<<dim3(gx, rc), dim3(kCopyThreads), 0, st>>>(D, W, A, rb);
+        if (D.flags & FL_FLAG_UNORDERED_FABRIC)
+            fabric_copy_kernel<true><<<dim3(gx, rc), dim3(kCopyThreads), 0, st>>>(D, W, A, rb);
+        else
+            fabric_copy_kernel<false><<<dim3(gx, rc), dim3(kCopyThreads), 0, st>>>(D, W, A, rb);
     }
     return launch_status();
 }
@@ -373,8 +388,12 @@ int fl_moe_combine_reduce(fl_moe_ctx *ctx, int rb, int rc, const float *weights,
     const Dims &D = ctx->D;
     {
         LaunchTimer t(ctx, KID_COMBINE_REDUCE, st);
-        combine_reduce_kernel<<<dim3(D.T, rc), dim3(kCopyThreads), 0, st>>>(
-            D, ctx->W, rb, weights, (char *)out, ctx->num_tokens);
+        if (D.flags & FL_FLAG_UNORDERED_FABRIC)
+            combine_reduce_kernel<true><<<dim3(D.T, rc), dim3(kCopyThreads), 0, st>>>(
+                D, ctx->W, rb, weights, (char *)out, ctx->num_tokens);
+        else
+            combine_reduce_kernel<false><<<dim3(D.T, rc), dim3(kCopyThreads), 0, st>>>(
+                D, ctx->W, rb, weights, (char *)out, ctx->num_tokens);
     }
     return launch_status();
 }

@@ -33,6 +33,7 @@ __host__ __device__ inline size_t route_count_lds_bytes(int E, int N, int TT) {
 // Outputs for rank s: C[s][.], M[s][.], send_off[s][.], comb_off[s][.], per pair
 // send_row / pair_meta / comb_pos; the route record (C | M | comb_off | valid) is
 // pushed into every peer's routes[peer][s] and arrive_route[peer][s] is bumped.
+template <bool FENCED>
 __global__ __launch_bounds__(kRouteThreads) void route_count_kernel(
     Dims D, Tables W, int rank_begin, const int *__restrict__ indices,
     const int *__restrict__ num_tokens) {
@@ -155,9 +156,9 @@ __global__ __launch_bounds__(kRouteThreads) void route_count_kernel(
         else v = valid;
         W.routes[((size_t)peer * N + s) * RL + f] = v;
     }
-    __threadfence();
+    stores_done<FENCED>();
     __syncthreads();
-    if (tid < N) add_release(W.arrive_route + (size_t)tid * N + s, 1u);
+    if (tid < N) add_counter<FENCED>(W.arrive_route + (size_t)tid * N + s, 1u);
     if (tid == 0) W.epoch_route[s] += 1u;
 }
 
@@ -165,6 +166,7 @@ __global__ __launch_bounds__(kRouteThreads) void route_count_kernel(
 // derives every table rank r needs for the step from the records it holds.
 // All ranks see the same records, so all reach the same verdict on validity and
 // capacity: a bad step is skipped by everyone without further communication.
+template <bool FENCED>
 __global__ __launch_bounds__(kPlanThreads) void route_plan_kernel(Dims D, Tables W,
                                                                   int rank_begin) {
     extern __shared__ unsigned lds[];
@@ -183,9 +185,9 @@ __global__ __launch_bounds__(kPlanThreads) void route_plan_kernel(Dims D, Tables
         if (!wave_wait_counters(W.arrive_route + (size_t)r * N, N, expect, D.spin_limit)) {
             if (lane == 0) { flag = 1; latch_status(W.status, FL_STATUS_TIMEOUT); }
         }
+        acquire_payload<FENCED>();
     }
     __syncthreads();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
     if (flag) {
         if (tid == 0) W.plan_ok[r] = 0;
         return;

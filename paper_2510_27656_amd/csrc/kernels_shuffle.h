@@ -83,19 +83,20 @@ struct FabricArgs {
     int rows_per_block;
 };
 
+template <bool FENCED>
 __global__ __launch_bounds__(kCopyThreads) void fabric_copy_kernel(Dims D, Tables W,
                                                                    FabricArgs A, int rank_begin) {
     const int s = rank_begin + blockIdx.y, tid = threadIdx.x, N = D.N;
     __shared__ int off[FL_MAX_RANKS + 1];
     __shared__ int row_dst[kMaxRowsPerBlock];
     if (!W.plan_ok[s]) {                       // step skipped: keep the counters in step
-        if (blockIdx.x == 0 && tid < N) add_release(A.arrive + (size_t)tid * N + s, 1u);
+        if (blockIdx.x == 0 && tid < N) add_counter<FENCED>(A.arrive + (size_t)tid * N + s, 1u);
         return;
     }
     if (tid <= N) off[tid] = A.seg_off[(size_t)s * (N + 1) + tid];
     __syncthreads();
     if (blockIdx.x == 0 && tid < N && off[tid + 1] == off[tid])
-        add_release(A.arrive + (size_t)tid * N + s, 1u);
+        add_counter<FENCED>(A.arrive + (size_t)tid * N + s, 1u);
     const int total = off[N];
     const int i0 = blockIdx.x * A.rows_per_block;
     if (i0 >= total) return;
@@ -121,7 +122,7 @@ __global__ __launch_bounds__(kCopyThreads) void fabric_copy_kernel(Dims D, Table
         copy_row<kCopyThreads>((uint4 *)(dst + (size_t)row_dst[i - i0] * A.row_bytes),
                                (const uint4 *)(src + (size_t)i * A.row_bytes), nvec, tid);
     }
-    __threadfence();
+    stores_done<FENCED>();
     __syncthreads();
     if (tid == 0) {
         for (int dd = seg_of(off, N, i0); dd < N && off[dd] < i1; ++dd) {
@@ -129,11 +130,10 @@ __global__ __launch_bounds__(kCopyThreads) void fabric_copy_kernel(Dims D, Table
             if (hi <= lo) continue;
             const unsigned len = (unsigned)(off[dd + 1] - off[dd]);
             unsigned *done = A.seg_done + (size_t)s * N + dd;
-            const unsigned old = __hip_atomic_fetch_add(done, (unsigned)(hi - lo), __ATOMIC_ACQ_REL,
-                                                        __HIP_MEMORY_SCOPE_AGENT);
+            const unsigned old = add_counter<FENCED>(done, (unsigned)(hi - lo));
             if (old + (unsigned)(hi - lo) == len) {
                 __hip_atomic_store(done, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                add_release(A.arrive + (size_t)dd * N + s, 1u);
+                add_counter<FENCED>(A.arrive + (size_t)dd * N + s, 1u);
             }
         }
     }
@@ -145,6 +145,7 @@ __global__ __launch_bounds__(kCopyThreads) void fabric_copy_kernel(Dims D, Table
 // writes every row once per local expert that wants it, at
 //   base_x[d][local expert][source] + rank carried in the sidecar,
 // which is the (expert, source rank, token) order of the grouped layout.
+template <bool FENCED>
 __global__ __launch_bounds__(kCopyThreads) void dispatch_unpack_kernel(
     Dims D, Tables W, int rank_begin, char *__restrict__ expert_x,
     float *__restrict__ expert_scales, int *__restrict__ tokens_per_expert, int rows_per_block) {
@@ -183,9 +184,9 @@ __global__ __launch_bounds__(kCopyThreads) void dispatch_unpack_kernel(
                                 D.spin_limit)) {
             if (tid == 0) { timed_out = 1; latch_status(W.status, FL_STATUS_TIMEOUT); }
         }
+        acquire_payload<FENCED>();
     }
     __syncthreads();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
     if (timed_out) return;
     if (tid < r1 - r0) {
         const int r = r0 + tid;
@@ -296,6 +297,7 @@ __device__ inline void reduce_row(const char *__restrict__ recv, const int *pos,
     }
 }
 
+template <bool FENCED>
 __global__ __launch_bounds__(kCopyThreads) void combine_reduce_kernel(
     Dims D, Tables W, int rank_begin, const float *__restrict__ weights, char *__restrict__ out,
     const int *__restrict__ num_tokens) {
@@ -310,13 +312,13 @@ __global__ __launch_bounds__(kCopyThreads) void combine_reduce_kernel(
         if (!wave_wait_counters(W.arrive_comb + (size_t)s * N, N, W.epoch_comb[s], D.spin_limit)) {
             if (tid == 0) { timed_out = 1; latch_status(W.status, FL_STATUS_TIMEOUT); }
         }
+        acquire_payload<FENCED>();
     } else if (tid < kWave + K) {
         const int k = tid - kWave;
         pos[k] = W.comb_pos[((size_t)s * D.T + t) * K + k];
         w[k] = weights[((size_t)s * D.T + t) * K + k];
     }
     __syncthreads();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
     if (timed_out) return;
     const char *recv = W.bufA + (size_t)s * D.bufA_rank_bytes;
     uint4 *o = (uint4 *)(out + ((size_t)s * D.T + t) * D.Bc);

@@ -43,13 +43,14 @@ def check_tables(sh, ref, N):
     return tabs
 
 
-def run_and_compare(inp, align=1, zero_pad=False, capacity_factor=None, ranks_split=False):
+def run_and_compare(inp, align=1, zero_pad=False, capacity_factor=None, ranks_split=False,
+                    unordered=False):
     wl = inp.wl
     N, T = wl.n_ranks, wl.tokens
     ref = oracle_step(inp, align, zero_pad=True)
     dev = harness.to_device(inp)
     sh = harness.make_shuffle(inp, expert_align=align, zero_pad=zero_pad,
-                              capacity_factor=capacity_factor)
+                              capacity_factor=capacity_factor, unordered_fabric=unordered)
     try:
         sh.expert_x.view(torch.int16).fill_(POISON)
         sh.out.view(torch.int16).fill_(POISON)
@@ -137,6 +138,14 @@ def test_parity_small(name):
 def test_parity_with_padding(align, zero_pad):
     inp = wlmod.make_inputs(CASES["ragged_520"]())
     sh, _, _ = run_and_compare(inp, align=align, zero_pad=zero_pad)
+    sh.close()
+
+
+@pytest.mark.parametrize("name", ["ragged_520", "multi_tile", "k16"])
+def test_parity_unordered_fabric_mode(name):
+    """Same results when the counters carry release/acquire (FL_FLAG_UNORDERED_FABRIC)."""
+    inp = wlmod.make_inputs(CASES[name]())
+    sh, _, _ = run_and_compare(inp, unordered=True)
     sh.close()
 
 

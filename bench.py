@@ -50,6 +50,9 @@ def main():
     ap.add_argument("--unordered", action="store_true",
                     help="run the fabric with release/acquire counters (FL_FLAG_UNORDERED_FABRIC)")
     ap.add_argument("--profile-steps", type=int, default=30)
+    ap.add_argument("--counters", action="store_true",
+                    help="short run for `rocprofv3 --pmc`: a few steps plus one plain 1 GiB copy "
+                         "of known size to calibrate the byte counters; no timing output")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs the whole simulated expert-parallel group on ONE GPU; "
@@ -74,6 +77,19 @@ def main():
 
     def step():
         harness.run_hot_path(sh, dev)
+
+    if args.counters:
+        for _ in range(3):
+            step()
+        a = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0")
+        b = torch.ones(1 << 30, dtype=torch.uint8, device="cuda:0")
+        flmoe.fl_moe_debug_copy(a, b, 1 << 30)
+        torch.cuda.synchronize()
+        assert sh.status() == 0
+        print(json.dumps({"counters_run": True, "workload": wl.name, "copy_bytes": 1 << 30,
+                          "algorithmic_bytes": per_kernel}))
+        sh.close()
+        return
 
     for _ in range(args.warmup):
         step()
@@ -122,6 +138,28 @@ def main():
                 "traffic": traffic, "algorithmic_bytes": per_kernel[dominant],
                 "avg_us": round(kern_us[dominant], 2)}
 
+    # cold protocol (the paper clears caches between iterations): a 2 GiB copy between
+    # steps evicts the 256 MB last-level cache; per-call medians with HIP events
+    flush_src = torch.ones(1 << 30, dtype=torch.uint8, device="cuda:0")
+    flush_dst = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0")
+    cold = []
+    for i in range(args.profile_steps):
+        flmoe.fl_moe_debug_copy(flush_dst, flush_src, 1 << 30)
+        e = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        e[0].record(); step(); e[1].record()
+        cold.append(e)
+    torch.cuda.synchronize()
+    cold_us = float(np.median([a.elapsed_time(b) for a, b in cold])) * 1e3
+    # copy ceiling of this machine: plain 16-byte copy of 1 GiB (2 GiB of traffic)
+    ce = []
+    for i in range(12):
+        e = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        e[0].record(); flmoe.fl_moe_debug_copy(flush_dst, flush_src, 1 << 30); e[1].record()
+        ce.append(e)
+    torch.cuda.synchronize()
+    copy_gbps = 2 * (1 << 30) / (float(np.median([a.elapsed_time(b) for a, b in ce[2:]])) * 1e-3) / 1e9
+    del flush_src, flush_dst
+
     cpu = None
     if not args.no_cpu_baseline:
         from oracle.reference_step import oracle_step
@@ -149,6 +187,10 @@ def main():
         "frac_of_hbm_peak": round(value / HBM_PEAK_GBPS, 4),
         "algorithmic_bytes": {"dispatch": bytes_dispatch, "combine": bytes_combine},
         "dispatch_us": round(dispatch_us, 1), "combine_us": round(combine_us, 1),
+        "cold_step_us": round(cold_us, 1),
+        "cold_gbps": round(bytes_step / (cold_us * 1e-6) / 1e9, 1),
+        "copy_ceiling_gbps": round(copy_gbps, 1),
+        "frac_of_copy_ceiling": round(value / copy_gbps, 4),
         "call_us": {k: round(v, 1) for k, v in call_us.items()},
         "kernel_us": {k: round(v, 2) for k, v in kern_us.items()},
         "kernel_gbps": {k: round(per_kernel[k] / (kern_us[k] * 1e-6) / 1e9, 1)

@@ -202,6 +202,11 @@ const char *fl_moe_strerror(int code);
 
 int fl_moe_debug_views(fl_moe_ctx *ctx, fl_moe_debug_view *out /*host*/);
 
+/* Diagnostic: plain 16-byte grid-stride device copy of `bytes` bytes (multiple of
+ * 16, both pointers 16-byte aligned).  Used to measure the copy ceiling of the
+ * machine and to calibrate hardware byte counters against a known size. */
+int fl_moe_debug_copy(void *dst, const void *src, size_t bytes, void *stream);
+
 /* Per-kernel timing with HIP events on the caller's stream.  While enabled,
  * every kernel launch of the shuffle calls is bracketed by an event pair;
  * fl_moe_profile_collect synchronises, adds the elapsed times of the launches

@@ -434,6 +434,17 @@ int fl_moe_debug_views(fl_moe_ctx *ctx, fl_moe_debug_view *out) {
     return FL_OK;
 }
 
+int fl_moe_debug_copy(void *dst, const void *src, size_t bytes, void *stream) {
+    if (!dst || !src || bytes == 0 || bytes % 16 != 0) return FL_ERR_INVALID_ARG;
+    if (!aligned16(dst) || !aligned16(src)) return FL_ERR_ALIGNMENT;
+    const size_t nvec = bytes / 16;
+    size_t blocks = (nvec + kCopyThreads * 4 - 1) / (kCopyThreads * 4);
+    if (blocks > 256 * 64) blocks = 256 * 64;
+    plain_copy_kernel<<<dim3((unsigned)blocks), dim3(kCopyThreads), 0, (hipStream_t)stream>>>(
+        (uint4 *)dst, (const uint4 *)src, nvec);
+    return launch_status();
+}
+
 int fl_moe_profile_enable(fl_moe_ctx *ctx, int on) {
     if (!ctx) return FL_ERR_INVALID_ARG;
     ctx->profile = on ? 1 : 0;

@@ -329,4 +329,23 @@ __global__ __launch_bounds__(kCopyThreads) void combine_reduce_kernel(
     else reduce_row<0>(recv, pos, w, K, D.Bc, nvec, o, tid);
 }
 
+// ------------------------------------------------------------------ diagnostic copy
+__global__ __launch_bounds__(kCopyThreads) void plain_copy_kernel(uint4 *__restrict__ dst,
+                                                                  const uint4 *__restrict__ src,
+                                                                  size_t nvec) {
+    const size_t stride = (size_t)gridDim.x * kCopyThreads * 4;
+    for (size_t v = (size_t)blockIdx.x * kCopyThreads * 4 + threadIdx.x; v < nvec; v += stride) {
+        uint4 a, b, c, d;
+        const bool f = v + 3 * kCopyThreads < nvec;
+        a = src[v];
+        if (f) { b = src[v + kCopyThreads]; c = src[v + 2 * kCopyThreads]; d = src[v + 3 * kCopyThreads]; }
+        dst[v] = a;
+        if (f) { dst[v + kCopyThreads] = b; dst[v + 2 * kCopyThreads] = c; dst[v + 3 * kCopyThreads] = d; }
+        else {
+            for (size_t u = v + kCopyThreads; u < nvec && u < v + 4 * kCopyThreads; u += kCopyThreads)
+                dst[u] = src[u];
+        }
+    }
+}
+
 }  // namespace flmoe

@@ -54,7 +54,7 @@ class fl_moe_debug_view(C.Structure):
 EXPORTS = ["fl_moe_query_sizes", "fl_moe_create", "fl_moe_destroy", "fl_moe_layout",
            "fl_moe_dispatch_send", "fl_moe_dispatch_recv", "fl_moe_combine_send",
            "fl_moe_combine_reduce", "fl_moe_status", "fl_moe_strerror", "fl_moe_debug_views",
-           "fl_moe_profile_enable", "fl_moe_profile_collect", "fl_moe_profile_read",
+           "fl_moe_debug_copy", "fl_moe_profile_enable", "fl_moe_profile_collect", "fl_moe_profile_read",
            "fl_moe_kernel_name"]
 
 _lib = None
@@ -81,6 +81,7 @@ def lib():
         L.fl_moe_strerror.argtypes = [i32]
         L.fl_moe_strerror.restype = C.c_char_p
         L.fl_moe_debug_views.argtypes = [vp, C.POINTER(fl_moe_debug_view)]
+        L.fl_moe_debug_copy.argtypes = [vp, vp, C.c_size_t, vp]
         L.fl_moe_profile_enable.argtypes = [vp, i32]
         L.fl_moe_profile_collect.argtypes = [vp, vp]
         L.fl_moe_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i64)]
@@ -174,6 +175,11 @@ def fl_moe_debug_views(ctx) -> fl_moe_debug_view:
     out = fl_moe_debug_view()
     _check(lib().fl_moe_debug_views(ctx, C.byref(out)), "fl_moe_debug_views")
     return out
+
+
+def fl_moe_debug_copy(dst, src, nbytes, stream=None):
+    _check(lib().fl_moe_debug_copy(_ptr(dst), _ptr(src), nbytes, _stream(stream)),
+           "fl_moe_debug_copy")
 
 
 def fl_moe_profile_enable(ctx, on):

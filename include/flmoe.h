@@ -129,12 +129,12 @@ typedef struct fl_moe_debug_view {
     void *buf_b;              /* per rank: dispatch receive buffer / combine send buffer  */
     int64_t buf_a_rank_bytes;
     int64_t buf_b_rank_bytes;
-    uint32_t *arrive_route;   /* [N][N] monotone arrival counters, [destination][source]  */
-    uint32_t *arrive_disp;
-    uint32_t *arrive_comb;
-    uint32_t *epoch_route;    /* [N] number of layout / dispatch_send / combine_send calls */
-    uint32_t *epoch_disp;
-    uint32_t *epoch_comb;
+    uint32_t *arrive_route;   /* [N][N] route records received, [destination][source]      */
+    uint32_t *epoch_route;    /* [N] number of layout calls of each rank                   */
+    uint32_t *arrive_disp;    /* [N][N] monotone payload counters, [destination][source],  */
+    uint32_t *arrive_comb;    /*        in 16-byte units delivered by the fabric           */
+    uint32_t *expect_disp;    /* [N][N] what the receiver expects, from the counts it got  */
+    uint32_t *expect_comb;
     int32_t *status;          /* the device status word                                    */
 } fl_moe_debug_view;
 
@@ -164,8 +164,8 @@ int fl_moe_layout(fl_moe_ctx *ctx, int rank_begin, int rank_count, const int32_t
  * source per peer, then scattered).  x [N][T][H] bf16.  Packs one copy of each
  * token per distinct destination rank (quantising to e4m3 when configured),
  * copies every (source, destination) segment into the destination's receive
- * buffer and bumps arrive_disp[destination][source] once the segment is whole;
- * empty segments still notify. */
+ * buffer and adds what it delivered (in 16-byte units) to
+ * arrive_disp[destination][source]. */
 int fl_moe_dispatch_send(fl_moe_ctx *ctx, int rank_begin, int rank_count, const void *x,
                          void *stream);
 
@@ -181,7 +181,8 @@ int fl_moe_dispatch_recv(fl_moe_ctx *ctx, int rank_begin, int rank_count, void *
 /* Step 4 (section Combine: a single scatter per peer re-using the routing
  * information).  expert_y [N][expert_capacity_rows][H] bf16, same row layout as
  * expert_x.  Packs each peer's rows contiguously, copies them into the peer's
- * combine receive buffer and bumps arrive_comb[peer][this rank]. */
+ * combine receive buffer and adds what it delivered to arrive_comb[peer][this
+ * rank].  Call it once per fl_moe_layout, after fl_moe_dispatch_recv. */
 int fl_moe_combine_send(fl_moe_ctx *ctx, int rank_begin, int rank_count, const void *expert_y,
                         void *stream);
 
@@ -202,8 +203,17 @@ const char *fl_moe_strerror(int code);
 
 int fl_moe_debug_views(fl_moe_ctx *ctx, fl_moe_debug_view *out /*host*/);
 
-/* Diagnostic: plain 16-byte grid-stride device copy of `bytes` bytes (multiple of
- * 16, both pointers 16-byte aligned).  Used to measure the copy ceiling of the
+/* Diagnostic: overrides a launch-shape knob of the copy kernels (results never
+ * change).  knob 0 = rows per workgroup of the unpack / combine-pack kernels
+ * (0 = chosen from the row size, at most 64), knob 1 = row loads issued together
+ * per thread in combine_reduce (0 = all K, at most 8), knob 2 = waves per row in
+ * the fabric kernel (0 = chosen from the row size, else 1..16), knob 3 =
+ * workgroups per token in the pack kernel (0 = chosen from the row size, at
+ * most 16). */
+int fl_moe_debug_tune(fl_moe_ctx *ctx, int knob, int value);
+
+/* Diagnostic: plain linear device copy of `bytes` bytes with 16-byte accesses
+ * (multiple of 16, both pointers 16-byte aligned).  Used to measure the copy ceiling of the
  * machine and to calibrate hardware byte counters against a known size. */
 int fl_moe_debug_copy(void *dst, const void *src, size_t bytes, void *stream);
 

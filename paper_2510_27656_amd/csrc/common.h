@@ -20,14 +20,23 @@ struct Dims {
     long long Bx, Bw, Be, Bc;                   // row bytes: input, wire, expert_x, combine
     long long bufA_rank_bytes, bufB_rank_bytes;
     long long spin_limit;
+    int KM;               // words per sidecar row: K rounded up to a multiple of 4
+    int tune_rows;        // rows per block of the copy kernels (0 = by row size)
+    int tune_reduce;      // loads in flight per thread in the reduce kernel (0 = all K)
+    int tune_waves;       // waves per row in the fabric kernel (0 = by row size)
+    int tune_slices;      // blocks per token in the pack kernel (0 = by row size)
 };
 
 // Device pointers into the caller's workspace.
 struct Tables {
     int *status;
-    unsigned *epoch_route, *epoch_disp, *epoch_comb;          // [N]
-    unsigned *arrive_route, *arrive_disp, *arrive_comb;       // [N dst][N src], monotone
-    unsigned *seg_done_disp, *seg_done_comb;                  // [N src][N dst] rows delivered so far
+    unsigned *epoch_route;                                    // [N] layout calls of each rank
+    unsigned *arrive_route;                                   // [N dst][N src] route records received
+    // Payload counters, monotone, in 16-byte units: arrive_* is bumped by the fabric
+    // as data lands, expect_* by the receiver's own planning kernel from the counts
+    // it was sent, so a receiver waits for arrive >= expect per source.
+    unsigned *arrive_disp, *arrive_comb;                      // [N dst][N src]
+    unsigned *expect_disp, *expect_comb;                      // [N dst][N src]
     int *routes;          // [N receiver][N source][route_len]
     // written by the source side of the layout step
     int *C;               // [N][E]
@@ -42,13 +51,15 @@ struct Tables {
     int *expert_off;      // [N][El+1]
     int *recv_off;        // [N][N+1]
     int *dst_off;         // [N src][N dst]   row in dst's receive buffer where src's segment starts
+    int *comb_dst_off;    // [N d][N s]       row in s's combine receive buffer where d's reply starts
     int *base_x;          // [N][El][N]       first expert-major row of (local expert, source)
     int *cs_base;         // [N][N][El]       first combine-send row of (source, local expert)
     int *cs_off;          // [N][N+1]         first combine-send row of each source
-    int *comb_dst_off;    // [N d][N s]       row in s's combine receive buffer where d's reply starts
     int *plan_ok;         // [N]
-    unsigned *send_meta;  // [N][send_cap][K]
-    unsigned *recv_meta;  // [N][recv_cap][K]
+    unsigned *send_meta;  // [N][send_cap][KM]
+    unsigned *recv_meta;  // [N][recv_cap][KM]
+    int2 *fab_dst_disp;   // [N][send_cap]    (destination rank, row there) of every send row
+    int2 *fab_dst_comb;   // [N][expert_cap]  same for the combine send rows
     char *bufA;           // [N][bufA_rank_bytes]  dispatch send / combine receive
     char *bufB;           // [N][bufB_rank_bytes]  dispatch receive / combine send
 };
@@ -61,20 +72,21 @@ constexpr unsigned kNoEntry = 0xFFFFFFFFu;
 // kernel boundary already makes payloads visible; counters are bumped and polled
 // with relaxed atomics and no cache maintenance.  Unordered (FENCED = true):
 // senders and receivers may overlap in time, so a block releases (L2 write-back)
-// once before it reports progress and a receiver acquires (invalidate) once after
+// before it reports progress and a receiver acquires (invalidate) once after
 // its counters arrived.  On gfx950 each XCD has its own L2, which is why the
 // fenced form costs a write-back/invalidate per block and is not the default.
 __device__ inline unsigned ld_relaxed(const unsigned *p) {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+// The result is never used, so the hardware atomic does not return a value and
+// the wave does not wait for it.
 template <bool FENCED>
-__device__ inline unsigned add_counter(unsigned *p, unsigned v) {
-    return FENCED ? __hip_atomic_fetch_add(p, v, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT)
-                  : __hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+__device__ inline void add_counter(unsigned *p, unsigned v) {
+    if (FENCED) (void)__hip_atomic_fetch_add(p, v, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+    else (void)__hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-// Every thread calls this after its last payload store and before the barrier
-// that precedes add_counter<true> by one thread: waits until this wave's stores
-// have been acknowledged, without touching the caches.
+// Before a block-wide barrier that precedes add_counter<true> by one thread:
+// waits until this wave's stores have been acknowledged, without touching caches.
 template <bool FENCED>
 __device__ inline void stores_done() {
     if (FENCED) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
@@ -88,14 +100,16 @@ __device__ inline void latch_status(int *status, int bit) {
 }
 
 // Bounded wait of one wavefront: lane i (< n) polls ctr[i] until it has reached
-// `expect` (wrap-safe comparison).  Returns true when all n counters arrived,
+// its expectation (wrap-safe comparison; `expect` is either one value for all or,
+// with expect_arr, one per counter).  Returns true when all n counters arrived,
 // false when the poll budget ran out.  Every lane of the wave must call it.
-__device__ inline bool wave_wait_counters(const unsigned *ctr, int n, unsigned expect,
-                                          long long spin_limit) {
+__device__ inline bool wave_wait_counters(const unsigned *ctr, const unsigned *expect_arr,
+                                          unsigned expect, int n, long long spin_limit) {
     const int lane = threadIdx.x & (kWave - 1);
     for (int base = 0; base < n; base += kWave) {
         const int i = base + lane;
         long long spins = 0;
+        if (expect_arr && i < n) expect = expect_arr[i];
         for (;;) {
             bool ok = true;
             if (i < n) ok = (int)(ld_relaxed(ctr + i) - expect) >= 0;
@@ -149,16 +163,52 @@ __device__ inline int seg_of(const int *off, int n, int x) {
 }
 
 // ---------------------------------------------------------------- row copies
-// Cooperative copy of nvec 16-byte vectors by NT threads, four loads in flight.
-template <int NT>
-__device__ inline void copy_row(uint4 *__restrict__ dst, const uint4 *__restrict__ src, int nvec,
-                                int tid) {
-    int v = tid;
-    for (; v + 3 * NT < nvec; v += 4 * NT) {
-        uint4 a = src[v], b = src[v + NT], c = src[v + 2 * NT], d = src[v + 3 * NT];
-        dst[v] = a; dst[v + NT] = b; dst[v + 2 * NT] = c; dst[v + 3 * NT] = d;
+// 16-byte streaming accesses.  The payload of every copy kernel is touched once
+// per kernel, so loads and stores carry the non-temporal hint; on this part a
+// plain copy with these hints and four independent loads per thread in flight
+// measured fastest (more loads in flight per CU than that overruns the L2).
+typedef unsigned v4u __attribute__((ext_vector_type(4)));
+__device__ inline v4u ld_stream(const v4u *p) { return __builtin_nontemporal_load(p); }
+__device__ inline void st_stream(v4u *p, v4u v) { __builtin_nontemporal_store(v, p); }
+
+// A block copies `nrows` rows of `nvec` vectors each; vector v of the chunk lies
+// in row v / nvec.  src_of(row) / dst_of(row) return the row's byte address.
+// All loads of a batch are issued before its stores.
+template <int NT, class SrcFn, class DstFn>
+__device__ inline void copy_rows_flat(int nrows, int nvec, int tid, SrcFn src_of, DstFn dst_of) {
+    if (nrows == 1) {                          // one row per block: addresses are uniform
+        const v4u *s = (const v4u *)src_of(0);
+        v4u *d = (v4u *)dst_of(0);
+        for (int b = tid; b < nvec; b += 4 * NT) {
+            v4u r[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                if (b + i * NT < nvec) r[i] = ld_stream(s + b + i * NT);
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                if (b + i * NT < nvec) st_stream(d + b + i * NT, r[i]);
+        }
+        return;
     }
-    for (; v < nvec; v += NT) dst[v] = src[v];
+    const int total = nrows * nvec;
+    for (int b = tid; b < total; b += 4 * NT) {
+        v4u r[4];
+        int row[4], col[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int v = b + i * NT;
+            if (v < total) {
+                row[i] = v / nvec;
+                col[i] = v - row[i] * nvec;
+                r[i] = ld_stream((const v4u *)src_of(row[i]) + col[i]);
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int v = b + i * NT;
+            if (v < total) st_stream((v4u *)dst_of(row[i]) + col[i], r[i]);
+        }
+    }
 }
 
 // ---------------------------------------------------------------- bf16

@@ -64,6 +64,7 @@ int resolve(const fl_moe_config *c, Dims *D) {
     D->N = c->n_ranks; D->E = c->n_experts; D->El = El; D->T = c->max_tokens; D->K = c->top_k;
     D->H = c->hidden; D->dtype = c->dispatch_dtype; D->align = c->expert_align; D->flags = c->flags;
     D->route_len = D->E + 2 * D->N + 1;
+    D->KM = (D->K + 3) / 4 * 4;
     const long long NT = (long long)D->N * D->T;
     const long long minKEl = D->K < El ? D->K : El;
     const long long worst_recv = NT;
@@ -88,12 +89,18 @@ int resolve(const fl_moe_config *c, Dims *D) {
     const long long b1 = D->recv_cap * D->Bw, b2 = D->expert_cap * D->Bc;
     D->bufA_rank_bytes = (long long)align_up((size_t)(a1 > a2 ? a1 : a2), 256);
     D->bufB_rank_bytes = (long long)align_up((size_t)(b1 > b2 ? b1 : b2), 256);
+    // arrival counters count 16-byte units in 32 bits with a wrap-safe comparison
+    if ((long long)D->T * (D->Bc / 16) >= (1ll << 31)) return FL_ERR_INVALID_ARG;
     D->spin_limit = c->spin_limit ? c->spin_limit : kDefaultSpin;
     // Largest LDS tile of the counting kernel that stays under 60 KB.
     int tt = 32;
     while (tt < 1024 && route_count_lds_bytes(D->E, D->N, tt * 2) <= 60 * 1024) tt *= 2;
     const int need = (D->T + 31) / 32 * 32;
     D->TT = need < tt ? need : tt;
+    D->tune_rows = 0;
+    D->tune_reduce = 0;
+    D->tune_waves = 0;
+    D->tune_slices = 0;
     return FL_OK;
 }
 
@@ -103,13 +110,11 @@ size_t carve(const Dims &D, void *base, Tables *W, size_t *total) {
     const size_t N = D.N, E = D.E, El = D.El, T = D.T, K = D.K;
     W->status = c.take<int>(64);
     W->epoch_route = c.take<unsigned>(N);
-    W->epoch_disp = c.take<unsigned>(N);
-    W->epoch_comb = c.take<unsigned>(N);
     W->arrive_route = c.take<unsigned>(N * N);
     W->arrive_disp = c.take<unsigned>(N * N);
     W->arrive_comb = c.take<unsigned>(N * N);
-    W->seg_done_disp = c.take<unsigned>(N * N);
-    W->seg_done_comb = c.take<unsigned>(N * N);
+    W->expect_disp = c.take<unsigned>(N * N);
+    W->expect_comb = c.take<unsigned>(N * N);
     W->plan_ok = c.take<int>(N);
     W->routes = c.take<int>(N * N * D.route_len);
     W->C = c.take<int>(N * E);
@@ -120,16 +125,18 @@ size_t carve(const Dims &D, void *base, Tables *W, size_t *total) {
     W->expert_off = c.take<int>(N * (El + 1));
     W->recv_off = c.take<int>(N * (N + 1));
     W->dst_off = c.take<int>(N * N);
+    W->comb_dst_off = c.take<int>(N * N);
     W->base_x = c.take<int>(N * El * N);
     W->cs_base = c.take<int>(N * N * El);
     W->cs_off = c.take<int>(N * (N + 1));
-    W->comb_dst_off = c.take<int>(N * N);
     const size_t small = align_up(c.cur, 256);
     W->send_row = c.take<int>(N * T * K);
     W->pair_meta = c.take<unsigned>(N * T * K);
     W->comb_pos = c.take<int>(N * T * K);
-    W->send_meta = c.take<unsigned>(N * (size_t)D.send_cap * K);
-    W->recv_meta = c.take<unsigned>(N * (size_t)D.recv_cap * K);
+    W->send_meta = c.take<unsigned>(N * (size_t)D.send_cap * D.KM);
+    W->recv_meta = c.take<unsigned>(N * (size_t)D.recv_cap * D.KM);
+    W->fab_dst_disp = c.take<int2>(N * (size_t)D.send_cap);
+    W->fab_dst_comb = c.take<int2>(N * (size_t)D.expert_cap);
     W->bufA = c.take<char>(N * (size_t)D.bufA_rank_bytes);
     W->bufB = c.take<char>(N * (size_t)D.bufB_rank_bytes);
     *total = align_up(c.cur, 256);
@@ -138,8 +145,24 @@ size_t carve(const Dims &D, void *base, Tables *W, size_t *total) {
 
 bool aligned16(const void *p) { return ((uintptr_t)p & 15) == 0; }
 
-int rows_per_block(long long row_bytes) {
-    long long rb = 49152 / row_bytes;
+// Waves that share one row in the fabric kernel: enough that a lane has at most
+// a handful of 16-byte vectors.
+int waves_per_row(long long row_bytes, int tune_waves) {
+    if (tune_waves >= 1 && tune_waves <= 16) return tune_waves;
+    const long long nvec = row_bytes / 16;
+    return nvec >= 256 ? 4 : nvec >= 128 ? 2 : 1;
+}
+
+// Blocks that share one token in the pack kernel (each takes a slice of the row).
+int pack_slices(long long row_bytes, int tune_slices) {
+    if (tune_slices > 0) return tune_slices;
+    const long long nvec = row_bytes / 16;
+    long long s = (nvec + kPackThreads - 1) / kPackThreads;   // one vector per thread
+    return (int)(s < 1 ? 1 : s > 16 ? 16 : s);
+}
+
+int rows_per_block(long long row_bytes, int tune_rows) {
+    long long rb = tune_rows > 0 ? tune_rows : 16384 / row_bytes;
     if (rb < 1) rb = 1;
     if (rb > kMaxRowsPerBlock) rb = kMaxRowsPerBlock;
     return (int)rb;
@@ -298,24 +321,26 @@ int fl_moe_dispatch_send(fl_moe_ctx *ctx, int rb, int rc, const void *x, void *s
     if (D.dtype != FL_DTYPE_BF16) return FL_ERR_INVALID_ARG;   // e4m3 pack: not built yet
     {
         LaunchTimer t(ctx, KID_DISPATCH_PACK, st);
-        dispatch_pack_kernel<<<dim3(D.T, rc), dim3(kCopyThreads), 0, st>>>(
-            D, W, rb, (const char *)x, ctx->indices, ctx->num_tokens);
+        const int slices = pack_slices(D.Bx, D.tune_slices);
+        dispatch_pack_kernel<<<dim3((unsigned)D.T * slices, rc), dim3(kPackThreads), 0, st>>>(
+            D, W, rb, (const char *)x, ctx->indices, ctx->num_tokens, slices);
     }
     FabricArgs A;
     A.src_base = W.bufA; A.src_rank_stride = D.bufA_rank_bytes;
     A.dst_base = W.bufB; A.dst_rank_stride = D.bufB_rank_bytes;
-    A.seg_off = W.send_off; A.dst_off = W.dst_off;
-    A.src_meta = W.send_meta; A.src_meta_rank_stride = D.send_cap * D.K;
-    A.dst_meta = W.recv_meta; A.dst_meta_rank_stride = D.recv_cap * D.K;
-    A.arrive = W.arrive_disp; A.seg_done = W.seg_done_disp;
-    A.row_bytes = D.Bw; A.rows_per_block = rows_per_block(D.Bw);
-    const unsigned gx = (unsigned)((D.send_cap + A.rows_per_block - 1) / A.rows_per_block);
+    A.seg_off = W.send_off; A.row_dst = W.fab_dst_disp; A.row_cap = D.send_cap;
+    A.src_meta = W.send_meta; A.src_meta_rank_stride = D.send_cap * D.KM;
+    A.dst_meta = W.recv_meta; A.dst_meta_rank_stride = D.recv_cap * D.KM;
+    A.arrive = W.arrive_disp;
+    A.row_bytes = D.Bw; A.waves_per_row = waves_per_row(D.Bw, D.tune_waves);
+    const int wpb = kCopyThreads / kWave;
+    const unsigned gx = (unsigned)((D.send_cap * A.waves_per_row + wpb - 1) / wpb);
     {
         LaunchTimer t(ctx, KID_DISPATCH_FABRIC, st);
         if (D.flags & FL_FLAG_UNORDERED_FABRIC)
-            fabric_copy_kernel<true><<<dim3(gx, rc), dim3(kCopyThreads), 0, st>>>(D, W, A, rb);
+            fabric_copy_kernel<true, 0><<<dim3(gx, rc), dim3(kCopyThreads), 0, st>>>(D, W, A, rb);
         else
-            fabric_copy_kernel<false><<<dim3(gx, rc), dim3(kCopyThreads), 0, st>>>(D, W, A, rb);
+            fabric_copy_kernel<false, 0><<<dim3(gx, rc), dim3(kCopyThreads), 0, st>>>(D, W, A, rb);
     }
     return launch_status();
 }
@@ -330,7 +355,7 @@ int fl_moe_dispatch_recv(fl_moe_ctx *ctx, int rb, int rc, void *expert_x, float 
     if (!aligned16(expert_x) || ((uintptr_t)expert_scales & 3) || ((uintptr_t)tokens_per_expert & 3))
         return FL_ERR_ALIGNMENT;
     hipStream_t st = (hipStream_t)stream;
-    const int rbk = rows_per_block(D.Bw);
+    const int rbk = rows_per_block(D.Bw, D.tune_rows);
     unsigned gx = (unsigned)((D.recv_cap + rbk - 1) / rbk);
     if (gx < (unsigned)D.El) gx = D.El;      // the first El-1 blocks also clear padding rows
     {
@@ -353,7 +378,7 @@ int fl_moe_combine_send(fl_moe_ctx *ctx, int rb, int rc, const void *expert_y, v
     hipStream_t st = (hipStream_t)stream;
     const Dims &D = ctx->D;
     const Tables &W = ctx->W;
-    const int rbk = rows_per_block(D.Bc);
+    const int rbk = rows_per_block(D.Bc, D.tune_rows);
     const unsigned gx = (unsigned)((D.expert_cap + rbk - 1) / rbk);
     {
         LaunchTimer t(ctx, KID_COMBINE_PACK, st);
@@ -363,17 +388,19 @@ int fl_moe_combine_send(fl_moe_ctx *ctx, int rb, int rc, const void *expert_y, v
     FabricArgs A;
     A.src_base = W.bufB; A.src_rank_stride = D.bufB_rank_bytes;
     A.dst_base = W.bufA; A.dst_rank_stride = D.bufA_rank_bytes;
-    A.seg_off = W.cs_off; A.dst_off = W.comb_dst_off;
+    A.seg_off = W.cs_off; A.row_dst = W.fab_dst_comb; A.row_cap = D.expert_cap;
     A.src_meta = nullptr; A.src_meta_rank_stride = 0;
     A.dst_meta = nullptr; A.dst_meta_rank_stride = 0;
-    A.arrive = W.arrive_comb; A.seg_done = W.seg_done_comb;
-    A.row_bytes = D.Bc; A.rows_per_block = rbk;
+    A.arrive = W.arrive_comb;
+    A.row_bytes = D.Bc; A.waves_per_row = waves_per_row(D.Bc, D.tune_waves);
+    const int wpb = kCopyThreads / kWave;
+    const unsigned gxf = (unsigned)((D.expert_cap * A.waves_per_row + wpb - 1) / wpb);
     {
         LaunchTimer t(ctx, KID_COMBINE_FABRIC, st);
         if (D.flags & FL_FLAG_UNORDERED_FABRIC)
-            fabric_copy_kernel<true><<<dim3(gx, rc), dim3(kCopyThreads), 0, st>>>(D, W, A, rb);
+            fabric_copy_kernel<true, 1><<<dim3(gxf, rc), dim3(kCopyThreads), 0, st>>>(D, W, A, rb);
         else
-            fabric_copy_kernel<false><<<dim3(gx, rc), dim3(kCopyThreads), 0, st>>>(D, W, A, rb);
+            fabric_copy_kernel<false, 1><<<dim3(gxf, rc), dim3(kCopyThreads), 0, st>>>(D, W, A, rb);
     }
     return launch_status();
 }
@@ -388,11 +415,14 @@ int fl_moe_combine_reduce(fl_moe_ctx *ctx, int rb, int rc, const float *weights,
     const Dims &D = ctx->D;
     {
         LaunchTimer t(ctx, KID_COMBINE_REDUCE, st);
+        int nt = (int)((D.Bc / 16 + kWave - 1) / kWave * kWave);
+        if (nt > kReduceMaxThreads) nt = kReduceMaxThreads;
+        if (nt < 2 * kWave) nt = 2 * kWave;      // wave 0 waits, wave 1 fetches positions and weights
         if (D.flags & FL_FLAG_UNORDERED_FABRIC)
-            combine_reduce_kernel<true><<<dim3(D.T, rc), dim3(kCopyThreads), 0, st>>>(
+            combine_reduce_kernel<true><<<dim3(D.T, rc), dim3(nt), 0, st>>>(
                 D, ctx->W, rb, weights, (char *)out, ctx->num_tokens);
         else
-            combine_reduce_kernel<false><<<dim3(D.T, rc), dim3(kCopyThreads), 0, st>>>(
+            combine_reduce_kernel<false><<<dim3(D.T, rc), dim3(nt), 0, st>>>(
                 D, ctx->W, rb, weights, (char *)out, ctx->num_tokens);
     }
     return launch_status();
@@ -429,8 +459,20 @@ int fl_moe_debug_views(fl_moe_ctx *ctx, fl_moe_debug_view *out) {
     out->buf_a_rank_bytes = ctx->D.bufA_rank_bytes; out->buf_b_rank_bytes = ctx->D.bufB_rank_bytes;
     out->arrive_route = W.arrive_route; out->arrive_disp = W.arrive_disp;
     out->arrive_comb = W.arrive_comb;
-    out->epoch_route = W.epoch_route; out->epoch_disp = W.epoch_disp; out->epoch_comb = W.epoch_comb;
+    out->epoch_route = W.epoch_route; out->expect_disp = W.expect_disp; out->expect_comb = W.expect_comb;
     out->status = W.status;
+    return FL_OK;
+}
+
+int fl_moe_debug_tune(fl_moe_ctx *ctx, int knob, int value) {
+    if (!ctx || value < 0) return FL_ERR_INVALID_ARG;
+    switch (knob) {
+        case 0: if (value > kMaxRowsPerBlock) return FL_ERR_INVALID_ARG; ctx->D.tune_rows = value; break;
+        case 2: ctx->D.tune_waves = value; break;
+        case 3: if (value > 16) return FL_ERR_INVALID_ARG; ctx->D.tune_slices = value; break;
+        case 1: if (value > 8) return FL_ERR_INVALID_ARG; ctx->D.tune_reduce = value; break;
+        default: return FL_ERR_INVALID_ARG;
+    }
     return FL_OK;
 }
 
@@ -438,10 +480,10 @@ int fl_moe_debug_copy(void *dst, const void *src, size_t bytes, void *stream) {
     if (!dst || !src || bytes == 0 || bytes % 16 != 0) return FL_ERR_INVALID_ARG;
     if (!aligned16(dst) || !aligned16(src)) return FL_ERR_ALIGNMENT;
     const size_t nvec = bytes / 16;
-    size_t blocks = (nvec + kCopyThreads * 4 - 1) / (kCopyThreads * 4);
-    if (blocks > 256 * 64) blocks = 256 * 64;
+    const size_t blocks = (nvec + kCopyThreads * 4 - 1) / (kCopyThreads * 4);
+    if (blocks >= (1ull << 31)) return FL_ERR_INVALID_ARG;
     plain_copy_kernel<<<dim3((unsigned)blocks), dim3(kCopyThreads), 0, (hipStream_t)stream>>>(
-        (uint4 *)dst, (const uint4 *)src, nvec);
+        (v4u *)dst, (const v4u *)src, nvec);
     return launch_status();
 }
 

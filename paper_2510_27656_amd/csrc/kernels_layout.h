@@ -182,7 +182,7 @@ __global__ __launch_bounds__(kPlanThreads) void route_plan_kernel(Dims D, Tables
     __syncthreads();
     if (wid == 0) {
         const unsigned expect = W.epoch_route[r];
-        if (!wave_wait_counters(W.arrive_route + (size_t)r * N, N, expect, D.spin_limit)) {
+        if (!wave_wait_counters(W.arrive_route + (size_t)r * N, nullptr, expect, N, D.spin_limit)) {
             if (lane == 0) { flag = 1; latch_status(W.status, FL_STATUS_TIMEOUT); }
         }
         acquire_payload<FENCED>();
@@ -212,10 +212,12 @@ __global__ __launch_bounds__(kPlanThreads) void route_plan_kernel(Dims D, Tables
     __syncthreads();
 
     int over = 0;
+    unsigned exp_units = 0;       // wave 0: lane = source; wave 1: lane = peer answering in combine
     if (wid == 0) {
         // lane = source s: receive offsets, combine-send offsets of rank r
         const int s = lane;
         const int m = s < N ? rt[(size_t)s * RL + E + r] : 0;
+        exp_units = (unsigned)m * (unsigned)(D.Bw / 16);
         int inc = wave_incl_scan(m);
         if (s < N) W.recv_off[(size_t)r * (N + 1) + s] = inc - m;
         if (s == N - 1) W.recv_off[(size_t)r * (N + 1) + N] = inc;
@@ -234,17 +236,20 @@ __global__ __launch_bounds__(kPlanThreads) void route_plan_kernel(Dims D, Tables
         }
         if (s == N - 1) W.cs_off[(size_t)r * (N + 1) + N] = inc;
     } else if (wid == 1) {
-        // lane = destination d: capacity verdicts for every rank, send targets of rank r
+        // lane = rank d: capacity verdict for every rank, size of d's reply to rank r
         const int d = lane;
         if (d < N) {
             long long recv_rows = 0;
-            int before_me = 0;
+            int before_me = 0;                  // rows of lower ranks ahead of r's segment at d
             for (int s = 0; s < N; ++s) {
                 const int m = rt[(size_t)s * RL + E + d];
                 if (s < r) before_me += m;
                 recv_rows += m;
             }
             W.dst_off[(size_t)r * N + d] = before_me;
+            int mine = 0;                       // pairs of rank r served by rank d: its reply
+            for (int j = 0; j < El; ++j) mine += rt[(size_t)r * RL + d * El + j];
+            exp_units = (unsigned)mine * (unsigned)(D.Bc / 16);
             long long p = 0;
             for (int j = 0; j < El; ++j) {
                 const int g = G_all[d * El + j];
@@ -263,6 +268,8 @@ __global__ __launch_bounds__(kPlanThreads) void route_plan_kernel(Dims D, Tables
     for (int j = tid; j <= El; j += kPlanThreads) W.expert_off[(size_t)r * (El + 1) + j] = eoff[j];
     for (int i = tid; i < El * N; i += kPlanThreads)
         W.base_x[(size_t)r * El * N + i] += eoff[i / N];
+    if (wid == 0 && lane < N) W.expect_disp[(size_t)r * N + lane] += exp_units;
+    if (wid == 1 && lane < N) W.expect_comb[(size_t)r * N + lane] += exp_units;
     if (tid == 0) W.plan_ok[r] = 1;
 }
 

@@ -12,131 +12,129 @@
 namespace flmoe {
 
 constexpr int kCopyThreads = 256;
+constexpr int kPackThreads = 128;
 constexpr int kMaxRowsPerBlock = 64;
 
 // ------------------------------------------------------------------ dispatch: pack
-// One block per token (s, t): the row is read once and written once per
+// `slices` blocks per token (s, t), each taking a slice of the row (so a thread
+// usually has a single vector): the slice is read once and written once per
 // distinct destination rank, at send_off[s][d] + (rank of t among s's tokens
 // bound for d).  Each copy carries a sidecar of K words naming, for every expert
 // of the token that lives on d, the local expert and the token's rank among s's
 // tokens of that expert; the receiver turns that into an expert-major row.
-__global__ __launch_bounds__(kCopyThreads) void dispatch_pack_kernel(
+__global__ __launch_bounds__(kPackThreads) void dispatch_pack_kernel(
     Dims D, Tables W, int rank_begin, const char *__restrict__ x,
-    const int *__restrict__ indices, const int *__restrict__ num_tokens) {
-    const int s = rank_begin + blockIdx.y, t = blockIdx.x, tid = threadIdx.x;
+    const int *__restrict__ indices, const int *__restrict__ num_tokens, int slices) {
+    const int s = rank_begin + blockIdx.y, t = blockIdx.x / slices, slice = blockIdx.x % slices;
+    const int tid = threadIdx.x;
     const int K = D.K, El = D.El;
-    if (t == 0 && tid == 0) W.epoch_disp[s] += 1u;
     if (!W.plan_ok[s] || t >= num_tokens[s]) return;
-    __shared__ int dst_row[FL_MAX_TOPK];
-    __shared__ int ndst;
+    __shared__ int s_row[FL_MAX_TOPK];
+    __shared__ int s_dst[FL_MAX_TOPK];
+    __shared__ unsigned s_meta[FL_MAX_TOPK];
     const size_t pair0 = ((size_t)s * D.T + t) * K;
-    if (tid == 0) {
-        int n = 0;
-        for (int k = 0; k < K; ++k) {
-            const int r = W.send_row[pair0 + k];
-            if (r >= 0) dst_row[n++] = r;
-        }
-        ndst = n;
-    }
-    if (tid < K) {
-        const int r = W.send_row[pair0 + tid];
-        if (r >= 0) {
-            const int d = indices[pair0 + tid] / El;
-            unsigned *meta = W.send_meta + ((size_t)s * D.send_cap + r) * K;
-            int m = 0;
-            for (int k = 0; k < K; ++k)
-                if (indices[pair0 + k] / El == d) meta[m++] = W.pair_meta[pair0 + k];
-            for (; m < K; ++m) meta[m] = kNoEntry;
-        }
+    int my_row = -1, my_d = 0, delta = 0;
+    if (tid < K) {                             // independent loads first, then one dependent level
+        my_row = W.send_row[pair0 + tid];
+        my_d = indices[pair0 + tid] / El;
+        s_meta[tid] = W.pair_meta[pair0 + tid];
+        s_row[tid] = my_row;
+        s_dst[tid] = my_d;
+        if (my_row >= 0)                       // this copy's row in d's buffer minus its row here
+            delta = W.dst_off[(size_t)s * D.N + my_d] - W.send_off[(size_t)s * (D.N + 1) + my_d];
     }
     __syncthreads();
-    const int n = ndst;
+    if (slice == 0 && tid < K && my_row >= 0) {   // sidecar and fabric target of this copy
+        unsigned *meta = W.send_meta + ((size_t)s * D.send_cap + my_row) * D.KM;
+        int m = 0;
+        for (int k = 0; k < K; ++k)
+            if (s_dst[k] == my_d) meta[m++] = s_meta[k];
+        for (; m < D.KM; ++m) meta[m] = kNoEntry;
+        W.fab_dst_disp[(size_t)s * D.send_cap + my_row] = make_int2(my_d, my_row + delta);
+    }
     const int nvec = (int)(D.Bx / 16);
-    const uint4 *src = (const uint4 *)(x + ((size_t)s * D.T + t) * D.Bx);
+    const int per = (nvec + slices - 1) / slices;          // vectors of this slice: [v0, v1)
+    const int v0 = slice * per, v1 = min(v0 + per, nvec);
+    const v4u *src = (const v4u *)(x + ((size_t)s * D.T + t) * D.Bx);
     char *sendbuf = W.bufA + (size_t)s * D.bufA_rank_bytes;
-    for (int v = tid; v < nvec; v += kCopyThreads) {
-        const uint4 val = src[v];
-        for (int i = 0; i < n; ++i)
-            ((uint4 *)(sendbuf + (size_t)dst_row[i] * D.Bw))[v] = val;
+    for (int b = v0 + tid; b < v1; b += 4 * kPackThreads) {
+        v4u r[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            if (b + i * kPackThreads < v1) r[i] = ld_stream(src + b + i * kPackThreads);
+        for (int k = 0; k < K; ++k) {
+            const int row = s_row[k];          // uniform: one copy per distinct destination
+            if (row < 0) continue;
+            v4u *dst = (v4u *)(sendbuf + (size_t)row * D.Bw);
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                if (b + i * kPackThreads < v1) st_stream(dst + b + i * kPackThreads, r[i]);
+        }
     }
 }
 
 // ------------------------------------------------------------------ fabric copy
-// The stand-in for the NIC scatter: for every (source, destination) pair one
-// contiguous segment of the source's send buffer is copied into the range of
-// the destination's receive buffer that the exchanged counts reserved for it.
-// Blocks copy chunks of rows; a per-segment progress count finds the chunk that
-// completes a segment, and only then is arrive[destination][source] bumped
-// (release), so the counter says "this payload is fully delivered" and nothing
-// is assumed about the order in which chunks or segments land.  Empty segments
-// notify too, so every receiver expects exactly one bump per source per step.
+// The stand-in for the NIC scatter: every row of a source's send buffer is
+// copied into the row of the destination's receive buffer that the exchanged
+// counts reserved for it (the target of each row was recorded when the row was
+// packed, so a wave needs one small load before its payload loads; a version
+// that searched the offset tables per wave measured 25 % slower).  Waves work on
+// their own: a row is shared by `waves_per_row` waves, each copies its slice
+// with four loads in flight, then adds the number of 16-byte units it delivered
+// to arrive[destination][source] with an atomic whose result nobody waits for.
+// No barrier, no shared memory, no ticket: the counters only ever say "this much
+// of source s's payload has landed", in whatever order waves finish, and a
+// receiver compares them with what the counts told it to expect.
 struct FabricArgs {
     const char *src_base; long long src_rank_stride;
     char *dst_base;       long long dst_rank_stride;
-    const int *seg_off;   // [N][N+1] segment starts in the source buffer
-    const int *dst_off;   // [N src][N dst] first row in the destination buffer
+    const int *seg_off;   // [N][N+1] segment starts in the source buffer; [N] = rows in use
+    const int2 *row_dst;  // [N][row_cap] (destination rank, row in its buffer) of every source row
+    long long row_cap;
     const unsigned *src_meta; long long src_meta_rank_stride;   // in words; may be null
     unsigned *dst_meta;       long long dst_meta_rank_stride;
     unsigned *arrive;     // [N dst][N src]
-    unsigned *seg_done;   // [N src][N dst]
     long long row_bytes;
-    int rows_per_block;
+    int waves_per_row;    // 1..16
 };
 
-template <bool FENCED>
+template <bool FENCED, int PHASE>   // PHASE only names the launch: 0 dispatch, 1 combine
 __global__ __launch_bounds__(kCopyThreads) void fabric_copy_kernel(Dims D, Tables W,
                                                                    FabricArgs A, int rank_begin) {
-    const int s = rank_begin + blockIdx.y, tid = threadIdx.x, N = D.N;
-    __shared__ int off[FL_MAX_RANKS + 1];
-    __shared__ int row_dst[kMaxRowsPerBlock];
-    if (!W.plan_ok[s]) {                       // step skipped: keep the counters in step
-        if (blockIdx.x == 0 && tid < N) add_counter<FENCED>(A.arrive + (size_t)tid * N + s, 1u);
-        return;
-    }
-    if (tid <= N) off[tid] = A.seg_off[(size_t)s * (N + 1) + tid];
-    __syncthreads();
-    if (blockIdx.x == 0 && tid < N && off[tid + 1] == off[tid])
-        add_counter<FENCED>(A.arrive + (size_t)tid * N + s, 1u);
-    const int total = off[N];
-    const int i0 = blockIdx.x * A.rows_per_block;
-    if (i0 >= total) return;
-    const int i1 = min(i0 + A.rows_per_block, total);
-    if (tid < i1 - i0) {
-        const int i = i0 + tid;
-        const int d = seg_of(off, N, i);
-        const int dr = A.dst_off[(size_t)s * N + d] + (i - off[d]);
-        row_dst[tid] = dr;
-        if (A.src_meta) {
-            const unsigned *ms = A.src_meta + (size_t)s * A.src_meta_rank_stride + (size_t)i * D.K;
-            unsigned *md = A.dst_meta + (size_t)d * A.dst_meta_rank_stride + (size_t)dr * D.K;
-            for (int k = 0; k < D.K; ++k) md[k] = ms[k];
-        }
-    }
-    __syncthreads();
+    const int s = rank_begin + blockIdx.y, N = D.N;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = blockIdx.x * (kCopyThreads / kWave) + threadIdx.x / kWave;   // within rank s
+    const int G = A.waves_per_row;
+    const int i = wave / G, sub = wave % G;
+    if (i >= A.row_cap) return;
+    // three independent loads, then the payload
+    const int ok = W.plan_ok[s];
+    const int total = A.seg_off[(size_t)s * (N + 1) + N];
+    const int2 t = A.row_dst[(size_t)s * A.row_cap + i];
+    if (!ok || i >= total) return;             // step skipped or row unused: nothing sent
     const int nvec = (int)(A.row_bytes / 16);
-    const char *src = A.src_base + (size_t)s * A.src_rank_stride;
-    int d = seg_of(off, N, i0);
-    for (int i = i0; i < i1; ++i) {
-        while (off[d + 1] <= i) ++d;
-        char *dst = A.dst_base + (size_t)d * A.dst_rank_stride;
-        copy_row<kCopyThreads>((uint4 *)(dst + (size_t)row_dst[i - i0] * A.row_bytes),
-                               (const uint4 *)(src + (size_t)i * A.row_bytes), nvec, tid);
+    const v4u *src = (const v4u *)(A.src_base + (size_t)s * A.src_rank_stride + (size_t)i * A.row_bytes);
+    v4u *dst = (v4u *)(A.dst_base + (size_t)t.x * A.dst_rank_stride + (size_t)t.y * A.row_bytes);
+    const int step = G * kWave;
+    for (int b = sub * kWave + lane; b < nvec; b += 4 * step) {
+        v4u v[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if (b + j * step < nvec) v[j] = ld_stream(src + b + j * step);
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if (b + j * step < nvec) st_stream(dst + b + j * step, v[j]);
     }
-    stores_done<FENCED>();
-    __syncthreads();
-    if (tid == 0) {
-        for (int dd = seg_of(off, N, i0); dd < N && off[dd] < i1; ++dd) {
-            const int lo = max(off[dd], i0), hi = min(off[dd + 1], i1);
-            if (hi <= lo) continue;
-            const unsigned len = (unsigned)(off[dd + 1] - off[dd]);
-            unsigned *done = A.seg_done + (size_t)s * N + dd;
-            const unsigned old = add_counter<FENCED>(done, (unsigned)(hi - lo));
-            if (old + (unsigned)(hi - lo) == len) {
-                __hip_atomic_store(done, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                add_counter<FENCED>(A.arrive + (size_t)dd * N + s, 1u);
-            }
-        }
+    if (A.src_meta && sub == 0) {              // the sidecar travels with the row
+        const int mv = D.KM / 4;
+        const v4u *ms = (const v4u *)(A.src_meta + (size_t)s * A.src_meta_rank_stride) + (size_t)i * mv;
+        v4u *md = (v4u *)(A.dst_meta + (size_t)t.x * A.dst_meta_rank_stride) + (size_t)t.y * mv;
+        if (lane < mv) md[lane] = ms[lane];
     }
+    // units this wave delivered: vectors v < nvec with (v / 64) % G == sub
+    const int full = nvec / step, rem = nvec - full * step;
+    const int mine = full * kWave + min(max(rem - sub * kWave, 0), kWave);
+    if (lane == 0 && mine > 0) add_counter<FENCED>(A.arrive + (size_t)t.x * N + s, (unsigned)mine);
 }
 
 // ------------------------------------------------------------------ dispatch: unpack
@@ -180,8 +178,8 @@ __global__ __launch_bounds__(kCopyThreads) void dispatch_unpack_kernel(
     const int r1 = min(r0 + rows_per_block, total);
     const int s0 = seg_of(off, N, r0), s1 = seg_of(off, N, r1 - 1);
     if (tid < kWave) {
-        if (!wave_wait_counters(W.arrive_disp + (size_t)d * N + s0, s1 - s0 + 1, W.epoch_disp[d],
-                                D.spin_limit)) {
+        if (!wave_wait_counters(W.arrive_disp + (size_t)d * N + s0,
+                                W.expect_disp + (size_t)d * N + s0, 0u, s1 - s0 + 1, D.spin_limit)) {
             if (tid == 0) { timed_out = 1; latch_status(W.status, FL_STATUS_TIMEOUT); }
         }
         acquire_payload<FENCED>();
@@ -191,7 +189,7 @@ __global__ __launch_bounds__(kCopyThreads) void dispatch_unpack_kernel(
     if (tid < r1 - r0) {
         const int r = r0 + tid;
         const int s = seg_of(off, N, r);
-        const unsigned *meta = W.recv_meta + ((size_t)d * D.recv_cap + r) * K;
+        const unsigned *meta = W.recv_meta + ((size_t)d * D.recv_cap + r) * D.KM;
         int n = 0;
         for (int k = 0; k < K; ++k) {
             const unsigned m = meta[k];
@@ -204,15 +202,35 @@ __global__ __launch_bounds__(kCopyThreads) void dispatch_unpack_kernel(
     __syncthreads();
     const char *recv = W.bufB + (size_t)d * D.bufB_rank_bytes;
     const int nvec = (int)(D.Be / 16);
-    for (int r = r0; r < r1; ++r) {
-        const uint4 *src = (const uint4 *)(recv + (size_t)r * D.Bw);
+    {
+        const int total = (r1 - r0) * nvec;
+        for (int b = tid; b < total; b += 4 * kCopyThreads) {
+            v4u val[4];
+            int row[4], col[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int v = b + i * kCopyThreads;
+                if (v < total) {
+                    row[i] = v / nvec;
+                    col[i] = v - row[i] * nvec;
+                    val[i] = ld_stream((const v4u *)(recv + (size_t)(r0 + row[i]) * D.Bw) + col[i]);
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int v = b + i * kCopyThreads;
+                if (v < total) {
+                    const int n = dst_cnt[row[i]];
+                    for (int j = 0; j < n; ++j)
+                        st_stream((v4u *)(xd + (size_t)dst_rows[row[i]][j] * D.Be) + col[i], val[i]);
+                }
+            }
+        }
+    }
+    for (int r = r0; r < r1 && D.scales_per_row; ++r) {
         const int n = dst_cnt[r - r0];
         const int *dr = dst_rows[r - r0];
-        for (int v = tid; v < nvec; v += kCopyThreads) {
-            const uint4 val = src[v];
-            for (int i = 0; i < n; ++i) ((uint4 *)(xd + (size_t)dr[i] * D.Be))[v] = val;
-        }
-        if (D.scales_per_row) {                // e4m3: the scales follow the bytes on the wire
+        {                                      // e4m3: the scales follow the bytes on the wire
             const float *ssrc = (const float *)(recv + (size_t)r * D.Bw + D.Be);
             for (int v = tid; v < D.scales_per_row; v += kCopyThreads) {
                 const float val = ssrc[v];
@@ -233,7 +251,6 @@ __global__ __launch_bounds__(kCopyThreads) void combine_pack_kernel(
     const int d = rank_begin + blockIdx.y, tid = threadIdx.x, N = D.N, El = D.El;
     __shared__ int off[FL_MAX_RANKS + 1];
     __shared__ int src_row[kMaxRowsPerBlock];
-    if (blockIdx.x == 0 && tid == 0) W.epoch_comb[d] += 1u;
     if (!W.plan_ok[d]) return;
     if (tid <= N) off[tid] = W.cs_off[(size_t)d * (N + 1) + tid];
     __syncthreads();
@@ -247,58 +264,64 @@ __global__ __launch_bounds__(kCopyThreads) void combine_pack_kernel(
         const int *csb = W.cs_base + ((size_t)d * N + s) * El;
         const int j = seg_of(csb, El, q);
         src_row[tid] = W.base_x[((size_t)d * El + j) * N + s] + (q - csb[j]);
+        W.fab_dst_comb[(size_t)d * D.expert_cap + q] =
+            make_int2(s, W.comb_dst_off[(size_t)d * N + s] + (q - off[s]));
     }
     __syncthreads();
     const int nvec = (int)(D.Bc / 16);
     const char *yd = expert_y + (size_t)d * D.expert_cap * D.Bc;
     char *out = W.bufB + (size_t)d * D.bufB_rank_bytes;
-    for (int q = q0; q < q1; ++q)
-        copy_row<kCopyThreads>((uint4 *)(out + (size_t)q * D.Bc),
-                               (const uint4 *)(yd + (size_t)src_row[q - q0] * D.Bc), nvec, tid);
+    out += (size_t)q0 * D.Bc;
+    copy_rows_flat<kCopyThreads>(
+        q1 - q0, nvec, tid,
+        [&](int r) { return yd + (size_t)src_row[r] * D.Bc; },
+        [&](int r) { return out + (size_t)r * D.Bc; });
 }
 
 // ------------------------------------------------------------------ combine: reduce
 // One block per token (s, t):
 //   out[s][t] = bf16( sum_k w[k] * float(row comb_pos[s][t][k]) ), fp32 fused
 // multiply-add, k ascending, one final rounding.
+__device__ inline void fma8(float *acc, float wk, v4u y) {
+    acc[0] = fmaf(wk, bf16_lo(y.x), acc[0]); acc[1] = fmaf(wk, bf16_hi(y.x), acc[1]);
+    acc[2] = fmaf(wk, bf16_lo(y.y), acc[2]); acc[3] = fmaf(wk, bf16_hi(y.y), acc[3]);
+    acc[4] = fmaf(wk, bf16_lo(y.z), acc[4]); acc[5] = fmaf(wk, bf16_hi(y.z), acc[5]);
+    acc[6] = fmaf(wk, bf16_lo(y.w), acc[6]); acc[7] = fmaf(wk, bf16_hi(y.w), acc[7]);
+}
+
+// KT = number of row loads issued together (then consumed in k order); the sum
+// itself always runs k = 0..K-1.
 template <int KT>
 __device__ inline void reduce_row(const char *__restrict__ recv, const int *pos, const float *w,
-                                  int K, long long Bc, int nvec, uint4 *__restrict__ out, int tid) {
-    for (int v = tid; v < nvec; v += kCopyThreads) {
+                                  int K, long long Bc, int nvec, v4u *__restrict__ out, int tid) {
+    for (int v = tid; v < nvec; v += (int)blockDim.x) {
         float acc[8];
 #pragma unroll
         for (int i = 0; i < 8; ++i) acc[i] = 0.f;
-        if (KT > 0) {
-            uint4 y[KT > 0 ? KT : 1];
+        int k0 = 0;
+        for (; k0 + KT <= K; k0 += KT) {
+            v4u y[KT];
 #pragma unroll
-            for (int k = 0; k < KT; ++k) y[k] = ((const uint4 *)(recv + (size_t)pos[k] * Bc))[v];
+            for (int k = 0; k < KT; ++k)
+                y[k] = ld_stream((const v4u *)(recv + (size_t)pos[k0 + k] * Bc) + v);
 #pragma unroll
-            for (int k = 0; k < KT; ++k) {
-                const float wk = w[k];
-                acc[0] = fmaf(wk, bf16_lo(y[k].x), acc[0]); acc[1] = fmaf(wk, bf16_hi(y[k].x), acc[1]);
-                acc[2] = fmaf(wk, bf16_lo(y[k].y), acc[2]); acc[3] = fmaf(wk, bf16_hi(y[k].y), acc[3]);
-                acc[4] = fmaf(wk, bf16_lo(y[k].z), acc[4]); acc[5] = fmaf(wk, bf16_hi(y[k].z), acc[5]);
-                acc[6] = fmaf(wk, bf16_lo(y[k].w), acc[6]); acc[7] = fmaf(wk, bf16_hi(y[k].w), acc[7]);
-            }
-        } else {
-            for (int k = 0; k < K; ++k) {
-                const uint4 y = ((const uint4 *)(recv + (size_t)pos[k] * Bc))[v];
-                const float wk = w[k];
-                acc[0] = fmaf(wk, bf16_lo(y.x), acc[0]); acc[1] = fmaf(wk, bf16_hi(y.x), acc[1]);
-                acc[2] = fmaf(wk, bf16_lo(y.y), acc[2]); acc[3] = fmaf(wk, bf16_hi(y.y), acc[3]);
-                acc[4] = fmaf(wk, bf16_lo(y.z), acc[4]); acc[5] = fmaf(wk, bf16_hi(y.z), acc[5]);
-                acc[6] = fmaf(wk, bf16_lo(y.w), acc[6]); acc[7] = fmaf(wk, bf16_hi(y.w), acc[7]);
-            }
+            for (int k = 0; k < KT; ++k) fma8(acc, w[k0 + k], y[k]);
         }
-        uint4 o;
+        for (; k0 < K; ++k0)
+            fma8(acc, w[k0], ld_stream((const v4u *)(recv + (size_t)pos[k0] * Bc) + v));
+        v4u o;
         o.x = pack_bf16x2(acc[0], acc[1]); o.y = pack_bf16x2(acc[2], acc[3]);
         o.z = pack_bf16x2(acc[4], acc[5]); o.w = pack_bf16x2(acc[6], acc[7]);
-        out[v] = o;
+        st_stream(out + v, o);
     }
 }
 
+// The block has min(1024, vectors per row rounded up to a wave) threads, so a
+// 7168-wide row is one vector per thread and all K loads of a thread are in
+// flight at once.
+constexpr int kReduceMaxThreads = 1024;
 template <bool FENCED>
-__global__ __launch_bounds__(kCopyThreads) void combine_reduce_kernel(
+__global__ __launch_bounds__(kReduceMaxThreads, 7) void combine_reduce_kernel(
     Dims D, Tables W, int rank_begin, const float *__restrict__ weights, char *__restrict__ out,
     const int *__restrict__ num_tokens) {
     const int s = rank_begin + blockIdx.y, t = blockIdx.x, tid = threadIdx.x, N = D.N, K = D.K;
@@ -309,7 +332,8 @@ __global__ __launch_bounds__(kCopyThreads) void combine_reduce_kernel(
     if (tid == 0) timed_out = 0;
     __syncthreads();
     if (tid < kWave) {
-        if (!wave_wait_counters(W.arrive_comb + (size_t)s * N, N, W.epoch_comb[s], D.spin_limit)) {
+        if (!wave_wait_counters(W.arrive_comb + (size_t)s * N, W.expect_comb + (size_t)s * N, 0u, N,
+                                D.spin_limit)) {
             if (tid == 0) { timed_out = 1; latch_status(W.status, FL_STATUS_TIMEOUT); }
         }
         acquire_payload<FENCED>();
@@ -321,31 +345,29 @@ __global__ __launch_bounds__(kCopyThreads) void combine_reduce_kernel(
     __syncthreads();
     if (timed_out) return;
     const char *recv = W.bufA + (size_t)s * D.bufA_rank_bytes;
-    uint4 *o = (uint4 *)(out + ((size_t)s * D.T + t) * D.Bc);
+    v4u *o = (v4u *)(out + ((size_t)s * D.T + t) * D.Bc);
     const int nvec = (int)(D.Bc / 16);
-    if (K == 8) reduce_row<8>(recv, pos, w, K, D.Bc, nvec, o, tid);
-    else if (K == 4) reduce_row<4>(recv, pos, w, K, D.Bc, nvec, o, tid);
-    else if (K == 2) reduce_row<2>(recv, pos, w, K, D.Bc, nvec, o, tid);
-    else reduce_row<0>(recv, pos, w, K, D.Bc, nvec, o, tid);
+    const int kt = D.tune_reduce ? D.tune_reduce : K;
+    if (kt >= 8) reduce_row<8>(recv, pos, w, K, D.Bc, nvec, o, tid);
+    else if (kt >= 4) reduce_row<4>(recv, pos, w, K, D.Bc, nvec, o, tid);
+    else if (kt >= 2) reduce_row<2>(recv, pos, w, K, D.Bc, nvec, o, tid);
+    else reduce_row<1>(recv, pos, w, K, D.Bc, nvec, o, tid);
 }
 
 // ------------------------------------------------------------------ diagnostic copy
-__global__ __launch_bounds__(kCopyThreads) void plain_copy_kernel(uint4 *__restrict__ dst,
-                                                                  const uint4 *__restrict__ src,
+// Plain linear copy in the shape that measured fastest on this part: one 16 KB
+// chunk per block, four non-temporal loads per thread in flight, then the stores.
+__global__ __launch_bounds__(kCopyThreads) void plain_copy_kernel(v4u *__restrict__ dst,
+                                                                  const v4u *__restrict__ src,
                                                                   size_t nvec) {
-    const size_t stride = (size_t)gridDim.x * kCopyThreads * 4;
-    for (size_t v = (size_t)blockIdx.x * kCopyThreads * 4 + threadIdx.x; v < nvec; v += stride) {
-        uint4 a, b, c, d;
-        const bool f = v + 3 * kCopyThreads < nvec;
-        a = src[v];
-        if (f) { b = src[v + kCopyThreads]; c = src[v + 2 * kCopyThreads]; d = src[v + 3 * kCopyThreads]; }
-        dst[v] = a;
-        if (f) { dst[v + kCopyThreads] = b; dst[v + 2 * kCopyThreads] = c; dst[v + 3 * kCopyThreads] = d; }
-        else {
-            for (size_t u = v + kCopyThreads; u < nvec && u < v + 4 * kCopyThreads; u += kCopyThreads)
-                dst[u] = src[u];
-        }
-    }
+    const size_t base = (size_t)blockIdx.x * kCopyThreads * 4 + threadIdx.x;
+    v4u r[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+        if (base + (size_t)i * kCopyThreads < nvec) r[i] = ld_stream(src + base + (size_t)i * kCopyThreads);
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+        if (base + (size_t)i * kCopyThreads < nvec) st_stream(dst + base + (size_t)i * kCopyThreads, r[i]);
 }
 
 }  // namespace flmoe

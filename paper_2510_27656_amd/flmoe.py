@@ -46,15 +46,15 @@ class fl_moe_layout_view(C.Structure):
 class fl_moe_debug_view(C.Structure):
     _fields_ = [("buf_a", C.c_void_p), ("buf_b", C.c_void_p),
                 ("buf_a_rank_bytes", C.c_int64), ("buf_b_rank_bytes", C.c_int64),
-                ("arrive_route", C.c_void_p), ("arrive_disp", C.c_void_p),
-                ("arrive_comb", C.c_void_p), ("epoch_route", C.c_void_p),
-                ("epoch_disp", C.c_void_p), ("epoch_comb", C.c_void_p), ("status", C.c_void_p)]
+                ("arrive_route", C.c_void_p), ("epoch_route", C.c_void_p),
+                ("arrive_disp", C.c_void_p), ("arrive_comb", C.c_void_p),
+                ("expect_disp", C.c_void_p), ("expect_comb", C.c_void_p), ("status", C.c_void_p)]
 
 
 EXPORTS = ["fl_moe_query_sizes", "fl_moe_create", "fl_moe_destroy", "fl_moe_layout",
            "fl_moe_dispatch_send", "fl_moe_dispatch_recv", "fl_moe_combine_send",
            "fl_moe_combine_reduce", "fl_moe_status", "fl_moe_strerror", "fl_moe_debug_views",
-           "fl_moe_debug_copy", "fl_moe_profile_enable", "fl_moe_profile_collect", "fl_moe_profile_read",
+           "fl_moe_debug_tune", "fl_moe_debug_copy", "fl_moe_profile_enable", "fl_moe_profile_collect", "fl_moe_profile_read",
            "fl_moe_kernel_name"]
 
 _lib = None
@@ -81,6 +81,7 @@ def lib():
         L.fl_moe_strerror.argtypes = [i32]
         L.fl_moe_strerror.restype = C.c_char_p
         L.fl_moe_debug_views.argtypes = [vp, C.POINTER(fl_moe_debug_view)]
+        L.fl_moe_debug_tune.argtypes = [vp, i32, i32]
         L.fl_moe_debug_copy.argtypes = [vp, vp, C.c_size_t, vp]
         L.fl_moe_profile_enable.argtypes = [vp, i32]
         L.fl_moe_profile_collect.argtypes = [vp, vp]
@@ -175,6 +176,10 @@ def fl_moe_debug_views(ctx) -> fl_moe_debug_view:
     out = fl_moe_debug_view()
     _check(lib().fl_moe_debug_views(ctx, C.byref(out)), "fl_moe_debug_views")
     return out
+
+
+def fl_moe_debug_tune(ctx, knob, value):
+    _check(lib().fl_moe_debug_tune(ctx, knob, value), "fl_moe_debug_tune")
 
 
 def fl_moe_debug_copy(dst, src, nbytes, stream=None):
@@ -310,8 +315,8 @@ class MoEShuffle:
             "arrive_disp": self.table(dv.arrive_disp, (N, N)),
             "arrive_comb": self.table(dv.arrive_comb, (N, N)),
             "epoch_route": self.table(dv.epoch_route, (N,)),
-            "epoch_disp": self.table(dv.epoch_disp, (N,)),
-            "epoch_comb": self.table(dv.epoch_comb, (N,)),
+            "expect_disp": self.table(dv.expect_disp, (N, N)),
+            "expect_comb": self.table(dv.expect_comb, (N, N)),
             "buf_a": self.table(dv.buf_a, (N, dv.buf_a_rank_bytes), torch.uint8),
             "buf_b": self.table(dv.buf_b, (N, dv.buf_b_rank_bytes), torch.uint8),
         }

@@ -165,8 +165,16 @@ def test_repeated_steps_are_deterministic_and_counters_monotone():
             assert (bits(out) == first).all()
         dbg = sh.debug()
         assert (dbg["epoch_route"].cpu().numpy() == 4).all()
-        assert (dbg["arrive_disp"].cpu().numpy() == 4).all()
-        assert (dbg["arrive_comb"].cpu().numpy() == 4).all()
+        assert (dbg["arrive_route"].cpu().numpy() == 4).all()
+        # payload counters: delivered == expected, 4 steps x rows x 16-byte units per row
+        units = inp.wl.hidden * 2 // 16
+        ref = oracle_step(inp)
+        want_disp = 4 * ref.lay.M.T.astype(np.int64) * units            # [dst][src]
+        pairs = ref.lay.C.reshape(inp.wl.n_ranks, inp.wl.n_ranks, -1).sum(2)   # [src][owner]
+        assert (dbg["arrive_disp"].cpu().numpy() == want_disp).all()
+        assert (dbg["expect_disp"].cpu().numpy() == want_disp).all()
+        assert (dbg["arrive_comb"].cpu().numpy() == 4 * pairs * units).all()
+        assert (dbg["expect_comb"].cpu().numpy() == 4 * pairs * units).all()
         assert sh.status() == 0
     finally:
         sh.close()

@@ -101,7 +101,7 @@ typedef struct fl_moe_sizes {
     int64_t send_capacity_rows;   /* T * min(K, N)                                        */
     int64_t x_row_bytes;          /* 2*H                                                  */
     int64_t wire_row_bytes;       /* bytes of one dispatched row in the send/receive
-                                     buffers: 2*H, or H + 4*H/128 for e4m3                */
+                                     buffers: 2*H, or H + 4*H/128 rounded up to 16 for e4m3 */
     int64_t expert_x_row_bytes;   /* 2*H or H                                             */
     int64_t scales_per_row;       /* 0 or H/128                                           */
     int64_t combine_row_bytes;    /* 2*H                                                  */

@@ -388,3 +388,13 @@ void orc_e4m3_decode_array(int64_t n, const uint8_t *in, float *out) {
 void orc_f32_to_bf16_array(int64_t n, const float *in, uint16_t *out) {
     for (int64_t i = 0; i < n; ++i) out[i] = f32_to_bf16_rne(in[i]);
 }
+
+/* Stand-in expert on explicit rows: row r is scaled by gains[r] (used when a test
+ * checks sampled tokens of a workload too large to lay out on the host). */
+void orc_scale_rows(int64_t rows, int H, const float *gains, uint16_t *data) {
+    for (int64_t r = 0; r < rows; ++r)
+        for (int h = 0; h < H; ++h) {
+            uint16_t *p = data + (size_t)r * H + h;
+            *p = f32_to_bf16_rne(bf16_to_f32(*p) * gains[r]);
+        }
+}

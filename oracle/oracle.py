@@ -194,3 +194,23 @@ def f32_to_bf16_array(a):
     out = np.empty(a.shape, np.uint16)
     lib().orc_f32_to_bf16_array(C.c_int64(a.size), _p(a), _p(out))
     return out
+
+
+def scale_rows(rows, gains):
+    """rows uint16 [n][H] (modified in place): row r *= gains[r], rounded to bf16."""
+    _chk(rows, np.uint16)
+    _chk(gains, np.float32, (rows.shape[0],))
+    lib().orc_scale_rows(C.c_int64(rows.shape[0]), rows.shape[1], _p(gains), _p(rows))
+    return rows
+
+
+def combine_sampled(E, K, indices, weights, y_rows):
+    """Combine for an explicit list of n tokens: indices/weights [n][K], y_rows uint16
+    [n*K][H] holds the expert output of pair (i, k) at row i*K + k.  Returns [n][H]."""
+    n = indices.shape[0]
+    H = y_rows.shape[1]
+    idx = np.ascontiguousarray(indices.reshape(1, n, K), np.int32)
+    w = np.ascontiguousarray(weights.reshape(1, n, K), np.float32)
+    slot = np.arange(n * K, dtype=np.int32).reshape(1, n, K)
+    nt = np.array([n], np.int32)
+    return combine(1, E, K, nt, idx, slot, w, y_rows, 0, H)[0]

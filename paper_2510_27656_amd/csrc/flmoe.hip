@@ -82,8 +82,7 @@ int resolve(const fl_moe_config *c, Dims *D) {
     } else {
         D->scales_per_row = D->H / 128;
         D->Be = D->H;
-        D->Bw = D->H + 4ll * D->scales_per_row;
-        if (D->Bw % 16 != 0) return FL_ERR_ALIGNMENT;
+        D->Bw = (long long)align_up((size_t)(D->H + 4ll * D->scales_per_row), 16);
     }
     const long long a1 = D->send_cap * D->Bw, a2 = (long long)D->T * D->K * D->Bc;
     const long long b1 = D->recv_cap * D->Bw, b2 = D->expert_cap * D->Bc;
@@ -318,8 +317,13 @@ int fl_moe_dispatch_send(fl_moe_ctx *ctx, int rb, int rc, const void *x, void *s
     hipStream_t st = (hipStream_t)stream;
     const Dims &D = ctx->D;
     const Tables &W = ctx->W;
-    if (D.dtype != FL_DTYPE_BF16) return FL_ERR_INVALID_ARG;   // e4m3 pack: not built yet
-    {
+    if (D.dtype == FL_DTYPE_E4M3_BLOCK128) {
+        LaunchTimer t(ctx, KID_DISPATCH_PACK_E4M3, st);
+        const int per_block = kPackThreads / kQuantLanes;        // quantisation blocks per workgroup
+        const int slices = (D.scales_per_row + per_block - 1) / per_block;
+        dispatch_pack_e4m3_kernel<<<dim3((unsigned)D.T * slices, rc), dim3(kPackThreads), 0, st>>>(
+            D, W, rb, (const char *)x, ctx->indices, ctx->num_tokens, slices);
+    } else {
         LaunchTimer t(ctx, KID_DISPATCH_PACK, st);
         const int slices = pack_slices(D.Bx, D.tune_slices);
         dispatch_pack_kernel<<<dim3((unsigned)D.T * slices, rc), dim3(kPackThreads), 0, st>>>(

@@ -73,6 +73,101 @@ __global__ __launch_bounds__(kPackThreads) void dispatch_pack_kernel(
     }
 }
 
+// ------------------------------------------------------------------ dispatch: pack with e4m3 quantisation
+// Payload of section Kernel Microbenchmarks: H e4m3 bytes followed by H/128 fp32
+// scales per token.  Rule per 128-element block: amax = max |x|, scale =
+// amax / 448 (1 when amax is 0), q = e4m3(x / scale) rounded to nearest even and
+// saturated at +-448; both divisions are IEEE fp32 divisions.
+//
+// OCP E4M3, finite-only: 1 sign, 4 exponent bits (bias 7), 3 mantissa bits,
+// subnormals m * 2^-9, largest finite 448, no infinities.
+__device__ inline unsigned e4m3_encode(float v) {
+    unsigned u = __float_as_uint(v);
+    const unsigned sign = (u >> 24) & 0x80u;
+    u &= 0x7fffffffu;
+    if (u > 0x7f800000u) return sign | 0x7fu;          // NaN
+    if (u >= 0x43e00000u) return sign | 0x7eu;         // |v| >= 448 saturates
+    if (u >= 0x3c800000u) {                            // |v| >= 2^-6: a normal e4m3 number
+        u += 0x7ffffu + ((u >> 20) & 1u);              // drop 20 mantissa bits, ties to even
+        return sign | ((u >> 20) - (120u << 3));       // re-bias the exponent: 127 -> 7
+    }
+    // subnormal range: m = rne(|v| * 2^9), m = 8 is the smallest normal number
+    return sign | (unsigned)__float2int_rn(__uint_as_float(u) * 512.0f);
+}
+
+constexpr int kQuantLanes = 8;     // lanes per 128-element block: 16 bf16 values each
+
+// One block of kPackThreads threads takes 16 quantisation blocks of one token;
+// every lane loads 32 bytes, takes part in an 8-lane max, and stores 16 bytes of
+// e4m3 per destination copy; the group's first lane stores the scale.
+__global__ __launch_bounds__(kPackThreads) void dispatch_pack_e4m3_kernel(
+    Dims D, Tables W, int rank_begin, const char *__restrict__ x,
+    const int *__restrict__ indices, const int *__restrict__ num_tokens, int slices) {
+    const int s = rank_begin + blockIdx.y, t = blockIdx.x / slices, slice = blockIdx.x % slices;
+    const int tid = threadIdx.x;
+    const int K = D.K, El = D.El;
+    if (!W.plan_ok[s] || t >= num_tokens[s]) return;
+    __shared__ int s_row[FL_MAX_TOPK];
+    __shared__ int s_dst[FL_MAX_TOPK];
+    __shared__ unsigned s_meta[FL_MAX_TOPK];
+    const size_t pair0 = ((size_t)s * D.T + t) * K;
+    int my_row = -1, my_d = 0, delta = 0;
+    if (tid < K) {
+        my_row = W.send_row[pair0 + tid];
+        my_d = indices[pair0 + tid] / El;
+        s_meta[tid] = W.pair_meta[pair0 + tid];
+        s_row[tid] = my_row;
+        s_dst[tid] = my_d;
+        if (my_row >= 0)
+            delta = W.dst_off[(size_t)s * D.N + my_d] - W.send_off[(size_t)s * (D.N + 1) + my_d];
+    }
+    __syncthreads();
+    if (slice == 0 && tid < K && my_row >= 0) {
+        unsigned *meta = W.send_meta + ((size_t)s * D.send_cap + my_row) * D.KM;
+        int m = 0;
+        for (int k = 0; k < K; ++k)
+            if (s_dst[k] == my_d) meta[m++] = s_meta[k];
+        for (; m < D.KM; ++m) meta[m] = kNoEntry;
+        W.fab_dst_disp[(size_t)s * D.send_cap + my_row] = make_int2(my_d, my_row + delta);
+    }
+    const int nblk = D.scales_per_row;                          // 128-element blocks in the row
+    const int blk = slice * (kPackThreads / kQuantLanes) + tid / kQuantLanes;
+    const int sub = tid % kQuantLanes;
+    const bool live = blk < nblk;
+    v4u in0 = {0u, 0u, 0u, 0u}, in1 = {0u, 0u, 0u, 0u};
+    if (live) {
+        const v4u *src = (const v4u *)(x + ((size_t)s * D.T + t) * D.Bx) + (size_t)blk * 16 + sub * 2;
+        in0 = ld_stream(src);
+        in1 = ld_stream(src + 1);
+    }
+    float f[16];
+    const unsigned w[8] = {in0.x, in0.y, in0.z, in0.w, in1.x, in1.y, in1.z, in1.w};
+#pragma unroll
+    for (int i = 0; i < 8; ++i) { f[2 * i] = bf16_lo(w[i]); f[2 * i + 1] = bf16_hi(w[i]); }
+    float amax = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) amax = fmaxf(amax, fabsf(f[i]));
+#pragma unroll
+    for (int o = 1; o < kQuantLanes; o <<= 1) amax = fmaxf(amax, __shfl_xor(amax, o));
+    const float scale = amax == 0.f ? 1.0f : __fdiv_rn(amax, 448.0f);
+    unsigned q[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+        q[i] = e4m3_encode(__fdiv_rn(f[4 * i], scale)) | (e4m3_encode(__fdiv_rn(f[4 * i + 1], scale)) << 8) |
+               (e4m3_encode(__fdiv_rn(f[4 * i + 2], scale)) << 16) |
+               (e4m3_encode(__fdiv_rn(f[4 * i + 3], scale)) << 24);
+    const v4u out = {q[0], q[1], q[2], q[3]};
+    if (!live) return;
+    char *sendbuf = W.bufA + (size_t)s * D.bufA_rank_bytes;
+    for (int k = 0; k < K; ++k) {
+        const int row = s_row[k];
+        if (row < 0) continue;
+        char *dst = sendbuf + (size_t)row * D.Bw;
+        st_stream((v4u *)dst + (size_t)blk * kQuantLanes + sub, out);
+        if (sub == 0) ((float *)(dst + D.Be))[blk] = scale;
+    }
+}
+
 // ------------------------------------------------------------------ fabric copy
 // The stand-in for the NIC scatter: every row of a source's send buffer is
 // copied into the row of the destination's receive buffer that the exchanged

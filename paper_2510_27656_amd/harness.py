@@ -49,16 +49,26 @@ def row_gain(sh: flmoe.MoEShuffle, gain: torch.Tensor):
 
 def expert_stage(sh: flmoe.MoEShuffle, gain: torch.Tensor, identity=False):
     """y = bf16(float(x) * gain[e]) on every row; in place on a copy of expert_x."""
-    if identity:
+    if identity and sh.expert_scales is None:
         return sh.expert_x
     g = row_gain(sh, gain)
     if sh.expert_scales is None:
-        xf = sh.expert_x.float()
-    else:   # e4m3 payload: dequantise first, y = bf16(bf16(float(q) * scale) * gain)
-        q = sh.expert_x.view(torch.float8_e4m3fn).float()
-        sc = sh.expert_scales.repeat_interleave(128, dim=-1)
+        if sh.expert_x.numel() < (1 << 31):
+            return (sh.expert_x.float() * g[..., None]).to(torch.bfloat16)
+        y = torch.empty_like(sh.expert_x)                 # rank by rank to bound the temporaries
+        for d in range(sh.N):
+            y[d] = (sh.expert_x[d].float() * g[d][:, None]).to(torch.bfloat16)
+        return y
+    # e4m3 payload: dequantise first, y = bf16(bf16(float(q) * scale) * gain); rank by rank
+    # to bound the temporaries; codes are decoded through a 256-entry table
+    lut = torch.arange(256, dtype=torch.uint8).view(torch.float8_e4m3fn).float().to(gain.device)
+    y = torch.empty(sh.expert_x.shape, dtype=torch.bfloat16, device=gain.device)
+    for d in range(sh.N):
+        q = lut[sh.expert_x[d].long()]
+        sc = sh.expert_scales[d].repeat_interleave(128, dim=-1)
         xf = (q * sc).to(torch.bfloat16).float()
-    return (xf * g[..., None]).to(torch.bfloat16)
+        y[d] = xf.to(torch.bfloat16) if identity else (xf * g[d][:, None]).to(torch.bfloat16)
+    return y
 
 
 def run_step(sh: flmoe.MoEShuffle, dev, identity=False, ranks=None):
@@ -70,10 +80,12 @@ def run_step(sh: flmoe.MoEShuffle, dev, identity=False, ranks=None):
     return sh.combine_reduce(dev["weights"], ranks)
 
 
-def run_hot_path(sh: flmoe.MoEShuffle, dev):
-    """The five calls back to back (identity expert: expert_y aliases expert_x)."""
+def run_hot_path(sh: flmoe.MoEShuffle, dev, expert_y=None):
+    """The five calls back to back.  bf16 dispatch: identity expert, expert_y aliases
+    expert_x.  e4m3 dispatch: the caller passes a resident bf16 expert_y of the layout's
+    shape (the stand-in expert is not part of the timed path)."""
     sh.layout(dev["indices"], dev["num_tokens"])
     sh.dispatch_send(dev["x"])
     sh.dispatch_recv()
-    sh.combine_send(sh.expert_x)
+    sh.combine_send(sh.expert_x if expert_y is None else expert_y)
     return sh.combine_reduce(dev["weights"])

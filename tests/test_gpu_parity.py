@@ -52,7 +52,8 @@ def run_and_compare(inp, align=1, zero_pad=False, capacity_factor=None, ranks_sp
     sh = harness.make_shuffle(inp, expert_align=align, zero_pad=zero_pad,
                               capacity_factor=capacity_factor, unordered_fabric=unordered)
     try:
-        sh.expert_x.view(torch.int16).fill_(POISON)
+        if wl.dispatch_dtype == "bf16":
+            sh.expert_x.view(torch.int16).fill_(POISON)
         sh.out.view(torch.int16).fill_(POISON)
         identity = wl.expert == "identity"
         if not ranks_split:
@@ -80,9 +81,18 @@ def run_and_compare(inp, align=1, zero_pad=False, capacity_factor=None, ranks_sp
             n = inp.num_tokens[s]
             assert (cp[s, :n] == ref.comb_pos[s, :n]).all()
         # dispatched rows, bit for bit; padding and unused capacity as specified
-        ex = bits(sh.expert_x[:, :ref.stride])
-        exi = sh.expert_x.view(torch.int16)
-        for d in range(N):
+        fp8 = wl.dispatch_dtype == "e4m3"
+        if fp8:
+            ex = sh.expert_x[:, :ref.stride].cpu().numpy()
+            exs = sh.expert_scales[:, :ref.stride].cpu().numpy().view(np.uint32)
+            for d in range(N):
+                n = ref.expert_rows[d].shape[0]
+                assert (ex[d, :n] == ref.expert_rows[d]).all(), f"e4m3 bytes, rank {d}"
+                assert (exs[d, :n] == ref.expert_scales[d].view(np.uint32)).all(), f"scales, rank {d}"
+        else:
+            ex = bits(sh.expert_x[:, :ref.stride])
+            exi = sh.expert_x.view(torch.int16)
+        for d in range(N if not fp8 else 0):
             rows = ref.expert_rows[d]
             n = rows.shape[0]
             if zero_pad:
@@ -195,6 +205,95 @@ def test_parity_named_workloads(name):
     inp = wlmod.make_inputs(wlmod.WORKLOADS[name])
     sh, _, _ = run_and_compare(inp)
     sh.close()
+
+
+FP8_CASES = {
+    "fp8_small": lambda: wlmod.custom("fp8_small", 4, 32, 60, 512, 4, seed=31, ragged=True,
+                                      dispatch_dtype="e4m3"),
+    "fp8_one_block": lambda: wlmod.custom("fp8_one_block", 2, 8, 16, 128, 2, seed=32,
+                                          dispatch_dtype="e4m3", expert="identity"),
+    "fp8_k16": lambda: wlmod.custom("fp8_k16", 4, 64, 40, 2304, 16, seed=33, dispatch_dtype="e4m3"),
+}
+
+
+@pytest.mark.parametrize("name", list(FP8_CASES))
+def test_parity_e4m3_dispatch_small(name):
+    inp = wlmod.make_inputs(FP8_CASES[name]())
+    sh, _, _ = run_and_compare(inp, zero_pad=True, align=4)
+    sh.close()
+
+
+def test_parity_e4m3_dispatch_edge_values():
+    """Blocks of zeros, tiny and huge magnitudes, exact ties: same codes and scales."""
+    wl = wlmod.custom("fp8_edges", 2, 8, 32, 256, 2, seed=34, dispatch_dtype="e4m3")
+    inp = wlmod.make_inputs(wl)
+    x = inp.x.reshape(-1, 128)
+    f = lambda v: torch.tensor(v, dtype=torch.float32).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    x[0] = 0                                             # all-zero block: scale 1
+    x[1] = f([1e-38] * 128)                               # scale is a subnormal fp32
+    x[2] = f([3e38] * 64 + [-3e38] * 64)                  # near the top of the range
+    x[3] = f([448.0] + [v * 448.0 / 16 for v in range(1, 128)])   # many exact multiples and ties
+    x[4] = f([1.0] + [2.0 ** -e for e in range(1, 128)])  # deep into the subnormal e4m3 range
+    x[5] = f([-0.0] * 127 + [5.0])
+    sh, _, _ = run_and_compare(inp, zero_pad=True)
+    sh.close()
+
+
+def test_parity_named_workload_dsv3_fp8():
+    inp = wlmod.make_inputs(wlmod.WORKLOADS["dsv3_fp8"])
+    sh, _, _ = run_and_compare(inp)
+    sh.close()
+
+
+def test_prefill_full_shape():
+    """The 4096-tokens-per-rank workload at its real shape (buffers of 16 GB, byte
+    offsets beyond 2^31).  Tables are compared in full; every dispatched row is
+    compared on the GPU against the input row at the slot the oracle computed; the
+    combined output is compared with the oracle on sampled tokens."""
+    wl = wlmod.WORKLOADS["dsv3_prefill"]
+    print("drawing inputs ...", flush=True)
+    inp = wlmod.make_inputs(wl)
+    N, E, K, H, T = wl.n_ranks, wl.n_experts, wl.top_k, wl.hidden, wl.tokens
+    El = E // N
+    print("oracle layout ...", flush=True)
+    lay = orc.layout(N, E, K, inp.num_tokens, inp.indices)
+    comb_pos = orc.comb_pos(N, E, K, inp.num_tokens, inp.indices)
+    dev = harness.to_device(inp)
+    sh = harness.make_shuffle(inp, capacity_factor=1.1)
+    try:
+        print("gpu step ...", flush=True)
+        out = harness.run_step(sh, dev)
+        torch.cuda.synchronize()
+        assert sh.status() == 0
+        tabs = {k: v.cpu().numpy() for k, v in sh.layout_tables().items()}
+        for name, want in [("C", lay.C), ("M", lay.M), ("G", lay.G), ("send_off", lay.send_off),
+                           ("recv_off", lay.recv_off), ("expert_off", lay.expert_off),
+                           ("comb_off", lay.comb_off), ("comb_pos", comb_pos)]:
+            assert (tabs[name] == want).all(), name
+        assert (sh.tokens_per_expert.cpu().numpy() == lay.G).all()
+        print("rows ...", flush=True)
+        slot = torch.from_numpy(lay.slot).to("cuda:0").long()
+        owner = (dev["indices"] // El).long()
+        for s in range(N):
+            got = sh.expert_x[owner[s], slot[s]]                    # [T][K][H]
+            assert bool((got.view(torch.int16) == dev["x"][s].view(torch.int16)[:, None, :]).all()), s
+            del got
+        # every row of the layout is one of those pairs: counts already match (G, expert_off)
+        print("combine on sampled tokens ...", flush=True)
+        rng = np.random.default_rng(0)
+        ss = np.repeat(np.arange(N), 8)
+        tt = rng.integers(0, T, size=ss.size)
+        idx = inp.indices[ss, tt]                                    # [n][K]
+        y = np.repeat(inp.x[ss, tt], K, axis=0).copy()               # row i*K+k = x of token i
+        orc.scale_rows(y, np.ascontiguousarray(inp.expert_gain[idx.reshape(-1)]))
+        want = orc.combine_sampled(E, K, idx, inp.weights[ss, tt], y)
+        got = bits(out[torch.from_numpy(ss).cuda(), torch.from_numpy(tt).cuda()])
+        dist = ulp_distance(got, want)
+        print(f"[dsv3_prefill] sampled combine: max ulp {int(dist.max())}, "
+              f"bit-exact {int((dist == 0).sum())}/{dist.size}")
+        assert dist.max() <= 1
+    finally:
+        sh.close()
 
 
 def test_decode_with_practical_capacity():

@@ -536,3 +536,19 @@ def test_oracle_digests_unchanged():
     spec.loader.exec_module(mod)
     stored = json.load(open(os.path.join(HERE, "golden", "oracle_digests.json")))
     assert mod.compute() == stored
+
+
+def test_sampled_combine_helper_equals_full_path():
+    """The helpers used for workloads too large to lay out on the host (explicit rows,
+    per-row gain) give what the full dispatch -> expert -> combine path gives."""
+    from oracle.reference_step import oracle_step
+    wl = wlmod.custom("c", 4, 32, 37, 64, 4, seed=1)
+    inp = wlmod.make_inputs(wl)
+    ref = oracle_step(inp)
+    ss = np.repeat(np.arange(4), 5)
+    tt = np.random.default_rng(0).integers(0, 37, ss.size)
+    idx = inp.indices[ss, tt]
+    y = np.repeat(inp.x[ss, tt], 4, axis=0).copy()
+    orc.scale_rows(y, np.ascontiguousarray(inp.expert_gain[idx.reshape(-1)]))
+    got = orc.combine_sampled(32, 4, idx, inp.weights[ss, tt], y)
+    assert (got == ref.out[ss, tt]).all()

@@ -26,6 +26,8 @@ const char *kKernelNames[FL_KERNEL_COUNT] = {
     "combine_reduce_kernel", "dispatch_pack_e4m3_kernel"};
 
 constexpr int kEventPool = 64;
+constexpr long long kMaxFabricBlocks = 1 << 16;   // waves loop cheaply (no barriers)
+constexpr long long kMaxRowBlocks = 1 << 18;      // blocks with barriers: loop only when far oversized
 constexpr long long kDefaultSpin = 1 << 22;
 
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
@@ -148,8 +150,9 @@ bool aligned16(const void *p) { return ((uintptr_t)p & 15) == 0; }
 // a handful of 16-byte vectors.
 int waves_per_row(long long row_bytes, int tune_waves) {
     if (tune_waves >= 1 && tune_waves <= 16) return tune_waves;
-    const long long nvec = row_bytes / 16;
-    return nvec >= 256 ? 4 : nvec >= 128 ? 2 : 1;
+    // about 4 KB per wave: one counter update per wave, and those updates serialise in L2
+    const long long w = (row_bytes + 4095) / 4096;
+    return (int)(w < 1 ? 1 : w > 4 ? 4 : w);
 }
 
 // Blocks that share one token in the pack kernel (each takes a slice of the row).
@@ -158,6 +161,18 @@ int pack_slices(long long row_bytes, int tune_slices) {
     const long long nvec = row_bytes / 16;
     long long s = (nvec + kPackThreads - 1) / kPackThreads;   // one vector per thread
     return (int)(s < 1 ? 1 : s > 16 ? 16 : s);
+}
+
+// Grids are sized from capacities (the rows really in use are only known on the
+// device), so a generous capacity would launch mostly idle blocks; beyond this
+// many blocks per launch the kernels loop instead.
+unsigned capped_grid(long long blocks_needed, int rank_count, long long max_blocks,
+                     int multiple_of = 1) {
+    long long limit = max_blocks / rank_count;
+    if (limit < 1) limit = 1;
+    long long g = blocks_needed < limit ? blocks_needed : limit;
+    g = (g + multiple_of - 1) / multiple_of * multiple_of;
+    return (unsigned)(g < 1 ? 1 : g);
 }
 
 int rows_per_block(long long row_bytes, int tune_rows) {
@@ -338,7 +353,9 @@ int fl_moe_dispatch_send(fl_moe_ctx *ctx, int rb, int rc, const void *x, void *s
     A.arrive = W.arrive_disp;
     A.row_bytes = D.Bw; A.waves_per_row = waves_per_row(D.Bw, D.tune_waves);
     const int wpb = kCopyThreads / kWave;
-    const unsigned gx = (unsigned)((D.send_cap * A.waves_per_row + wpb - 1) / wpb);
+    // a multiple of waves_per_row blocks keeps every row's waves at a fixed stride
+    const unsigned gx = capped_grid((D.send_cap * A.waves_per_row + wpb - 1) / wpb, rc, kMaxFabricBlocks,
+                                     A.waves_per_row);
     {
         LaunchTimer t(ctx, KID_DISPATCH_FABRIC, st);
         if (D.flags & FL_FLAG_UNORDERED_FABRIC)
@@ -360,7 +377,7 @@ int fl_moe_dispatch_recv(fl_moe_ctx *ctx, int rb, int rc, void *expert_x, float 
         return FL_ERR_ALIGNMENT;
     hipStream_t st = (hipStream_t)stream;
     const int rbk = rows_per_block(D.Bw, D.tune_rows);
-    unsigned gx = (unsigned)((D.recv_cap + rbk - 1) / rbk);
+    unsigned gx = capped_grid((D.recv_cap + rbk - 1) / rbk, rc, kMaxRowBlocks);
     if (gx < (unsigned)D.El) gx = D.El;      // the first El-1 blocks also clear padding rows
     {
         LaunchTimer t(ctx, KID_DISPATCH_UNPACK, st);
@@ -383,7 +400,7 @@ int fl_moe_combine_send(fl_moe_ctx *ctx, int rb, int rc, const void *expert_y, v
     const Dims &D = ctx->D;
     const Tables &W = ctx->W;
     const int rbk = rows_per_block(D.Bc, D.tune_rows);
-    const unsigned gx = (unsigned)((D.expert_cap + rbk - 1) / rbk);
+    const unsigned gx = capped_grid((D.expert_cap + rbk - 1) / rbk, rc, kMaxRowBlocks);
     {
         LaunchTimer t(ctx, KID_COMBINE_PACK, st);
         combine_pack_kernel<<<dim3(gx, rc), dim3(kCopyThreads), 0, st>>>(
@@ -398,7 +415,8 @@ int fl_moe_combine_send(fl_moe_ctx *ctx, int rb, int rc, const void *expert_y, v
     A.arrive = W.arrive_comb;
     A.row_bytes = D.Bc; A.waves_per_row = waves_per_row(D.Bc, D.tune_waves);
     const int wpb = kCopyThreads / kWave;
-    const unsigned gxf = (unsigned)((D.expert_cap * A.waves_per_row + wpb - 1) / wpb);
+    const unsigned gxf = capped_grid((D.expert_cap * A.waves_per_row + wpb - 1) / wpb, rc,
+                                      kMaxFabricBlocks, A.waves_per_row);
     {
         LaunchTimer t(ctx, KID_COMBINE_FABRIC, st);
         if (D.flags & FL_FLAG_UNORDERED_FABRIC)

@@ -200,36 +200,45 @@ __global__ __launch_bounds__(kCopyThreads) void fabric_copy_kernel(Dims D, Table
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = blockIdx.x * (kCopyThreads / kWave) + threadIdx.x / kWave;   // within rank s
     const int G = A.waves_per_row;
-    const int i = wave / G, sub = wave % G;
-    if (i >= A.row_cap) return;
-    // three independent loads, then the payload
+    const int sub = wave % G;
+    const int row_stride = (int)(gridDim.x * (kCopyThreads / kWave)) / G;   // grid is a multiple of G waves
     const int ok = W.plan_ok[s];
-    const int total = A.seg_off[(size_t)s * (N + 1) + N];
-    const int2 t = A.row_dst[(size_t)s * A.row_cap + i];
-    if (!ok || i >= total) return;             // step skipped or row unused: nothing sent
+    const int total = ok ? A.seg_off[(size_t)s * (N + 1) + N] : 0;   // step skipped: nothing sent
     const int nvec = (int)(A.row_bytes / 16);
-    const v4u *src = (const v4u *)(A.src_base + (size_t)s * A.src_rank_stride + (size_t)i * A.row_bytes);
-    v4u *dst = (v4u *)(A.dst_base + (size_t)t.x * A.dst_rank_stride + (size_t)t.y * A.row_bytes);
     const int step = G * kWave;
-    for (int b = sub * kWave + lane; b < nvec; b += 4 * step) {
-        v4u v[4];
+    // The first row's target is fetched together with the two loads above; capacities
+    // are upper bounds, so the grid may be smaller than the rows in use and a wave loops.
+    int i = wave / G;
+    int2 t = make_int2(0, 0);
+    if (i < A.row_cap) t = A.row_dst[(size_t)s * A.row_cap + i];
+    while (i < total) {
+        const v4u *src =
+            (const v4u *)(A.src_base + (size_t)s * A.src_rank_stride + (size_t)i * A.row_bytes);
+        v4u *dst = (v4u *)(A.dst_base + (size_t)t.x * A.dst_rank_stride + (size_t)t.y * A.row_bytes);
+        for (int b = sub * kWave + lane; b < nvec; b += 4 * step) {
+            v4u v[4];
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-            if (b + j * step < nvec) v[j] = ld_stream(src + b + j * step);
+            for (int j = 0; j < 4; ++j)
+                if (b + j * step < nvec) v[j] = ld_stream(src + b + j * step);
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-            if (b + j * step < nvec) st_stream(dst + b + j * step, v[j]);
+            for (int j = 0; j < 4; ++j)
+                if (b + j * step < nvec) st_stream(dst + b + j * step, v[j]);
+        }
+        if (A.src_meta && sub == 0) {          // the sidecar travels with the row
+            const int mv = D.KM / 4;
+            const v4u *ms =
+                (const v4u *)(A.src_meta + (size_t)s * A.src_meta_rank_stride) + (size_t)i * mv;
+            v4u *md = (v4u *)(A.dst_meta + (size_t)t.x * A.dst_meta_rank_stride) + (size_t)t.y * mv;
+            if (lane < mv) md[lane] = ms[lane];
+        }
+        // units this wave delivered: vectors v < nvec with (v / 64) % G == sub
+        const int full = nvec / step, rem = nvec - full * step;
+        const int mine = full * kWave + min(max(rem - sub * kWave, 0), kWave);
+        if (lane == 0 && mine > 0)
+            add_counter<FENCED>(A.arrive + (size_t)t.x * N + s, (unsigned)mine);
+        i += row_stride;
+        if (i < total) t = A.row_dst[(size_t)s * A.row_cap + i];
     }
-    if (A.src_meta && sub == 0) {              // the sidecar travels with the row
-        const int mv = D.KM / 4;
-        const v4u *ms = (const v4u *)(A.src_meta + (size_t)s * A.src_meta_rank_stride) + (size_t)i * mv;
-        v4u *md = (v4u *)(A.dst_meta + (size_t)t.x * A.dst_meta_rank_stride) + (size_t)t.y * mv;
-        if (lane < mv) md[lane] = ms[lane];
-    }
-    // units this wave delivered: vectors v < nvec with (v / 64) % G == sub
-    const int full = nvec / step, rem = nvec - full * step;
-    const int mine = full * kWave + min(max(rem - sub * kWave, 0), kWave);
-    if (lane == 0 && mine > 0) add_counter<FENCED>(A.arrive + (size_t)t.x * N + s, (unsigned)mine);
 }
 
 // ------------------------------------------------------------------ dispatch: unpack
@@ -268,8 +277,8 @@ __global__ __launch_bounds__(kCopyThreads) void dispatch_unpack_kernel(
     if (tid == 0) timed_out = 0;
     __syncthreads();
     const int total = off[N];
-    const int r0 = blockIdx.x * rows_per_block;
-    if (r0 >= total) return;
+    // capacities are upper bounds, so the grid may be smaller than the rows in use
+    for (int r0 = blockIdx.x * rows_per_block; r0 < total; r0 += gridDim.x * rows_per_block) {
     const int r1 = min(r0 + rows_per_block, total);
     const int s0 = seg_of(off, N, r0), s1 = seg_of(off, N, r1 - 1);
     if (tid < kWave) {
@@ -334,6 +343,8 @@ __global__ __launch_bounds__(kCopyThreads) void dispatch_unpack_kernel(
             }
         }
     }
+    __syncthreads();                           // the row plan in LDS is rewritten by the next chunk
+    }
 }
 
 // ------------------------------------------------------------------ combine: pack
@@ -350,8 +361,9 @@ __global__ __launch_bounds__(kCopyThreads) void combine_pack_kernel(
     if (tid <= N) off[tid] = W.cs_off[(size_t)d * (N + 1) + tid];
     __syncthreads();
     const int total = off[N];
-    const int q0 = blockIdx.x * rows_per_block;
-    if (q0 >= total) return;
+    const int nvec = (int)(D.Bc / 16);
+    const char *yd = expert_y + (size_t)d * D.expert_cap * D.Bc;
+    for (int q0 = blockIdx.x * rows_per_block; q0 < total; q0 += gridDim.x * rows_per_block) {
     const int q1 = min(q0 + rows_per_block, total);
     if (tid < q1 - q0) {
         const int q = q0 + tid;
@@ -363,14 +375,13 @@ __global__ __launch_bounds__(kCopyThreads) void combine_pack_kernel(
             make_int2(s, W.comb_dst_off[(size_t)d * N + s] + (q - off[s]));
     }
     __syncthreads();
-    const int nvec = (int)(D.Bc / 16);
-    const char *yd = expert_y + (size_t)d * D.expert_cap * D.Bc;
-    char *out = W.bufB + (size_t)d * D.bufB_rank_bytes;
-    out += (size_t)q0 * D.Bc;
+    char *out = W.bufB + (size_t)d * D.bufB_rank_bytes + (size_t)q0 * D.Bc;
     copy_rows_flat<kCopyThreads>(
         q1 - q0, nvec, tid,
         [&](int r) { return yd + (size_t)src_row[r] * D.Bc; },
         [&](int r) { return out + (size_t)r * D.Bc; });
+    __syncthreads();                           // src_row is rewritten by the next chunk
+    }
 }
 
 // ------------------------------------------------------------------ combine: reduce

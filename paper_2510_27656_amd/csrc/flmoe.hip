@@ -311,7 +311,7 @@ int fl_moe_layout(fl_moe_ctx *ctx, int rb, int rc, const int32_t *indices,
     }
     {
         LaunchTimer t(ctx, KID_ROUTE_PLAN, st);
-        const size_t lds = (D.E + D.El + 1) * sizeof(int);
+        const size_t lds = route_plan_lds_bytes(D.E, D.N, D.El);
         if (fenced) route_plan_kernel<true><<<dim3(rc), dim3(kPlanThreads), lds, st>>>(D, ctx->W, rb);
         else route_plan_kernel<false><<<dim3(rc), dim3(kPlanThreads), lds, st>>>(D, ctx->W, rb);
     }

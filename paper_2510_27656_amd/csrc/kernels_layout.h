@@ -11,11 +11,11 @@
 namespace flmoe {
 
 constexpr int kRouteThreads = 1024;
-constexpr int kPlanThreads = 256;
+constexpr int kPlanThreads = 1024;
 
 __host__ __device__ inline size_t route_count_lds_bytes(int E, int N, int TT) {
     size_t rows = (size_t)E + N;
-    return rows * (TT / 32) * 2 * sizeof(unsigned) + rows * 2 * sizeof(int) + 32 * sizeof(int);
+    return rows * (TT / 32) * 2 * sizeof(unsigned) + rows * 3 * sizeof(int) + 32 * sizeof(int);
 }
 
 // One block per source rank s.
@@ -29,6 +29,10 @@ __host__ __device__ inline size_t route_count_lds_bytes(int E, int N, int TT) {
 //     bits below t in its word
 // which is the stable counting-sort position the canonical (source rank, token
 // index) order needs, with no ticket atomics.
+//
+// Pass 1 counts (per row totals over all tiles), one block scan over the E + N
+// totals turns them into offsets, pass 2 rebuilds each tile's bits (kept from
+// pass 1 when there is a single tile) and writes every pair's final positions.
 //
 // Outputs for rank s: C[s][.], M[s][.], send_off[s][.], comb_off[s][.], per pair
 // send_row / pair_meta / comb_pos; the route record (C | M | comb_off | valid) is
@@ -44,23 +48,22 @@ __global__ __launch_bounds__(kRouteThreads) void route_count_kernel(
     const int rows = E + N;
     const int Wd = D.TT / 32;
     unsigned *bits = lds;                                  // [rows][Wd]
-    unsigned *pre = bits + (size_t)rows * Wd;              // [rows][Wd]
-    int *base = (int *)(pre + (size_t)rows * Wd);          // [rows] hits in earlier tiles
-    int *tot = base + rows;                                // [rows] hits in this tile
-    int *scan_tmp = tot + rows;                            // [32]
+    unsigned *pre = bits + (size_t)rows * Wd;              // [rows][Wd] popcount prefix inside the tile
+    int *count = (int *)(pre + (size_t)rows * Wd);         // [rows] hits over all tiles (C | M)
+    int *start = count + rows;                             // [rows] exclusive scan of count
+    int *base = start + rows;                              // [rows] hits in the tiles before the current one
+    int *scan_tmp = base + rows;                           // [32]
     __shared__ int bad;
 
     int Ts = num_tokens[s];
     if (tid == 0) bad = (Ts < 0 || Ts > D.T) ? 1 : 0;
     Ts = max(0, min(Ts, D.T));
-    for (int r = tid; r < rows; r += kRouteThreads) base[r] = 0;
+    const int ntiles = (Ts + D.TT - 1) / D.TT;
+    for (int r = tid; r < rows; r += kRouteThreads) { count[r] = 0; base[r] = 0; }
     const int *idx_s = indices + (size_t)s * D.T * K;
-    int *rank_se = W.comb_pos + (size_t)s * D.T * K;       // holds the bare rank until the second pass
-    int *rank_sd = W.send_row + (size_t)s * D.T * K;
-    __syncthreads();
 
-    for (int t0 = 0; t0 < Ts; t0 += D.TT) {
-        const int nt = min(D.TT, Ts - t0);
+    // bits and in-tile popcount prefixes of one tile; returns each row's hits in tile_hits
+    auto fill_tile = [&](int t0, int nt, int *tile_hits, bool accumulate) {
         for (int i = tid; i < rows * Wd; i += kRouteThreads) bits[i] = 0;
         __syncthreads();
         for (int p = tid; p < nt * K; p += kRouteThreads) {
@@ -79,80 +82,88 @@ __global__ __launch_bounds__(kRouteThreads) void route_count_kernel(
                 pre[(size_t)r * Wd + w] = run;
                 run += __popc(bits[(size_t)r * Wd + w]);
             }
-            tot[r] = run;
+            tile_hits[r] = accumulate ? tile_hits[r] + run : run;
         }
         __syncthreads();
-        for (int p = tid; p < nt * K; p += kRouteThreads) {
-            const int tl = p / K;
-            const int e = idx_s[(size_t)t0 * K + p];
-            if (e < 0 || e >= E) continue;
-            const unsigned below = (1u << (tl & 31)) - 1u;
-            const int w = tl >> 5;
-            const int re = e, rd = E + e / El;
-            rank_se[(size_t)t0 * K + p] =
-                base[re] + pre[(size_t)re * Wd + w] + __popc(bits[(size_t)re * Wd + w] & below);
-            rank_sd[(size_t)t0 * K + p] =
-                base[rd] + pre[(size_t)rd * Wd + w] + __popc(bits[(size_t)rd * Wd + w] & below);
-        }
-        __syncthreads();
-        for (int r = tid; r < rows; r += kRouteThreads) base[r] += tot[r];
-        __syncthreads();
+    };
+
+    // pass 1: totals over all tiles
+    __syncthreads();
+    for (int tile = 0; tile < ntiles; ++tile) {
+        const int t0 = tile * D.TT;
+        fill_tile(t0, min(D.TT, Ts - t0), count, true);
     }
 
-    // Totals and their exclusive scans.  tot[] is reused: tot[e] = comb_base[e]
-    // (first combine-receive row of expert e), tot[E+d] = send_off[d].
-    int total;
+    // one exclusive scan over the E + N totals (two slots per thread)
     {
-        const int v = tid < E ? base[tid] : 0;             // E <= kRouteThreads
-        const int ex = block_excl_scan(v, scan_tmp, &total);
-        if (tid < E) {
-            tot[tid] = ex;
-            W.C[(size_t)s * E + tid] = v;
-        }
-    }
-    const int pairs_total = total;
-    {
-        const int v = tid < N ? base[E + tid] : 0;         // N <= 64
-        const int ex = block_excl_scan(v, scan_tmp, &total);
-        if (tid < N) {
-            tot[E + tid] = ex;
-            W.M[(size_t)s * N + tid] = v;
-            W.send_off[(size_t)s * (N + 1) + tid] = ex;
-        }
-        if (tid == 0) W.send_off[(size_t)s * (N + 1) + N] = total;
+        const int a = 2 * tid < rows ? count[2 * tid] : 0;
+        const int b = 2 * tid + 1 < rows ? count[2 * tid + 1] : 0;
+        int total;
+        const int ex = block_excl_scan(a + b, scan_tmp, &total);
+        if (2 * tid < rows) start[2 * tid] = ex;
+        if (2 * tid + 1 < rows) start[2 * tid + 1] = ex + a;
     }
     __syncthreads();
-    if (tid < N) W.comb_off[(size_t)s * (N + 1) + tid] = tot[tid * El];
-    if (tid == 0) W.comb_off[(size_t)s * (N + 1) + N] = pairs_total;
+    // start[e] = first combine-receive row of expert e; start[E + d] = pairs + send_off[d]
+    const int pairs_total = start[E];
+    if (tid < E) W.C[(size_t)s * E + tid] = count[tid];
+    if (tid < N) {
+        W.M[(size_t)s * N + tid] = count[E + tid];
+        W.send_off[(size_t)s * (N + 1) + tid] = start[E + tid] - pairs_total;
+        W.comb_off[(size_t)s * (N + 1) + tid] = start[tid * El];
+    }
+    if (tid == 0) {
+        W.send_off[(size_t)s * (N + 1) + N] = start[E + N - 1] + count[E + N - 1] - pairs_total;
+        W.comb_off[(size_t)s * (N + 1) + N] = pairs_total;
+    }
 
-    // Second pass over the pairs: absolute positions.
-    for (int p = tid; p < Ts * K; p += kRouteThreads) {
-        const int k = p % K;
-        const int e = idx_s[p];
-        if (e < 0 || e >= E) continue;
-        const int d = e / El;
-        const int rse = rank_se[p];
-        bool first = true;
-        for (int k2 = 0; k2 < k; ++k2) {
-            const int e2 = idx_s[p - k + k2];
-            if (e2 >= 0 && e2 < E && e2 / El == d) first = false;
+    // pass 2: final position of every pair
+    for (int tile = 0; tile < ntiles; ++tile) {
+        const int t0 = tile * D.TT, nt = min(D.TT, Ts - t0);
+        if (ntiles > 1) fill_tile(t0, nt, count, false);   // count[] now holds this tile's hits
+        for (int p = tid; p < nt * K; p += kRouteThreads) {
+            const int tl = p / K, k = p - tl * K;
+            const size_t g = (size_t)t0 * K + p;
+            const int e = idx_s[g];
+            if (e < 0 || e >= E) continue;
+            const int d = e / El;
+            const unsigned below = (1u << (tl & 31)) - 1u;
+            const int w = tl >> 5;
+            const int re = e, rd = E + d;
+            const int rank_e =
+                base[re] + pre[(size_t)re * Wd + w] + __popc(bits[(size_t)re * Wd + w] & below);
+            const int rank_d =
+                base[rd] + pre[(size_t)rd * Wd + w] + __popc(bits[(size_t)rd * Wd + w] & below);
+            bool first = true;                             // first slot of this token bound for rank d?
+            for (int k2 = 0; k2 < k; ++k2) {
+                const int e2 = idx_s[g - k + k2];
+                if (e2 >= 0 && e2 < E && e2 / El == d) first = false;
+            }
+            const size_t o = (size_t)s * D.T * K + g;
+            W.comb_pos[o] = start[re] + rank_e;
+            W.pair_meta[o] = ((unsigned)(e - d * El) << 24) | (unsigned)rank_e;
+            W.send_row[o] = first ? start[rd] - pairs_total + rank_d : -1;
         }
-        W.comb_pos[(size_t)s * D.T * K + p] = tot[e] + rse;
-        W.pair_meta[(size_t)s * D.T * K + p] = ((unsigned)(e - d * El) << 24) | (unsigned)rse;
-        rank_sd[p] = first ? tot[E + d] + rank_sd[p] : -1;
+        if (ntiles > 1) {
+            __syncthreads();
+            for (int r = tid; r < rows; r += kRouteThreads) base[r] += count[r];
+            __syncthreads();
+        }
     }
     __syncthreads();
     const int valid = bad ? 0 : 1;
     if (bad && tid == 0) latch_status(W.status, FL_STATUS_BAD_INDEX);
 
     // Route exchange: push this rank's record into every peer's table, then notify.
+    // The record is read back from the rank's own tables, which this block wrote above
+    // (count[] may have been reused by pass 2).
     const int RL = D.route_len;
     for (int i = tid; i < N * RL; i += kRouteThreads) {
-        const int peer = i / RL, f = i % RL;
+        const int peer = i / RL, f = i - peer * RL;
         int v;
-        if (f < E) v = base[f];
-        else if (f < E + N) v = base[f];
-        else if (f < E + 2 * N) v = tot[(f - E - N) * El];
+        if (f < E) v = W.C[(size_t)s * E + f];
+        else if (f < E + N) v = W.M[(size_t)s * N + (f - E)];
+        else if (f < E + 2 * N) v = W.comb_off[(size_t)s * (N + 1) + (f - E - N)];
         else v = valid;
         W.routes[((size_t)peer * N + s) * RL + f] = v;
     }
@@ -162,10 +173,16 @@ __global__ __launch_bounds__(kRouteThreads) void route_count_kernel(
     if (tid == 0) W.epoch_route[s] += 1u;
 }
 
-// One block per rank r: waits for the route records of all sources, then
-// derives every table rank r needs for the step from the records it holds.
-// All ranks see the same records, so all reach the same verdict on validity and
-// capacity: a bad step is skipped by everyone without further communication.
+__host__ __device__ inline size_t route_plan_lds_bytes(int E, int N, int El) {
+    return ((size_t)E /*G_all*/ + (size_t)N * El /*own counts*/ + (size_t)N * N /*M*/ + El + 1 +
+            3 * (size_t)N + 8) * sizeof(int);
+}
+
+// One block per rank r: waits for the route records of all sources, stages what
+// it needs from them in LDS with one wide round of loads, then derives every
+// table rank r needs for the step.  All ranks see the same records, so all reach
+// the same verdict on validity and capacity: a bad step is skipped by everyone
+// without further communication.
 template <bool FENCED>
 __global__ __launch_bounds__(kPlanThreads) void route_plan_kernel(Dims D, Tables W,
                                                                   int rank_begin) {
@@ -173,12 +190,16 @@ __global__ __launch_bounds__(kPlanThreads) void route_plan_kernel(Dims D, Tables
     const int r = rank_begin + blockIdx.x;
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wid = tid / kWave;
     const int E = D.E, N = D.N, El = D.El, RL = D.route_len;
-    int *G_all = (int *)lds;              // [E]
-    int *eoff = G_all + E;                // [El+1] of rank r
-    __shared__ int flag;
+    int *G_all = (int *)lds;              // [E]      tokens per expert over all sources
+    int *Cown = G_all + E;                // [N][El]  counts of rank r's experts per source
+    int *Mall = Cown + N * El;            // [N][N]   de-duplicated counts, [source][destination]
+    int *eoff = Mall + N * N;             // [El+1]   expert offsets of rank r
+    int *csoff = eoff + El + 1;           // [N]      first combine-send row of each source
+    __shared__ int flag, invalid, over;
     const int *rt = W.routes + (size_t)r * N * RL;
 
-    if (tid == 0) flag = 0;
+    if (tid == 0) { flag = 0; invalid = 0; over = 0; }
+    for (int e = tid; e < E; e += kPlanThreads) G_all[e] = 0;
     __syncthreads();
     if (wid == 0) {
         const unsigned expect = W.epoch_route[r];
@@ -192,62 +213,59 @@ __global__ __launch_bounds__(kPlanThreads) void route_plan_kernel(Dims D, Tables
         if (tid == 0) W.plan_ok[r] = 0;
         return;
     }
-    int ok = 1;
-    if (tid < N) ok = rt[(size_t)tid * RL + E + 2 * N];
-    if (!__syncthreads_and(ok)) {
+
+    // One wide round of loads.  Expert columns: each thread sums a residue class of
+    // the sources for one expert (all its loads are independent), LDS adds the parts.
+    {
+        const int parts = max(1, kPlanThreads / E);
+        for (int i = tid; i < E * parts; i += kPlanThreads) {
+            const int e = i % E, part = i / E;
+            int acc = 0;
+            for (int s = part; s < N; s += parts) acc += rt[(size_t)s * RL + e];
+            atomicAdd(&G_all[e], acc);
+        }
+        for (int i = tid; i < N * El; i += kPlanThreads)
+            Cown[i] = rt[(size_t)(i / El) * RL + r * El + (i % El)];
+        for (int i = tid; i < N * N; i += kPlanThreads)
+            Mall[i] = rt[(size_t)(i / N) * RL + E + (i % N)];
+        if (tid < N && rt[(size_t)tid * RL + E + 2 * N] == 0) invalid = 1;
+        if (tid < N) W.comb_dst_off[(size_t)r * N + tid] = rt[(size_t)tid * RL + E + N + r];
+    }
+    __syncthreads();
+    if (invalid) {
         if (tid == 0) W.plan_ok[r] = 0;       // the offending source latched BAD_INDEX
         return;
     }
 
-    // Column sums over sources for every expert; running prefixes for own experts.
-    for (int e = tid; e < E; e += kPlanThreads) {
-        const bool own = e / El == r;
-        int acc = 0;
-        for (int s = 0; s < N; ++s) {
-            if (own) W.base_x[((size_t)r * El + (e - r * El)) * N + s] = acc;
-            acc += rt[(size_t)s * RL + e];
-        }
-        G_all[e] = acc;
-    }
-    __syncthreads();
-
-    int over = 0;
     unsigned exp_units = 0;       // wave 0: lane = source; wave 1: lane = peer answering in combine
     if (wid == 0) {
-        // lane = source s: receive offsets, combine-send offsets of rank r
+        // lane = source s: receive offsets and combine-send offsets of rank r
         const int s = lane;
-        const int m = s < N ? rt[(size_t)s * RL + E + r] : 0;
+        const int m = s < N ? Mall[s * N + r] : 0;
         exp_units = (unsigned)m * (unsigned)(D.Bw / 16);
         int inc = wave_incl_scan(m);
         if (s < N) W.recv_off[(size_t)r * (N + 1) + s] = inc - m;
         if (s == N - 1) W.recv_off[(size_t)r * (N + 1) + N] = inc;
         int len = 0;
         if (s < N)
-            for (int j = 0; j < El; ++j) len += rt[(size_t)s * RL + r * El + j];
+            for (int j = 0; j < El; ++j) len += Cown[s * El + j];
         inc = wave_incl_scan(len);
-        if (s < N) {
-            int acc = inc - len;
-            W.cs_off[(size_t)r * (N + 1) + s] = acc;
-            for (int j = 0; j < El; ++j) {
-                W.cs_base[((size_t)r * N + s) * El + j] = acc;
-                acc += rt[(size_t)s * RL + r * El + j];
-            }
-            W.comb_dst_off[(size_t)r * N + s] = rt[(size_t)s * RL + E + N + r];
-        }
+        if (s < N) { csoff[s] = inc - len; W.cs_off[(size_t)r * (N + 1) + s] = inc - len; }
         if (s == N - 1) W.cs_off[(size_t)r * (N + 1) + N] = inc;
     } else if (wid == 1) {
-        // lane = rank d: capacity verdict for every rank, size of d's reply to rank r
+        // lane = rank d: capacity verdict for every rank, start of r's segment at d,
+        // size of d's reply to rank r
         const int d = lane;
         if (d < N) {
             long long recv_rows = 0;
-            int before_me = 0;                  // rows of lower ranks ahead of r's segment at d
+            int before_me = 0;
             for (int s = 0; s < N; ++s) {
-                const int m = rt[(size_t)s * RL + E + d];
+                const int m = Mall[s * N + d];
                 if (s < r) before_me += m;
                 recv_rows += m;
             }
             W.dst_off[(size_t)r * N + d] = before_me;
-            int mine = 0;                       // pairs of rank r served by rank d: its reply
+            int mine = 0;
             for (int j = 0; j < El; ++j) mine += rt[(size_t)r * RL + d * El + j];
             exp_units = (unsigned)mine * (unsigned)(D.Bc / 16);
             long long p = 0;
@@ -260,14 +278,24 @@ __global__ __launch_bounds__(kPlanThreads) void route_plan_kernel(Dims D, Tables
             if (recv_rows > D.recv_cap || p > D.expert_cap) over = 1;
         }
     }
-    over = __syncthreads_or(over);
+    __syncthreads();
     if (over) {
         if (tid == 0) { W.plan_ok[r] = 0; latch_status(W.status, FL_STATUS_CAPACITY); }
         return;
     }
     for (int j = tid; j <= El; j += kPlanThreads) W.expert_off[(size_t)r * (El + 1) + j] = eoff[j];
-    for (int i = tid; i < El * N; i += kPlanThreads)
-        W.base_x[(size_t)r * El * N + i] += eoff[i / N];
+    // base_x[j][s] = expert_off[j] + rows of lower sources in expert j;
+    // cs_base[s][j] = cs_off[s] + rows of lower experts for source s
+    for (int i = tid; i < El * N; i += kPlanThreads) {
+        const int j = i / N, s = i - j * N;
+        int acc = eoff[j];
+        for (int s2 = 0; s2 < s; ++s2) acc += Cown[s2 * El + j];
+        W.base_x[(size_t)r * El * N + i] = acc;
+        const int s3 = i / El, j3 = i - s3 * El;
+        int acc3 = csoff[s3];
+        for (int j2 = 0; j2 < j3; ++j2) acc3 += Cown[s3 * El + j2];
+        W.cs_base[((size_t)r * N + s3) * El + j3] = acc3;
+    }
     if (wid == 0 && lane < N) W.expect_disp[(size_t)r * N + lane] += exp_units;
     if (wid == 1 && lane < N) W.expect_comb[(size_t)r * N + lane] += exp_units;
     if (tid == 0) W.plan_ok[r] = 1;

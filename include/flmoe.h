@@ -64,10 +64,10 @@ extern "C" {
  * call in stream order (one stream, or events between streams); the arrival
  * counters are then bumped and checked with relaxed atomics and no cache
  * maintenance.  With it, send and receive kernels may overlap in time (other
- * streams, other orders): a sender releases its payload before it reports
- * progress and a receiver acquires after its counters arrived, which is the
- * ImmCounter contract with no ordering assumed; it costs one L2 write-back or
- * invalidate per workgroup. */
+ * streams, other orders): a sender writes its payload through to memory
+ * (device-scope stores) and waits for the acknowledgement before it reports
+ * progress, and a receiver invalidates its caches once after its counters
+ * arrived, which is the ImmCounter contract with no ordering assumed. */
 #define FL_FLAG_UNORDERED_FABRIC 2
 
 #define FL_MAX_RANKS 64

@@ -69,31 +69,43 @@ constexpr unsigned kNoEntry = 0xFFFFFFFFu;
 // ---------------------------------------------------------------- atomics
 // Two ways to run the fabric.  Stream-ordered (FENCED = false): the caller keeps
 // every send kernel before the matching receive kernel in stream order, so the
-// kernel boundary already makes payloads visible; counters are bumped and polled
-// with relaxed atomics and no cache maintenance.  Unordered (FENCED = true):
-// senders and receivers may overlap in time, so a block releases (L2 write-back)
-// before it reports progress and a receiver acquires (invalidate) once after
-// its counters arrived.  On gfx950 each XCD has its own L2, which is why the
-// fenced form costs a write-back/invalidate per block and is not the default.
+// kernel boundary already makes payloads visible; payload stores are ordinary
+// streaming stores and the counters are relaxed atomics.  Unordered (FENCED =
+// true): senders and receivers may overlap in time.  On gfx950 each XCD has its
+// own L2, so a payload only becomes visible to a receiver on another XCD once it
+// has left the sender's L2.  An agent-scope release fence would write back the
+// whole L2 (measured: 5x to 25x slower fabric kernel, depending on how many
+// waves fence).  Instead the sender writes the payload with device-scope stores
+// (sc1: written through to memory), waits until its own stores are acknowledged,
+// and only then updates the counter; the receiver polls the counter with
+// device-scope loads and, once it has arrived, invalidates its caches once
+// (agent-scope acquire) before touching the payload.
 __device__ inline unsigned ld_relaxed(const unsigned *p) {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 // The result is never used, so the hardware atomic does not return a value and
 // the wave does not wait for it.
-template <bool FENCED>
 __device__ inline void add_counter(unsigned *p, unsigned v) {
-    if (FENCED) (void)__hip_atomic_fetch_add(p, v, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
-    else (void)__hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    (void)__hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-// Before a block-wide barrier that precedes add_counter<true> by one thread:
-// waits until this wave's stores have been acknowledged, without touching caches.
+// After a wave's last payload store and before its add_counter: in unordered mode,
+// wait until every store of this wave (including the device-scope ones issued
+// from inline assembly, which the compiler does not count) has been acknowledged.
 template <bool FENCED>
 __device__ inline void stores_done() {
-    if (FENCED) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    if (FENCED) {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    }
 }
 template <bool FENCED>
 __device__ inline void acquire_payload() {
     if (FENCED) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+}
+template <bool FENCED>
+__device__ inline void st_word(int *p, int v) {        // small table entries pushed to a peer
+    if (FENCED) __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    else *p = v;
 }
 __device__ inline void latch_status(int *status, int bit) {
     __hip_atomic_fetch_or(status, bit, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -170,6 +182,13 @@ __device__ inline int seg_of(const int *off, int n, int x) {
 typedef unsigned v4u __attribute__((ext_vector_type(4)));
 __device__ inline v4u ld_stream(const v4u *p) { return __builtin_nontemporal_load(p); }
 __device__ inline void st_stream(v4u *p, v4u v) { __builtin_nontemporal_store(v, p); }
+// Fabric payload store: streaming, or (unordered mode) device scope, written through
+// to memory so that another XCD can see it without an L2 write-back.
+template <bool FENCED>
+__device__ inline void st_payload(v4u *p, v4u v) {
+    if (FENCED) asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(p), "v"(v) : "memory");
+    else __builtin_nontemporal_store(v, p);
+}
 
 // A block copies `nrows` rows of `nvec` vectors each; vector v of the chunk lies
 // in row v / nvec.  src_of(row) / dst_of(row) return the row's byte address.

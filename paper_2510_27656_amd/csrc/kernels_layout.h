@@ -13,9 +13,14 @@ namespace flmoe {
 constexpr int kRouteThreads = 1024;
 constexpr int kPlanThreads = 1024;
 
+// Words per row of the LDS bit matrices: the words in use, padded to an odd
+// number so that rows do not all start in the same bank.
+__host__ __device__ inline int route_row_stride(int TT) { return (TT / 32) | 1; }
+
 __host__ __device__ inline size_t route_count_lds_bytes(int E, int N, int TT) {
     size_t rows = (size_t)E + N;
-    return rows * (TT / 32) * 2 * sizeof(unsigned) + rows * 3 * sizeof(int) + 32 * sizeof(int);
+    return rows * route_row_stride(TT) * 2 * sizeof(unsigned) + rows * 3 * sizeof(int) +
+           32 * sizeof(int);
 }
 
 // One block per source rank s.
@@ -46,7 +51,8 @@ __global__ __launch_bounds__(kRouteThreads) void route_count_kernel(
     const int tid = threadIdx.x;
     const int E = D.E, N = D.N, El = D.El, K = D.K;
     const int rows = E + N;
-    const int Wd = D.TT / 32;
+    const int Wn = D.TT / 32;                              // words in use per row
+    const int Wd = route_row_stride(D.TT);                 // row stride in words
     unsigned *bits = lds;                                  // [rows][Wd]
     unsigned *pre = bits + (size_t)rows * Wd;              // [rows][Wd] popcount prefix inside the tile
     int *count = (int *)(pre + (size_t)rows * Wd);         // [rows] hits over all tiles (C | M)
@@ -78,7 +84,7 @@ __global__ __launch_bounds__(kRouteThreads) void route_count_kernel(
         __syncthreads();
         for (int r = tid; r < rows; r += kRouteThreads) {
             int run = 0;
-            for (int w = 0; w < Wd; ++w) {
+            for (int w = 0; w < Wn; ++w) {
                 pre[(size_t)r * Wd + w] = run;
                 run += __popc(bits[(size_t)r * Wd + w]);
             }
@@ -165,11 +171,11 @@ __global__ __launch_bounds__(kRouteThreads) void route_count_kernel(
         else if (f < E + N) v = W.M[(size_t)s * N + (f - E)];
         else if (f < E + 2 * N) v = W.comb_off[(size_t)s * (N + 1) + (f - E - N)];
         else v = valid;
-        W.routes[((size_t)peer * N + s) * RL + f] = v;
+        st_word<FENCED>(&W.routes[((size_t)peer * N + s) * RL + f], v);
     }
     stores_done<FENCED>();
     __syncthreads();
-    if (tid < N) add_counter<FENCED>(W.arrive_route + (size_t)tid * N + s, 1u);
+    if (tid < N) add_counter(W.arrive_route + (size_t)tid * N + s, 1u);
     if (tid == 0) W.epoch_route[s] += 1u;
 }
 

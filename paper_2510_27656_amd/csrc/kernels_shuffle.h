@@ -222,20 +222,20 @@ __global__ __launch_bounds__(kCopyThreads) void fabric_copy_kernel(Dims D, Table
                 if (b + j * step < nvec) v[j] = ld_stream(src + b + j * step);
 #pragma unroll
             for (int j = 0; j < 4; ++j)
-                if (b + j * step < nvec) st_stream(dst + b + j * step, v[j]);
+                if (b + j * step < nvec) st_payload<FENCED>(dst + b + j * step, v[j]);
         }
         if (A.src_meta && sub == 0) {          // the sidecar travels with the row
             const int mv = D.KM / 4;
             const v4u *ms =
                 (const v4u *)(A.src_meta + (size_t)s * A.src_meta_rank_stride) + (size_t)i * mv;
             v4u *md = (v4u *)(A.dst_meta + (size_t)t.x * A.dst_meta_rank_stride) + (size_t)t.y * mv;
-            if (lane < mv) md[lane] = ms[lane];
+            if (lane < mv) st_payload<FENCED>(md + lane, ms[lane]);
         }
         // units this wave delivered: vectors v < nvec with (v / 64) % G == sub
         const int full = nvec / step, rem = nvec - full * step;
         const int mine = full * kWave + min(max(rem - sub * kWave, 0), kWave);
-        if (lane == 0 && mine > 0)
-            add_counter<FENCED>(A.arrive + (size_t)t.x * N + s, (unsigned)mine);
+        stores_done<FENCED>();
+        if (lane == 0 && mine > 0) add_counter(A.arrive + (size_t)t.x * N + s, (unsigned)mine);
         i += row_stride;
         if (i < total) t = A.row_dst[(size_t)s * A.row_cap + i];
     }

@@ -277,44 +277,44 @@ __global__ __launch_bounds__(kCopyThreads) void dispatch_unpack_kernel(
     if (tid == 0) timed_out = 0;
     __syncthreads();
     const int total = off[N];
-    // capacities are upper bounds, so the grid may be smaller than the rows in use
-    for (int r0 = blockIdx.x * rows_per_block; r0 < total; r0 += gridDim.x * rows_per_block) {
-    const int r1 = min(r0 + rows_per_block, total);
-    const int s0 = seg_of(off, N, r0), s1 = seg_of(off, N, r1 - 1);
-    if (tid < kWave) {
-        if (!wave_wait_counters(W.arrive_disp + (size_t)d * N + s0,
-                                W.expect_disp + (size_t)d * N + s0, 0u, s1 - s0 + 1, D.spin_limit)) {
-            if (tid == 0) { timed_out = 1; latch_status(W.status, FL_STATUS_TIMEOUT); }
-        }
-        acquire_payload<FENCED>();
-    }
-    __syncthreads();
-    if (timed_out) return;
-    if (tid < r1 - r0) {
-        const int r = r0 + tid;
-        const int s = seg_of(off, N, r);
-        const unsigned *meta = W.recv_meta + ((size_t)d * D.recv_cap + r) * D.KM;
-        int n = 0;
-        for (int k = 0; k < K; ++k) {
-            const unsigned m = meta[k];
-            if (m == kNoEntry) break;
-            const int j = (int)(m >> 24), i = (int)(m & 0xFFFFFFu);
-            dst_rows[tid][n++] = W.base_x[((size_t)d * El + j) * N + s] + i;
-        }
-        dst_cnt[tid] = n;
-    }
-    __syncthreads();
     const char *recv = W.bufB + (size_t)d * D.bufB_rank_bytes;
     const int nvec = (int)(D.Be / 16);
-    {
-        const int total = (r1 - r0) * nvec;
-        for (int b = tid; b < total; b += 4 * kCopyThreads) {
+    // capacities are upper bounds, so the grid may be smaller than the rows in use
+    for (int r0 = blockIdx.x * rows_per_block; r0 < total; r0 += gridDim.x * rows_per_block) {
+        const int r1 = min(r0 + rows_per_block, total);
+        const int s0 = seg_of(off, N, r0), s1 = seg_of(off, N, r1 - 1);
+        if (tid < kWave) {
+            if (!wave_wait_counters(W.arrive_disp + (size_t)d * N + s0,
+                                    W.expect_disp + (size_t)d * N + s0, 0u, s1 - s0 + 1,
+                                    D.spin_limit)) {
+                if (tid == 0) { timed_out = 1; latch_status(W.status, FL_STATUS_TIMEOUT); }
+            }
+            acquire_payload<FENCED>();
+        }
+        __syncthreads();
+        if (timed_out) return;
+        if (tid < r1 - r0) {                   // plan of one received row: its expert-major rows
+            const int r = r0 + tid;
+            const int s = seg_of(off, N, r);
+            const unsigned *meta = W.recv_meta + ((size_t)d * D.recv_cap + r) * D.KM;
+            int n = 0;
+            for (int k = 0; k < K; ++k) {
+                const unsigned m = meta[k];
+                if (m == kNoEntry) break;
+                const int j = (int)(m >> 24), i = (int)(m & 0xFFFFFFu);
+                dst_rows[tid][n++] = W.base_x[((size_t)d * El + j) * N + s] + i;
+            }
+            dst_cnt[tid] = n;
+        }
+        __syncthreads();
+        const int chunk = (r1 - r0) * nvec;
+        for (int b = tid; b < chunk; b += 4 * kCopyThreads) {
             v4u val[4];
             int row[4], col[4];
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const int v = b + i * kCopyThreads;
-                if (v < total) {
+                if (v < chunk) {
                     row[i] = v / nvec;
                     col[i] = v - row[i] * nvec;
                     val[i] = ld_stream((const v4u *)(recv + (size_t)(r0 + row[i]) * D.Bw) + col[i]);
@@ -323,27 +323,26 @@ __global__ __launch_bounds__(kCopyThreads) void dispatch_unpack_kernel(
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const int v = b + i * kCopyThreads;
-                if (v < total) {
+                if (v < chunk) {
                     const int n = dst_cnt[row[i]];
                     for (int j = 0; j < n; ++j)
                         st_stream((v4u *)(xd + (size_t)dst_rows[row[i]][j] * D.Be) + col[i], val[i]);
                 }
             }
         }
-    }
-    for (int r = r0; r < r1 && D.scales_per_row; ++r) {
-        const int n = dst_cnt[r - r0];
-        const int *dr = dst_rows[r - r0];
-        {                                      // e4m3: the scales follow the bytes on the wire
-            const float *ssrc = (const float *)(recv + (size_t)r * D.Bw + D.Be);
-            for (int v = tid; v < D.scales_per_row; v += kCopyThreads) {
-                const float val = ssrc[v];
-                for (int i = 0; i < n; ++i)
-                    expert_scales[((size_t)d * D.expert_cap + dr[i]) * D.scales_per_row + v] = val;
+        if (D.scales_per_row) {                // e4m3: the scales follow the bytes on the wire
+            for (int r = r0; r < r1; ++r) {
+                const int n = dst_cnt[r - r0];
+                const int *dr = dst_rows[r - r0];
+                const float *ssrc = (const float *)(recv + (size_t)r * D.Bw + D.Be);
+                for (int v = tid; v < D.scales_per_row; v += kCopyThreads) {
+                    const float val = ssrc[v];
+                    for (int i = 0; i < n; ++i)
+                        expert_scales[((size_t)d * D.expert_cap + dr[i]) * D.scales_per_row + v] = val;
+                }
             }
         }
-    }
-    __syncthreads();                           // the row plan in LDS is rewritten by the next chunk
+        __syncthreads();                       // the row plan in LDS is rewritten by the next chunk
     }
 }
 
@@ -363,24 +362,25 @@ __global__ __launch_bounds__(kCopyThreads) void combine_pack_kernel(
     const int total = off[N];
     const int nvec = (int)(D.Bc / 16);
     const char *yd = expert_y + (size_t)d * D.expert_cap * D.Bc;
+    // capacities are upper bounds, so the grid may be smaller than the rows in use
     for (int q0 = blockIdx.x * rows_per_block; q0 < total; q0 += gridDim.x * rows_per_block) {
-    const int q1 = min(q0 + rows_per_block, total);
-    if (tid < q1 - q0) {
-        const int q = q0 + tid;
-        const int s = seg_of(off, N, q);
-        const int *csb = W.cs_base + ((size_t)d * N + s) * El;
-        const int j = seg_of(csb, El, q);
-        src_row[tid] = W.base_x[((size_t)d * El + j) * N + s] + (q - csb[j]);
-        W.fab_dst_comb[(size_t)d * D.expert_cap + q] =
-            make_int2(s, W.comb_dst_off[(size_t)d * N + s] + (q - off[s]));
-    }
-    __syncthreads();
-    char *out = W.bufB + (size_t)d * D.bufB_rank_bytes + (size_t)q0 * D.Bc;
-    copy_rows_flat<kCopyThreads>(
-        q1 - q0, nvec, tid,
-        [&](int r) { return yd + (size_t)src_row[r] * D.Bc; },
-        [&](int r) { return out + (size_t)r * D.Bc; });
-    __syncthreads();                           // src_row is rewritten by the next chunk
+        const int q1 = min(q0 + rows_per_block, total);
+        if (tid < q1 - q0) {
+            const int q = q0 + tid;
+            const int s = seg_of(off, N, q);
+            const int *csb = W.cs_base + ((size_t)d * N + s) * El;
+            const int j = seg_of(csb, El, q);
+            src_row[tid] = W.base_x[((size_t)d * El + j) * N + s] + (q - csb[j]);
+            W.fab_dst_comb[(size_t)d * D.expert_cap + q] =
+                make_int2(s, W.comb_dst_off[(size_t)d * N + s] + (q - off[s]));
+        }
+        __syncthreads();
+        char *out = W.bufB + (size_t)d * D.bufB_rank_bytes + (size_t)q0 * D.Bc;
+        copy_rows_flat<kCopyThreads>(
+            q1 - q0, nvec, tid,
+            [&](int r) { return yd + (size_t)src_row[r] * D.Bc; },
+            [&](int r) { return out + (size_t)r * D.Bc; });
+        __syncthreads();                       // src_row is rewritten by the next chunk
     }
 }
 

@@ -303,6 +303,94 @@ def test_decode_with_practical_capacity():
     sh.close()
 
 
+# ------------------------------------------------------------------ limits, empty input, graph replay
+LIMIT_CASES = {
+    "max_ranks_experts_topk": lambda: wlmod.custom("limits", 64, 1024, 9, 64, 16, seed=41, ragged=True),
+    "max_experts_per_rank": lambda: wlmod.custom("el256", 4, 1024, 33, 64, 8, seed=42),
+    "min_hidden": lambda: wlmod.custom("h8", 4, 16, 40, 8, 2, seed=43, ragged=True),
+    "long_row": lambda: wlmod.custom("h32k", 2, 8, 12, 32768, 3, seed=44),
+}
+
+
+@pytest.mark.parametrize("name", list(LIMIT_CASES))
+def test_parity_at_the_limits_of_the_interface(name):
+    inp = wlmod.make_inputs(LIMIT_CASES[name]())
+    sh, _, _ = run_and_compare(inp)
+    sh.close()
+
+
+def test_no_tokens_anywhere_is_a_clean_no_op():
+    inp = wlmod.make_inputs(CASES["ragged_520"]())
+    inp.num_tokens[:] = 0
+    dev = harness.to_device(inp)
+    sh = harness.make_shuffle(inp)
+    try:
+        sh.expert_x.view(torch.int16).fill_(POISON)
+        sh.out.view(torch.int16).fill_(POISON)
+        sh.tokens_per_expert.fill_(-1)
+        harness.run_step(sh, dev)
+        torch.cuda.synchronize()
+        assert sh.status() == 0
+        assert (sh.tokens_per_expert.cpu().numpy() == 0).all()
+        tabs = sh.layout_tables()
+        assert (tabs["C"].cpu().numpy() == 0).all() and (tabs["expert_off"].cpu().numpy() == 0).all()
+        assert (bits(sh.expert_x) == POISON).all() and (bits(sh.out) == POISON).all()
+        dbg = sh.debug()
+        assert (dbg["arrive_disp"].cpu().numpy() == 0).all()
+        assert (dbg["expect_disp"].cpu().numpy() == 0).all()
+    finally:
+        sh.close()
+
+
+def test_hip_graph_replay_with_new_inputs():
+    """The five calls only enqueue kernels (no allocation, no reset, no synchronisation):
+    captured once, the graph is replayed on new routing and new hidden states written
+    into the same tensors, with eager work and synchronisation between replays, and every
+    replay matches the oracle."""
+    wl0 = wlmod.custom("graph0", 4, 32, 64, 520, 4, seed=51, expert="identity")
+    inputs = [wlmod.make_inputs(wlmod.custom(f"graph{i}", 4, 32, 64, 520, 4, seed=51 + i,
+                                             ragged=(i % 2 == 1), expert="identity"))
+              for i in range(4)]
+    dev = harness.to_device(inputs[0])
+    sh = harness.make_shuffle(inputs[0])
+    try:
+        harness.run_hot_path(sh, dev)              # warm-up outside capture
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            harness.run_hot_path(sh, dev)
+        for i, inp in enumerate(inputs):
+            fresh = harness.to_device(inp)
+            for k in ("x", "indices", "weights", "num_tokens"):
+                dev[k].copy_(fresh[k])
+            sh.out.view(torch.int16).fill_(POISON)
+            graph.replay()
+            torch.cuda.synchronize()
+            assert sh.status() == 0
+            ref = oracle_step(inp)
+            ob = bits(sh.out)
+            ex = bits(sh.expert_x[:, :ref.stride])
+            for d in range(4):
+                n = ref.expert_rows[d].shape[0]
+                assert (ex[d, :n] == ref.expert_rows[d]).all(), (i, d)
+            for s in range(4):
+                n = inp.num_tokens[s]
+                assert (ob[s, :n] == ref.out[s, :n]).all(), (i, s)
+                assert (ob[s, n:] == POISON).all()
+            # eager work between replays: a full eager step on the same context
+            eager = harness.run_hot_path(sh, dev)
+            torch.cuda.synchronize()
+            assert (bits(eager)[0, :inp.num_tokens[0]] == ref.out[0, :inp.num_tokens[0]]).all()
+    finally:
+        sh.close()
+
+
+def test_unordered_mode_with_e4m3_dispatch():
+    inp = wlmod.make_inputs(FP8_CASES["fp8_small"]())
+    sh, _, _ = run_and_compare(inp, unordered=True, zero_pad=True, align=4)
+    sh.close()
+
+
 # ------------------------------------------------------------------ failure handling
 def small_shuffle(spin_limit=0, **kw):
     inp = wlmod.make_inputs(CASES["ragged_520"]())

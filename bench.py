@@ -49,6 +49,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--unordered", action="store_true",
                     help="run the fabric with release/acquire counters (FL_FLAG_UNORDERED_FABRIC)")
+    ap.add_argument("--overlap", action="store_true",
+                    help="unordered fabric with send calls on a second stream: receivers poll the "
+                         "arrival counters while the fabric copy runs (reports the step time only)")
     ap.add_argument("--profile-steps", type=int, default=30)
     ap.add_argument("--counters", action="store_true",
                     help="short run for `rocprofv3 --pmc`: a few steps plus one plain 1 GiB copy "
@@ -80,7 +83,8 @@ def main():
         cf = None                       # skewed routing: size for the worst case
     elif big:
         cf = min(cf or 1.1, 1.1)        # 16 GB buffers at 1.1x the mean; the worst case would not fit
-    sh = harness.make_shuffle(inp, capacity_factor=cf, unordered_fabric=args.unordered)
+    sh = harness.make_shuffle(inp, capacity_factor=cf,
+                              unordered_fabric=args.unordered or args.overlap)
     ttot, D, P = stats["tokens_total"], stats["dedup_rows"], stats["pairs"]
     per_kernel, bytes_dispatch, bytes_combine = algorithmic_bytes(wl, ttot, D, P, sh.sizes)
     bytes_step = bytes_dispatch + bytes_combine
@@ -92,6 +96,32 @@ def main():
 
     def step():
         harness.run_hot_path(sh, dev, expert_y)
+
+    if args.overlap:
+        streams = (torch.cuda.Stream(), torch.cuda.Stream())
+        y = sh.expert_x if expert_y is None else expert_y
+
+        def ostep():
+            harness.run_step_two_streams(sh, dev, expert_y=y, streams=streams)
+
+        for _ in range(args.warmup):
+            ostep()
+        torch.cuda.synchronize()
+        assert sh.status() == 0
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            ostep()
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / args.steps
+        assert sh.status() == 0
+        print(json.dumps({"metric": "dispatch+combine achieved HBM GB/s, senders and receivers on "
+                                    "two streams (unordered fabric)",
+                          "value": round(bytes_step / (ms * 1e-3) / 1e9, 1), "unit": "GB/s",
+                          "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+                          "ms_per_step": round(ms, 4), "higher_is_better": True,
+                          "config": {"workload": wl.name, "fabric": "unordered, two streams"}}))
+        sh.close()
+        return
 
     if args.counters:
         for _ in range(3):

@@ -191,6 +191,7 @@ struct fl_moe_ctx {
     size_t workspace_bytes;
     const int32_t *indices = nullptr;
     const int32_t *num_tokens = nullptr;
+    int cu_count = 256;
     // profiling
     int profile = 0;
     hipEvent_t ev_start[kEventPool], ev_stop[kEventPool];
@@ -266,6 +267,13 @@ int fl_moe_create(const fl_moe_config *cfg, void *workspace, size_t workspace_by
     if (hipMemset(workspace, 0, small) != hipSuccess || hipDeviceSynchronize() != hipSuccess) {
         delete ctx;
         return FL_ERR_HIP;
+    }
+    {
+        int dev = 0, cus = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess &&
+            cus > 0)
+            ctx->cu_count = cus;
     }
     for (int i = 0; i < kEventPool; ++i) {
         if (hipEventCreate(&ctx->ev_start[i]) != hipSuccess ||
@@ -377,7 +385,11 @@ int fl_moe_dispatch_recv(fl_moe_ctx *ctx, int rb, int rc, void *expert_x, float 
         return FL_ERR_ALIGNMENT;
     hipStream_t st = (hipStream_t)stream;
     const int rbk = rows_per_block(D.Bw, D.tune_rows);
-    unsigned gx = capped_grid((D.recv_cap + rbk - 1) / rbk, rc, kMaxRowBlocks);
+    // In unordered mode the receivers may be polling while senders still need
+    // somewhere to run: they take at most half of the resident-block slots.
+    const bool unordered = D.flags & FL_FLAG_UNORDERED_FABRIC;
+    unsigned gx = capped_grid((D.recv_cap + rbk - 1) / rbk, rc,
+                              unordered ? (long long)ctx->cu_count * 4 : kMaxRowBlocks);
     if (gx < (unsigned)D.El) gx = D.El;      // the first El-1 blocks also clear padding rows
     {
         LaunchTimer t(ctx, KID_DISPATCH_UNPACK, st);
@@ -440,8 +452,9 @@ int fl_moe_combine_reduce(fl_moe_ctx *ctx, int rb, int rc, const float *weights,
         int nt = (int)((D.Bc / 16 + kWave - 1) / kWave * kWave);
         if (nt > kReduceMaxThreads) nt = kReduceMaxThreads;
         if (nt < 2 * kWave) nt = 2 * kWave;      // wave 0 waits, wave 1 fetches positions and weights
-        if (D.flags & FL_FLAG_UNORDERED_FABRIC)
-            combine_reduce_kernel<true><<<dim3(D.T, rc), dim3(nt), 0, st>>>(
+        if (D.flags & FL_FLAG_UNORDERED_FABRIC)  // polling receivers: at most half of the machine
+            combine_reduce_kernel<true><<<dim3(capped_grid(D.T, rc, (long long)ctx->cu_count * 1024 / nt), rc),
+                                          dim3(nt), 0, st>>>(
                 D, ctx->W, rb, weights, (char *)out, ctx->num_tokens);
         else
             combine_reduce_kernel<false><<<dim3(D.T, rc), dim3(nt), 0, st>>>(

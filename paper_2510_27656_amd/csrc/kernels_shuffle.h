@@ -430,11 +430,13 @@ template <bool FENCED>
 __global__ __launch_bounds__(kReduceMaxThreads, 7) void combine_reduce_kernel(
     Dims D, Tables W, int rank_begin, const float *__restrict__ weights, char *__restrict__ out,
     const int *__restrict__ num_tokens) {
-    const int s = rank_begin + blockIdx.y, t = blockIdx.x, tid = threadIdx.x, N = D.N, K = D.K;
+    const int s = rank_begin + blockIdx.y, tid = threadIdx.x, N = D.N, K = D.K;
     __shared__ int pos[FL_MAX_TOPK];
     __shared__ float w[FL_MAX_TOPK];
     __shared__ int timed_out;
-    if (!W.plan_ok[s] || t >= num_tokens[s]) return;
+    if (!W.plan_ok[s]) return;
+    const int Ts = num_tokens[s];
+    if ((int)blockIdx.x >= Ts) return;
     if (tid == 0) timed_out = 0;
     __syncthreads();
     if (tid < kWave) {
@@ -443,21 +445,26 @@ __global__ __launch_bounds__(kReduceMaxThreads, 7) void combine_reduce_kernel(
             if (tid == 0) { timed_out = 1; latch_status(W.status, FL_STATUS_TIMEOUT); }
         }
         acquire_payload<FENCED>();
-    } else if (tid < kWave + K) {
-        const int k = tid - kWave;
-        pos[k] = W.comb_pos[((size_t)s * D.T + t) * K + k];
-        w[k] = weights[((size_t)s * D.T + t) * K + k];
     }
-    __syncthreads();
-    if (timed_out) return;
     const char *recv = W.bufA + (size_t)s * D.bufA_rank_bytes;
-    v4u *o = (v4u *)(out + ((size_t)s * D.T + t) * D.Bc);
     const int nvec = (int)(D.Bc / 16);
     const int kt = D.tune_reduce ? D.tune_reduce : K;
-    if (kt >= 8) reduce_row<8>(recv, pos, w, K, D.Bc, nvec, o, tid);
-    else if (kt >= 4) reduce_row<4>(recv, pos, w, K, D.Bc, nvec, o, tid);
-    else if (kt >= 2) reduce_row<2>(recv, pos, w, K, D.Bc, nvec, o, tid);
-    else reduce_row<1>(recv, pos, w, K, D.Bc, nvec, o, tid);
+    // one token per block unless the grid was made smaller than the token count
+    for (int t = blockIdx.x; t < Ts; t += gridDim.x) {
+        if (tid >= kWave && tid < kWave + K) {
+            const int k = tid - kWave;
+            pos[k] = W.comb_pos[((size_t)s * D.T + t) * K + k];
+            w[k] = weights[((size_t)s * D.T + t) * K + k];
+        }
+        __syncthreads();
+        if (timed_out) return;
+        v4u *o = (v4u *)(out + ((size_t)s * D.T + t) * D.Bc);
+        if (kt >= 8) reduce_row<8>(recv, pos, w, K, D.Bc, nvec, o, tid);
+        else if (kt >= 4) reduce_row<4>(recv, pos, w, K, D.Bc, nvec, o, tid);
+        else if (kt >= 2) reduce_row<2>(recv, pos, w, K, D.Bc, nvec, o, tid);
+        else reduce_row<1>(recv, pos, w, K, D.Bc, nvec, o, tid);
+        __syncthreads();                       // positions and weights are rewritten for the next token
+    }
 }
 
 // ------------------------------------------------------------------ diagnostic copy

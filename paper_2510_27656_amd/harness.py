@@ -89,3 +89,41 @@ def run_hot_path(sh: flmoe.MoEShuffle, dev, expert_y=None):
     sh.dispatch_recv()
     sh.combine_send(sh.expert_x if expert_y is None else expert_y)
     return sh.combine_reduce(dev["weights"])
+
+
+def run_step_two_streams(sh: flmoe.MoEShuffle, dev, identity=False, send_order=None, expert_y=None,
+                         streams=None):
+    """One step with senders and receivers overlapping in time (needs a context created
+    with unordered_fabric=True).  Receive kernels are enqueued on stream A right after
+    the layout, send kernels on stream B: the receivers poll the arrival counters while
+    the fabric copy is still running (or has not started).  Events order only what the
+    re-use of the two staging buffers needs.  send_order: list of (rank_begin,
+    rank_count) launches for the send calls, default one launch for all ranks."""
+    N = sh.N
+    a, b = streams or (torch.cuda.Stream(), torch.cuda.Stream())
+    cur = torch.cuda.current_stream()
+    a.wait_stream(cur)
+    b.wait_stream(cur)
+    order = send_order or [(0, N)]
+    with torch.cuda.stream(a):
+        sh.layout(dev["indices"], dev["num_tokens"])
+        planned = torch.cuda.Event()
+        planned.record(a)
+    with torch.cuda.stream(b):
+        b.wait_event(planned)
+        for rg in order:
+            sh.dispatch_send(dev["x"], rg)
+    with torch.cuda.stream(a):
+        sh.dispatch_recv()                       # polls per source while stream B delivers
+        y = expert_y if expert_y is not None else expert_stage(sh, dev["gain"], identity)
+        unpacked = torch.cuda.Event()
+        unpacked.record(a)
+    with torch.cuda.stream(b):
+        b.wait_event(unpacked)                   # the receive buffer becomes the combine send buffer
+        for rg in reversed(order):
+            sh.combine_send(y, rg)
+    with torch.cuda.stream(a):
+        out = sh.combine_reduce(dev["weights"])  # polls while the replies are still arriving
+    cur.wait_stream(a)
+    cur.wait_stream(b)
+    return out

@@ -391,6 +391,47 @@ def test_unordered_mode_with_e4m3_dispatch():
     sh.close()
 
 
+# ------------------------------------------------------------------ senders and receivers overlapping in time
+@pytest.mark.parametrize("name,shuffled", [("ragged_520", False), ("ragged_520", True),
+                                           ("overlap_7168", False), ("overlap_7168", True),
+                                           ("dsv3_decode", False)])
+def test_unordered_fabric_with_concurrent_send_and_receive(name, shuffled):
+    if name == "overlap_7168":
+        wl = wlmod.custom("overlap_7168", 8, 64, 128, 7168, 8, seed=61)
+    elif name == "dsv3_decode":
+        wl = wlmod.WORKLOADS[name]
+    else:
+        wl = CASES[name]()
+    inp = wlmod.make_inputs(wl)
+    N = wl.n_ranks
+    ref = oracle_step(inp)
+    dev = harness.to_device(inp)
+    sh = harness.make_shuffle(inp, unordered_fabric=True, capacity_factor=2.0 if N >= 8 else None)
+    try:
+        order = None
+        if shuffled:      # one launch per sender, in a seeded random order
+            perm = np.random.default_rng(5).permutation(N)
+            order = [(int(r), 1) for r in perm]
+        for rep in range(3):
+            sh.out.view(torch.int16).fill_(POISON)
+            out = harness.run_step_two_streams(sh, dev, wl.expert == "identity", order)
+            torch.cuda.synchronize()
+            assert sh.status() == 0, "a receiver gave up waiting"
+            ex = bits(sh.expert_x[:, :ref.stride])
+            ob = bits(out)
+            for d in range(N):
+                n = ref.expert_rows[d].shape[0]
+                assert (ex[d, :n] == ref.expert_rows[d]).all(), (rep, d)
+            for s in range(N):
+                n = inp.num_tokens[s]
+                assert (ob[s, :n] == ref.out[s, :n]).all(), (rep, s)
+        dbg = sh.debug()
+        assert (dbg["arrive_disp"] == dbg["expect_disp"]).all()
+        assert (dbg["arrive_comb"] == dbg["expect_comb"]).all()
+    finally:
+        sh.close()
+
+
 # ------------------------------------------------------------------ failure handling
 def small_shuffle(spin_limit=0, **kw):
     inp = wlmod.make_inputs(CASES["ragged_520"]())

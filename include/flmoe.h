@@ -209,7 +209,8 @@ int fl_moe_debug_views(fl_moe_ctx *ctx, fl_moe_debug_view *out /*host*/);
  * per thread in combine_reduce (0 = all K, at most 8), knob 2 = waves per row in
  * the fabric kernel (0 = chosen from the row size, else 1..16), knob 3 =
  * workgroups per token in the pack kernel (0 = chosen from the row size, at
- * most 16). */
+ * most 16), knob 4 = size in MiB of the receive buffers a fabric launch may
+ * write above which it uses streaming instead of cached stores (default 1024). */
 int fl_moe_debug_tune(fl_moe_ctx *ctx, int knob, int value);
 
 /* Diagnostic: plain linear device copy of `bytes` bytes with 16-byte accesses

@@ -102,6 +102,7 @@ int resolve(const fl_moe_config *c, Dims *D) {
     D->tune_reduce = 0;
     D->tune_waves = 0;
     D->tune_slices = 0;
+    D->tune_stream_mb = 1024;
     return FL_OK;
 }
 
@@ -366,10 +367,13 @@ int fl_moe_dispatch_send(fl_moe_ctx *ctx, int rb, int rc, const void *x, void *s
                                      A.waves_per_row);
     {
         LaunchTimer t(ctx, KID_DISPATCH_FABRIC, st);
+        const bool streaming = (long long)rc * D.send_cap * D.Bw > ((long long)D.tune_stream_mb << 20);
         if (D.flags & FL_FLAG_UNORDERED_FABRIC)
-            fabric_copy_kernel<true, 0><<<dim3(gx, rc), dim3(kCopyThreads), 0, st>>>(D, W, A, rb);
+            fabric_copy_kernel<true, 0, true><<<dim3(gx, rc), dim3(kCopyThreads), 0, st>>>(D, W, A, rb);
+        else if (streaming)
+            fabric_copy_kernel<false, 0, true><<<dim3(gx, rc), dim3(kCopyThreads), 0, st>>>(D, W, A, rb);
         else
-            fabric_copy_kernel<false, 0><<<dim3(gx, rc), dim3(kCopyThreads), 0, st>>>(D, W, A, rb);
+            fabric_copy_kernel<false, 0, false><<<dim3(gx, rc), dim3(kCopyThreads), 0, st>>>(D, W, A, rb);
     }
     return launch_status();
 }
@@ -431,10 +435,14 @@ int fl_moe_combine_send(fl_moe_ctx *ctx, int rb, int rc, const void *expert_y, v
                                       kMaxFabricBlocks, A.waves_per_row);
     {
         LaunchTimer t(ctx, KID_COMBINE_FABRIC, st);
+        // what the launch can write: every rank gets back at most T*K rows
+        const bool streaming = (long long)D.N * D.T * D.K * D.Bc > ((long long)D.tune_stream_mb << 20);
         if (D.flags & FL_FLAG_UNORDERED_FABRIC)
-            fabric_copy_kernel<true, 1><<<dim3(gxf, rc), dim3(kCopyThreads), 0, st>>>(D, W, A, rb);
+            fabric_copy_kernel<true, 1, true><<<dim3(gxf, rc), dim3(kCopyThreads), 0, st>>>(D, W, A, rb);
+        else if (streaming)
+            fabric_copy_kernel<false, 1, true><<<dim3(gxf, rc), dim3(kCopyThreads), 0, st>>>(D, W, A, rb);
         else
-            fabric_copy_kernel<false, 1><<<dim3(gxf, rc), dim3(kCopyThreads), 0, st>>>(D, W, A, rb);
+            fabric_copy_kernel<false, 1, false><<<dim3(gxf, rc), dim3(kCopyThreads), 0, st>>>(D, W, A, rb);
     }
     return launch_status();
 }
@@ -504,6 +512,7 @@ int fl_moe_debug_tune(fl_moe_ctx *ctx, int knob, int value) {
     switch (knob) {
         case 0: if (value > kMaxRowsPerBlock) return FL_ERR_INVALID_ARG; ctx->D.tune_rows = value; break;
         case 2: ctx->D.tune_waves = value; break;
+        case 4: ctx->D.tune_stream_mb = value; break;
         case 3: if (value > 16) return FL_ERR_INVALID_ARG; ctx->D.tune_slices = value; break;
         case 1: if (value > 8) return FL_ERR_INVALID_ARG; ctx->D.tune_reduce = value; break;
         default: return FL_ERR_INVALID_ARG;

@@ -193,7 +193,7 @@ struct FabricArgs {
     int waves_per_row;    // 1..16
 };
 
-template <bool FENCED, int PHASE>   // PHASE only names the launch: 0 dispatch, 1 combine
+template <bool FENCED, int PHASE, bool STREAMING>   // PHASE only names the launch: 0 dispatch, 1 combine
 __global__ __launch_bounds__(kCopyThreads) void fabric_copy_kernel(Dims D, Tables W,
                                                                    FabricArgs A, int rank_begin) {
     const int s = rank_begin + blockIdx.y, N = D.N;
@@ -222,14 +222,14 @@ __global__ __launch_bounds__(kCopyThreads) void fabric_copy_kernel(Dims D, Table
                 if (b + j * step < nvec) v[j] = ld_stream(src + b + j * step);
 #pragma unroll
             for (int j = 0; j < 4; ++j)
-                if (b + j * step < nvec) st_payload<FENCED>(dst + b + j * step, v[j]);
+                if (b + j * step < nvec) st_payload<FENCED, STREAMING>(dst + b + j * step, v[j]);
         }
         if (A.src_meta && sub == 0) {          // the sidecar travels with the row
             const int mv = D.KM / 4;
             const v4u *ms =
                 (const v4u *)(A.src_meta + (size_t)s * A.src_meta_rank_stride) + (size_t)i * mv;
             v4u *md = (v4u *)(A.dst_meta + (size_t)t.x * A.dst_meta_rank_stride) + (size_t)t.y * mv;
-            if (lane < mv) st_payload<FENCED>(md + lane, ms[lane]);
+            if (lane < mv) st_payload<FENCED, STREAMING>(md + lane, ms[lane]);
         }
         // units this wave delivered: vectors v < nvec with (v / 64) % G == sub
         const int full = nvec / step, rem = nvec - full * step;

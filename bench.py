@@ -52,7 +52,7 @@ def main():
     ap.add_argument("--overlap", action="store_true",
                     help="unordered fabric with send calls on a second stream: receivers poll the "
                          "arrival counters while the fabric copy runs (reports the step time only)")
-    ap.add_argument("--profile-steps", type=int, default=30)
+    ap.add_argument("--profile-steps", type=int, default=200)
     ap.add_argument("--counters", action="store_true",
                     help="short run for `rocprofv3 --pmc`: a few steps plus one plain 1 GiB copy "
                          "of known size to calibrate the byte counters; no timing output")
@@ -159,8 +159,16 @@ def main():
         sh.combine_send(sh.expert_x if expert_y is None else expert_y); ev[i][4].record()
         sh.combine_reduce(dev["weights"]); ev[i][5].record()
     torch.cuda.synchronize()
-    call_us = {c: float(np.median([ev[i][j].elapsed_time(ev[i][j + 1]) for i in range(args.profile_steps)])) * 1e3
-               for j, c in enumerate(calls)}
+    per_call = {c: np.array([ev[i][j].elapsed_time(ev[i][j + 1]) for i in range(args.profile_steps)]) * 1e3
+                for j, c in enumerate(calls)}
+    call_us = {c: float(np.median(v)) for c, v in per_call.items()}
+    disp = per_call["layout"] + per_call["dispatch_send"] + per_call["dispatch_recv"]
+    comb = per_call["combine_send"] + per_call["combine_reduce"]
+
+    def dist(v):      # the paper's latency figures show mean and p01..p99
+        return {"mean": round(float(v.mean()), 1), "p01": round(float(np.percentile(v, 1)), 1),
+                "p50": round(float(np.percentile(v, 50)), 1), "p99": round(float(np.percentile(v, 99)), 1)}
+    latency_us = {"dispatch": dist(disp), "combine": dist(comb), "samples": args.profile_steps}
     dispatch_us = call_us["layout"] + call_us["dispatch_send"] + call_us["dispatch_recv"]
     combine_us = call_us["combine_send"] + call_us["combine_reduce"]
 
@@ -239,6 +247,7 @@ def main():
         "cold_gbps": round(bytes_step / (cold_us * 1e-6) / 1e9, 1),
         "copy_ceiling_gbps": round(copy_gbps, 1),
         "frac_of_copy_ceiling": round(value / copy_gbps, 4),
+        "latency_us": latency_us,
         "call_us": {k: round(v, 1) for k, v in call_us.items()},
         "kernel_us": {k: round(v, 2) for k, v in kern_us.items()},
         "kernel_gbps": {k: round(per_kernel[k] / (kern_us[k] * 1e-6) / 1e9, 1)

@@ -5,8 +5,8 @@
  * simulated ranks; the "fabric" between ranks is a device-side copy whose
  * completion is signalled only through per-source arrival counters (the
  * paper's ImmCounter idea, section TransferEngine / Completion Notification:
- * a counter is bumped once a payload is fully delivered, and nothing else
- * orders transfers).
+ * a counter advances as payload is delivered, a receiver compares it with what
+ * the exchanged counts tell it to expect, and nothing else orders transfers).
  *
  * Problem statement (section MoE Dispatch/Combine, Architecture): N ranks host E
  * experts (expert e lives on rank e / (E/N)); every rank holds up to T tokens of
@@ -26,6 +26,10 @@
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  The
  *     five shuffle calls only enqueue kernels: they never synchronise, never
  *     allocate, and can be captured in a HIP graph.
+ *   - One step = the five calls once each, in the order layout, dispatch_send,
+ *     dispatch_recv, combine_send, combine_reduce, with every rank of the group
+ *     taking part in each (in one launch or several).  A receive call whose
+ *     senders never ran ends with FL_STATUS_TIMEOUT, not with a hang.
  *   - Return value: FL_OK or a negative FL_ERR_* for errors the host can see
  *     (nothing is enqueued then).  Errors found on the device (bad expert id,
  *     capacity overflow, arrival time-out) make the affected step a no-op on every

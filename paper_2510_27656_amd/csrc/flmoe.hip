@@ -385,7 +385,7 @@ int fl_moe_dispatch_recv(fl_moe_ctx *ctx, int rb, int rc, void *expert_x, float 
     const Dims &D = ctx->D;
     if (!expert_x || !tokens_per_expert) return FL_ERR_INVALID_ARG;
     if ((D.scales_per_row != 0) != (expert_scales != nullptr)) return FL_ERR_INVALID_ARG;
-    if (!aligned16(expert_x) || ((uintptr_t)expert_scales & 3) || ((uintptr_t)tokens_per_expert & 3))
+    if (!aligned16(expert_x) || !aligned16(expert_scales) || ((uintptr_t)tokens_per_expert & 3))
         return FL_ERR_ALIGNMENT;
     hipStream_t st = (hipStream_t)stream;
     const int rbk = rows_per_block(D.Bw, D.tune_rows);

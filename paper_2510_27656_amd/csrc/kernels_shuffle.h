@@ -273,12 +273,16 @@ __global__ __launch_bounds__(kCopyThreads) void dispatch_unpack_kernel(
             for (long long v = tid; v < (hi - lo) * D.scales_per_row; v += kCopyThreads) sp[v] = 0.f;
         }
     }
+    // grids are sized from capacities: blocks beyond the rows in use leave at once
+    const int total = W.recv_off[(size_t)d * (N + 1) + N];
+    if ((int)blockIdx.x * rows_per_block >= total) return;
     if (tid <= N) off[tid] = W.recv_off[(size_t)d * (N + 1) + tid];
     if (tid == 0) timed_out = 0;
     __syncthreads();
-    const int total = off[N];
     const char *recv = W.bufB + (size_t)d * D.bufB_rank_bytes;
     const int nvec = (int)(D.Be / 16);
+    const bool scales_as_vectors = D.scales_per_row > 0 && D.scales_per_row % 4 == 0;
+    const int rowvec = nvec + (scales_as_vectors ? D.scales_per_row / 4 : 0);
     // capacities are upper bounds, so the grid may be smaller than the rows in use
     for (int r0 = blockIdx.x * rows_per_block; r0 < total; r0 += gridDim.x * rows_per_block) {
         const int r1 = min(r0 + rows_per_block, total);
@@ -307,7 +311,9 @@ __global__ __launch_bounds__(kCopyThreads) void dispatch_unpack_kernel(
             dst_cnt[tid] = n;
         }
         __syncthreads();
-        const int chunk = (r1 - r0) * nvec;
+        // e4m3: when the scales of a row are a whole number of 16-byte vectors they are
+        // moved by the same loop (the vectors after the code bytes go to expert_scales)
+        const int chunk = (r1 - r0) * rowvec;
         for (int b = tid; b < chunk; b += 4 * kCopyThreads) {
             v4u val[4];
             int row[4], col[4];
@@ -315,8 +321,8 @@ __global__ __launch_bounds__(kCopyThreads) void dispatch_unpack_kernel(
             for (int i = 0; i < 4; ++i) {
                 const int v = b + i * kCopyThreads;
                 if (v < chunk) {
-                    row[i] = v / nvec;
-                    col[i] = v - row[i] * nvec;
+                    row[i] = v / rowvec;
+                    col[i] = v - row[i] * rowvec;
                     val[i] = ld_stream((const v4u *)(recv + (size_t)(r0 + row[i]) * D.Bw) + col[i]);
                 }
             }
@@ -325,12 +331,18 @@ __global__ __launch_bounds__(kCopyThreads) void dispatch_unpack_kernel(
                 const int v = b + i * kCopyThreads;
                 if (v < chunk) {
                     const int n = dst_cnt[row[i]];
-                    for (int j = 0; j < n; ++j)
-                        st_stream((v4u *)(xd + (size_t)dst_rows[row[i]][j] * D.Be) + col[i], val[i]);
+                    for (int j = 0; j < n; ++j) {
+                        const size_t dr = (size_t)dst_rows[row[i]][j];
+                        if (col[i] < nvec)
+                            st_stream((v4u *)(xd + dr * D.Be) + col[i], val[i]);
+                        else
+                            st_stream((v4u *)(expert_scales + ((size_t)d * D.expert_cap + dr) *
+                                                                  D.scales_per_row) + (col[i] - nvec), val[i]);
+                    }
                 }
             }
         }
-        if (D.scales_per_row) {                // e4m3: the scales follow the bytes on the wire
+        if (D.scales_per_row && !scales_as_vectors) {   // odd scale counts: element by element
             for (int r = r0; r < r1; ++r) {
                 const int n = dst_cnt[r - r0];
                 const int *dr = dst_rows[r - r0];
@@ -357,9 +369,11 @@ __global__ __launch_bounds__(kCopyThreads) void combine_pack_kernel(
     __shared__ int off[FL_MAX_RANKS + 1];
     __shared__ int src_row[kMaxRowsPerBlock];
     if (!W.plan_ok[d]) return;
+    // grids are sized from capacities: blocks beyond the rows in use leave at once
+    const int total = W.cs_off[(size_t)d * (N + 1) + N];
+    if ((int)blockIdx.x * rows_per_block >= total) return;
     if (tid <= N) off[tid] = W.cs_off[(size_t)d * (N + 1) + tid];
     __syncthreads();
-    const int total = off[N];
     const int nvec = (int)(D.Bc / 16);
     const char *yd = expert_y + (size_t)d * D.expert_cap * D.Bc;
     // capacities are upper bounds, so the grid may be smaller than the rows in use

@@ -343,9 +343,9 @@ int fl_moe_dispatch_send(fl_moe_ctx *ctx, int rb, int rc, const void *x, void *s
     const Tables &W = ctx->W;
     if (D.dtype == FL_DTYPE_E4M3_BLOCK128) {
         LaunchTimer t(ctx, KID_DISPATCH_PACK_E4M3, st);
-        const int per_block = kPackThreads / kQuantLanes;        // quantisation blocks per workgroup
+        const int per_block = kQuantThreads / kQuantLanes;       // quantisation blocks per workgroup
         const int slices = (D.scales_per_row + per_block - 1) / per_block;
-        dispatch_pack_e4m3_kernel<<<dim3((unsigned)D.T * slices, rc), dim3(kPackThreads), 0, st>>>(
+        dispatch_pack_e4m3_kernel<<<dim3((unsigned)D.T * slices, rc), dim3(kQuantThreads), 0, st>>>(
             D, W, rb, (const char *)x, ctx->indices, ctx->num_tokens, slices);
     } else {
         LaunchTimer t(ctx, KID_DISPATCH_PACK, st);

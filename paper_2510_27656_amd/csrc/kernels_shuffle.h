@@ -96,11 +96,12 @@ __device__ inline unsigned e4m3_encode(float v) {
 }
 
 constexpr int kQuantLanes = 8;     // lanes per 128-element block: 16 bf16 values each
+constexpr int kQuantThreads = 256; // 32 quantisation blocks per workgroup
 
-// One block of kPackThreads threads takes 16 quantisation blocks of one token;
+// One block of kQuantThreads threads takes 32 quantisation blocks of one token;
 // every lane loads 32 bytes, takes part in an 8-lane max, and stores 16 bytes of
 // e4m3 per destination copy; the group's first lane stores the scale.
-__global__ __launch_bounds__(kPackThreads) void dispatch_pack_e4m3_kernel(
+__global__ __launch_bounds__(kQuantThreads) void dispatch_pack_e4m3_kernel(
     Dims D, Tables W, int rank_begin, const char *__restrict__ x,
     const int *__restrict__ indices, const int *__restrict__ num_tokens, int slices) {
     const int s = rank_begin + blockIdx.y, t = blockIdx.x / slices, slice = blockIdx.x % slices;
@@ -131,7 +132,7 @@ __global__ __launch_bounds__(kPackThreads) void dispatch_pack_e4m3_kernel(
         W.fab_dst_disp[(size_t)s * D.send_cap + my_row] = make_int2(my_d, my_row + delta);
     }
     const int nblk = D.scales_per_row;                          // 128-element blocks in the row
-    const int blk = slice * (kPackThreads / kQuantLanes) + tid / kQuantLanes;
+    const int blk = slice * (kQuantThreads / kQuantLanes) + tid / kQuantLanes;
     const int sub = tid % kQuantLanes;
     const bool live = blk < nblk;
     v4u in0 = {0u, 0u, 0u, 0u}, in1 = {0u, 0u, 0u, 0u};
@@ -157,14 +158,27 @@ __global__ __launch_bounds__(kPackThreads) void dispatch_pack_e4m3_kernel(
                (e4m3_encode(__fdiv_rn(f[4 * i + 2], scale)) << 16) |
                (e4m3_encode(__fdiv_rn(f[4 * i + 3], scale)) << 24);
     const v4u out = {q[0], q[1], q[2], q[3]};
-    if (!live) return;
+    // the block's scales are gathered in LDS and stored as 16-byte vectors when the
+    // row's scale count allows it (scattered 4-byte stores are partial-line writes)
+    __shared__ __align__(16) float s_scale[kQuantThreads / kQuantLanes];
+    const bool scale_vectors = nblk % 4 == 0;
+    if (scale_vectors) {
+        if (live && sub == 0) s_scale[tid / kQuantLanes] = scale;
+        __syncthreads();
+    }
+    const int blk0 = slice * (kQuantThreads / kQuantLanes);
+    const int nsv = (min(nblk - blk0, kQuantThreads / kQuantLanes)) / 4;   // scale vectors of this block
     char *sendbuf = W.bufA + (size_t)s * D.bufA_rank_bytes;
     for (int k = 0; k < K; ++k) {
         const int row = s_row[k];
         if (row < 0) continue;
         char *dst = sendbuf + (size_t)row * D.Bw;
-        st_stream((v4u *)dst + (size_t)blk * kQuantLanes + sub, out);
-        if (sub == 0) ((float *)(dst + D.Be))[blk] = scale;
+        if (live) st_stream((v4u *)dst + (size_t)blk * kQuantLanes + sub, out);
+        if (scale_vectors) {
+            if (tid < nsv) st_stream((v4u *)(dst + D.Be) + blk0 / 4 + tid, ((const v4u *)s_scale)[tid]);
+        } else if (live && sub == 0) {
+            ((float *)(dst + D.Be))[blk] = scale;
+        }
     }
 }
 

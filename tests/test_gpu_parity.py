@@ -319,6 +319,28 @@ def test_parity_at_the_limits_of_the_interface(name):
     sh.close()
 
 
+def test_parity_random_shapes():
+    """Forty seeded random shapes: ranks, experts per rank, top-k, hidden size (any
+    multiple of 8), ragged token counts, padding, zero fill, fabric mode, capacity."""
+    rng = np.random.default_rng(2024)
+    for trial in range(40):
+        N = int(rng.choice([1, 2, 3, 4, 6, 8, 16]))
+        El = int(rng.choice([1, 2, 3, 4, 8, 16]))
+        E = N * El
+        K = int(rng.integers(1, min(E, 9) + 1))
+        T = int(rng.integers(1, 200))
+        fp8 = trial % 5 == 4
+        H = int(rng.integers(1, 9)) * 128 if fp8 else int(rng.integers(1, 300)) * 8
+        wl = wlmod.custom(f"rnd{trial}", N, E, T, H, K, seed=3000 + trial, ragged=bool(trial % 2),
+                          dispatch_dtype="e4m3" if fp8 else "bf16",
+                          expert="identity" if trial % 7 == 0 else "scale")
+        inp = wlmod.make_inputs(wl)
+        print(f"trial {trial}: N={N} El={El} K={K} T={T} H={H} fp8={fp8}", flush=True)
+        sh, _, _ = run_and_compare(inp, align=int(rng.choice([1, 1, 4, 7])), zero_pad=True,
+                                   unordered=bool(trial % 3 == 0))
+        sh.close()
+
+
 def test_no_tokens_anywhere_is_a_clean_no_op():
     inp = wlmod.make_inputs(CASES["ragged_520"]())
     inp.num_tokens[:] = 0

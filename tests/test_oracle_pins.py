@@ -552,3 +552,25 @@ def test_sampled_combine_helper_equals_full_path():
     orc.scale_rows(y, np.ascontiguousarray(inp.expert_gain[idx.reshape(-1)]))
     got = orc.combine_sampled(32, 4, idx, inp.weights[ss, tt], y)
     assert (got == ref.out[ss, tt]).all()
+
+
+def test_random_shapes_against_brute_force_sort():
+    """Many small random shapes (ranks, experts per rank, top-k, ragged token counts,
+    alignment): slots and rows equal the brute-force stable sort."""
+    rng = np.random.default_rng(123)
+    for trial in range(60):
+        N = int(rng.choice([1, 2, 3, 4, 5, 8]))
+        El = int(rng.choice([1, 2, 3, 4, 8]))
+        E = N * El
+        K = int(rng.integers(1, min(E, 6) + 1))
+        T = int(rng.integers(1, 24))
+        align = int(rng.choice([1, 2, 5, 8]))
+        inp = small_case(N, E, T, K, 8, seed=1000 + trial, ragged=bool(trial % 2))
+        lay = orc.layout(N, E, K, inp.num_tokens, inp.indices, align)
+        slot, rows = brute_force_layout(N, E, K, inp.num_tokens, inp.indices, align)
+        assert (lay.slot == slot).all(), (trial, N, El, K, T, align)
+        for d in range(N):
+            got = orc.dispatch_rank(d, N, E, K, inp.num_tokens, inp.indices, inp.x, align, zero_pad=True)
+            assert got.shape[0] == len(rows[d])
+            for r, st in enumerate(rows[d]):
+                assert (got[r] == (0 if st is None else inp.x[st[0], st[1]])).all()

@@ -52,6 +52,9 @@ def main():
     ap.add_argument("--overlap", action="store_true",
                     help="unordered fabric with send calls on a second stream: receivers poll the "
                          "arrival counters while the fabric copy runs (reports the step time only)")
+    ap.add_argument("--private-rows", type=int, default=0,
+                    help="first rows per (source, destination) sent to private slots in a scatter "
+                         "of their own (ablation of section Ablation: Private Buffer Size)")
     ap.add_argument("--profile-steps", type=int, default=200)
     ap.add_argument("--counters", action="store_true",
                     help="short run for `rocprofv3 --pmc`: a few steps plus one plain 1 GiB copy "
@@ -84,7 +87,8 @@ def main():
     elif big:
         cf = min(cf or 1.1, 1.1)        # 16 GB buffers at 1.1x the mean; the worst case would not fit
     sh = harness.make_shuffle(inp, capacity_factor=cf,
-                              unordered_fabric=args.unordered or args.overlap)
+                              unordered_fabric=args.unordered or args.overlap,
+                              max_private_rows=args.private_rows)
     ttot, D, P = stats["tokens_total"], stats["dedup_rows"], stats["pairs"]
     per_kernel, bytes_dispatch, bytes_combine = algorithmic_bytes(wl, ttot, D, P, sh.sizes)
     bytes_step = bytes_dispatch + bytes_combine
@@ -237,7 +241,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": wl.name, "ranks_simulated": wl.n_ranks, "experts": wl.n_experts,
                    "tokens_per_rank": wl.tokens, "hidden": wl.hidden, "top_k": wl.top_k,
-                   "dedup_rows": D, "pairs": P, "capacity_factor": cf, "fabric": "unordered (release/acquire)" if args.unordered else "stream-ordered",
+                   "dedup_rows": D, "pairs": P, "capacity_factor": cf, "private_rows": int(sh.sizes.private_rows), "fabric": "unordered (release/acquire)" if args.unordered else "stream-ordered",
                    "expert_stage": "identity (expert_y aliases expert_x)" if expert_y is None
                    else "none in the timed path (resident bf16 expert_y)"},
         "frac_of_hbm_peak": round(value / HBM_PEAK_GBPS, 4),

@@ -96,6 +96,15 @@ typedef struct fl_moe_config {
     int64_t expert_capacity_rows; /* per rank: rows of its expert-major layout, padding
                                      included; 0 = N*T*min(K, E/N) + padding              */
     int64_t spin_limit;     /* polls of an arrival counter before FL_STATUS_TIMEOUT; 0 = default */
+    int32_t max_private_rows; /* P: the first P rows a source sends to a destination go to fixed
+                               private slots at the head of the destination's receive buffer, in a
+                               scatter of their own that needs no exchanged counts; only the rows
+                               beyond P are packed into the shared contiguous range (section
+                               Dispatch, figure "Dispatch into private and contiguous buffers";
+                               section Ablation: Private Buffer Size).  0 = one scatter into the
+                               shared range; values above T act as T.  The receive buffer grows by
+                               N*P rows per rank; recv_capacity_rows bounds the shared range only. */
+    int32_t reserved;       /* must be 0 */
 } fl_moe_config;
 
 typedef struct fl_moe_sizes {
@@ -109,6 +118,9 @@ typedef struct fl_moe_sizes {
     int64_t expert_x_row_bytes;   /* 2*H or H                                             */
     int64_t scales_per_row;       /* 0 or H/128                                           */
     int64_t combine_row_bytes;    /* 2*H                                                  */
+    int64_t private_rows;         /* resolved P = min(max_private_rows, T)                */
+    int64_t recv_buffer_rows;     /* rows of one rank's dispatch receive buffer: N*P private
+                                     slots, then recv_capacity_rows of shared range       */
 } fl_moe_sizes;
 
 /* Device pointers into the workspace, valid until fl_moe_destroy; contents are
@@ -118,8 +130,11 @@ typedef struct fl_moe_layout_view {
     const int32_t *dedup_counts;      /* M [N][N]    distinct tokens per (source, destination rank)   */
     const int32_t *tokens_per_expert; /* G [N][E/N]                                                   */
     const int32_t *send_off;          /* [N][N+1]  exclusive scan of M[s][.]                          */
-    const int32_t *recv_off;          /* [N][N+1]  exclusive scan of M[.][d]: source s owns rows
-                                         [recv_off[d][s], recv_off[d][s+1]) of d's receive buffer     */
+    const int32_t *recv_off;          /* [N][N+1]  exclusive scan of M[.][d]: source s owns received
+                                         rows [recv_off[d][s], recv_off[d][s+1]) of rank d; with
+                                         max_private_rows = 0 these are also the rows of d's receive
+                                         buffer, otherwise the first P of each source sit in its
+                                         private slots and the rest in the shared range               */
     const int32_t *expert_off;        /* [N][E/N+1] first row of each local expert; last = end of rows */
     const int32_t *comb_off;          /* [N][N+1]  start of each peer's reply in the combine receive
                                          buffer of rank s                                              */
@@ -227,7 +242,7 @@ int fl_moe_debug_copy(void *dst, const void *src, size_t bytes, void *stream);
  * fl_moe_profile_collect synchronises, adds the elapsed times of the launches
  * since the last collect to per-kernel totals, and fl_moe_profile_read returns
  * totals (ms) and launch counts for kernel ids 0..FL_KERNEL_COUNT-1. */
-#define FL_KERNEL_COUNT 9
+#define FL_KERNEL_COUNT 10
 int fl_moe_profile_enable(fl_moe_ctx *ctx, int on);
 int fl_moe_profile_collect(fl_moe_ctx *ctx, void *stream);
 int fl_moe_profile_read(fl_moe_ctx *ctx, double *total_ms /*host [FL_KERNEL_COUNT]*/,

@@ -17,6 +17,8 @@ struct Dims {
     int route_len;        // ints one rank pushes to every peer: C[E] | M[N] | comb_off[N] | valid
     int scales_per_row;   // 0 or H/128
     long long recv_cap, expert_cap, send_cap;   // rows per rank
+    int P;                // private rows per (source, destination) at the head of a receive buffer
+    long long recv_rows;  // physical rows of a dispatch receive buffer: N*P private + recv_cap shared
     long long Bx, Bw, Be, Bc;                   // row bytes: input, wire, expert_x, combine
     long long bufA_rank_bytes, bufB_rank_bytes;
     long long spin_limit;
@@ -27,6 +29,15 @@ struct Dims {
     int tune_slices;      // blocks per token in the pack kernel (0 = by row size)
     int tune_stream_mb;   // fabric uses streaming stores when a launch may write more than this many MiB
 };
+
+// Row of a dispatch receive buffer that holds the i-th row source s sent to this
+// rank: the first P rows of every source have fixed private slots at the head of
+// the buffer (known without any exchange), later rows are packed into the shared
+// range behind them in source order (section MoE Dispatch/Combine, figure
+// "Dispatch into private and contiguous buffers").
+__host__ __device__ inline int recv_buffer_row(int N, int P, int s, int i, int shared_start) {
+    return i < P ? s * P + i : N * P + shared_start + (i - P);
+}
 
 // Device pointers into the caller's workspace.
 struct Tables {
@@ -50,8 +61,10 @@ struct Tables {
     // written by the receiving side of the layout step
     int *G;               // [N][El]
     int *expert_off;      // [N][El+1]
-    int *recv_off;        // [N][N+1]
-    int *dst_off;         // [N src][N dst]   row in dst's receive buffer where src's segment starts
+    int *recv_off;        // [N][N+1]         received rows of lower sources (the order unpack walks)
+    int *recv_shared_off; // [N dst][N src]   shared-range rows of lower sources: sum of max(M - P, 0)
+    int *dst_off;         // [N src][N dst]   the same number as seen by the sender: where src's rows
+                          //                  beyond its private slots start in dst's shared range
     int *comb_dst_off;    // [N d][N s]       row in s's combine receive buffer where d's reply starts
     int *base_x;          // [N][El][N]       first expert-major row of (local expert, source)
     int *cs_base;         // [N][N][El]       first combine-send row of (source, local expert)

@@ -18,12 +18,12 @@ namespace {
 enum KernelId {
     KID_ROUTE_COUNT = 0, KID_ROUTE_PLAN, KID_DISPATCH_PACK, KID_DISPATCH_FABRIC,
     KID_DISPATCH_UNPACK, KID_COMBINE_PACK, KID_COMBINE_FABRIC, KID_COMBINE_REDUCE,
-    KID_DISPATCH_PACK_E4M3
+    KID_DISPATCH_PACK_E4M3, KID_DISPATCH_FABRIC_PRIVATE
 };
 const char *kKernelNames[FL_KERNEL_COUNT] = {
     "route_count_kernel", "route_plan_kernel", "dispatch_pack_kernel", "fabric_copy_kernel(dispatch)",
     "dispatch_unpack_kernel", "combine_pack_kernel", "fabric_copy_kernel(combine)",
-    "combine_reduce_kernel", "dispatch_pack_e4m3_kernel"};
+    "combine_reduce_kernel", "dispatch_pack_e4m3_kernel", "fabric_copy_kernel(dispatch, private slots)"};
 
 constexpr int kEventPool = 64;
 constexpr long long kMaxFabricBlocks = 1 << 16;   // waves loop cheaply (no barriers)
@@ -62,6 +62,7 @@ int resolve(const fl_moe_config *c, Dims *D) {
     if (c->flags & ~(FL_FLAG_ZERO_PAD | FL_FLAG_UNORDERED_FABRIC)) return FL_ERR_INVALID_ARG;
     if (c->recv_capacity_rows < 0 || c->expert_capacity_rows < 0 || c->spin_limit < 0)
         return FL_ERR_INVALID_ARG;
+    if (c->max_private_rows < 0 || c->reserved != 0) return FL_ERR_INVALID_ARG;
 
     D->N = c->n_ranks; D->E = c->n_experts; D->El = El; D->T = c->max_tokens; D->K = c->top_k;
     D->H = c->hidden; D->dtype = c->dispatch_dtype; D->align = c->expert_align; D->flags = c->flags;
@@ -75,7 +76,9 @@ int resolve(const fl_moe_config *c, Dims *D) {
     D->expert_cap = c->expert_capacity_rows ? c->expert_capacity_rows : worst_expert;
     if (D->recv_cap > worst_recv) D->recv_cap = worst_recv;
     if (D->expert_cap > worst_expert) D->expert_cap = worst_expert;
-    if (D->recv_cap >= (1ll << 31) || D->expert_cap >= (1ll << 31)) return FL_ERR_INVALID_ARG;
+    D->P = c->max_private_rows < D->T ? c->max_private_rows : D->T;   // a source sends at most T rows
+    D->recv_rows = (long long)D->N * D->P + D->recv_cap;
+    if (D->recv_rows >= (1ll << 31) || D->expert_cap >= (1ll << 31)) return FL_ERR_INVALID_ARG;
     D->send_cap = (long long)D->T * (D->K < D->N ? D->K : D->N);
     D->Bx = 2ll * D->H;
     D->Bc = 2ll * D->H;
@@ -87,7 +90,7 @@ int resolve(const fl_moe_config *c, Dims *D) {
         D->Bw = (long long)align_up((size_t)(D->H + 4ll * D->scales_per_row), 16);
     }
     const long long a1 = D->send_cap * D->Bw, a2 = (long long)D->T * D->K * D->Bc;
-    const long long b1 = D->recv_cap * D->Bw, b2 = D->expert_cap * D->Bc;
+    const long long b1 = D->recv_rows * D->Bw, b2 = D->expert_cap * D->Bc;
     D->bufA_rank_bytes = (long long)align_up((size_t)(a1 > a2 ? a1 : a2), 256);
     D->bufB_rank_bytes = (long long)align_up((size_t)(b1 > b2 ? b1 : b2), 256);
     // arrival counters count 16-byte units in 32 bits with a wrap-safe comparison
@@ -126,6 +129,7 @@ size_t carve(const Dims &D, void *base, Tables *W, size_t *total) {
     W->G = c.take<int>(N * El);
     W->expert_off = c.take<int>(N * (El + 1));
     W->recv_off = c.take<int>(N * (N + 1));
+    W->recv_shared_off = c.take<int>(N * N);
     W->dst_off = c.take<int>(N * N);
     W->comb_dst_off = c.take<int>(N * N);
     W->base_x = c.take<int>(N * El * N);
@@ -136,7 +140,7 @@ size_t carve(const Dims &D, void *base, Tables *W, size_t *total) {
     W->pair_meta = c.take<unsigned>(N * T * K);
     W->comb_pos = c.take<int>(N * T * K);
     W->send_meta = c.take<unsigned>(N * (size_t)D.send_cap * D.KM);
-    W->recv_meta = c.take<unsigned>(N * (size_t)D.recv_cap * D.KM);
+    W->recv_meta = c.take<unsigned>(N * (size_t)D.recv_rows * D.KM);
     W->fab_dst_disp = c.take<int2>(N * (size_t)D.send_cap);
     W->fab_dst_comb = c.take<int2>(N * (size_t)D.expert_cap);
     W->bufA = c.take<char>(N * (size_t)D.bufA_rank_bytes);
@@ -245,6 +249,8 @@ int fl_moe_query_sizes(const fl_moe_config *cfg, fl_moe_sizes *out) {
     out->expert_x_row_bytes = D.Be;
     out->scales_per_row = D.scales_per_row;
     out->combine_row_bytes = D.Bc;
+    out->private_rows = D.P;
+    out->recv_buffer_rows = D.recv_rows;
     return FL_OK;
 }
 
@@ -358,16 +364,31 @@ int fl_moe_dispatch_send(fl_moe_ctx *ctx, int rb, int rc, const void *x, void *s
     A.dst_base = W.bufB; A.dst_rank_stride = D.bufB_rank_bytes;
     A.seg_off = W.send_off; A.row_dst = W.fab_dst_disp; A.row_cap = D.send_cap;
     A.src_meta = W.send_meta; A.src_meta_rank_stride = D.send_cap * D.KM;
-    A.dst_meta = W.recv_meta; A.dst_meta_rank_stride = D.recv_cap * D.KM;
+    A.dst_meta = W.recv_meta; A.dst_meta_rank_stride = D.recv_rows * D.KM;
+    A.dst_row_lo = 0;
     A.arrive = W.arrive_disp;
     A.row_bytes = D.Bw; A.waves_per_row = waves_per_row(D.Bw, D.tune_waves);
     const int wpb = kCopyThreads / kWave;
     // a multiple of waves_per_row blocks keeps every row's waves at a fixed stride
     const unsigned gx = capped_grid((D.send_cap * A.waves_per_row + wpb - 1) / wpb, rc, kMaxFabricBlocks,
                                      A.waves_per_row);
-    {
+    const bool streaming = (long long)rc * D.send_cap * D.Bw > ((long long)D.tune_stream_mb << 20);
+    if (D.P > 0) {
+        // First scatter: the rows bound for private slots.  Their targets follow from the
+        // sender's own counts alone, so this launch reads nothing a peer produced.
+        LaunchTimer t(ctx, KID_DISPATCH_FABRIC_PRIVATE, st);
+        const unsigned g1 = capped_grid(((long long)D.N * D.P * A.waves_per_row + wpb - 1) / wpb, rc,
+                                        kMaxFabricBlocks, A.waves_per_row);
+        if (D.flags & FL_FLAG_UNORDERED_FABRIC)
+            fabric_private_kernel<true, true><<<dim3(g1, rc), dim3(kCopyThreads), 0, st>>>(D, W, A, rb);
+        else if (streaming)
+            fabric_private_kernel<false, true><<<dim3(g1, rc), dim3(kCopyThreads), 0, st>>>(D, W, A, rb);
+        else
+            fabric_private_kernel<false, false><<<dim3(g1, rc), dim3(kCopyThreads), 0, st>>>(D, W, A, rb);
+        A.dst_row_lo = D.N * D.P;             // second scatter: the rest, into the shared range
+    }
+    if (D.P < D.T) {                          // with P = T every row has a private slot
         LaunchTimer t(ctx, KID_DISPATCH_FABRIC, st);
-        const bool streaming = (long long)rc * D.send_cap * D.Bw > ((long long)D.tune_stream_mb << 20);
         if (D.flags & FL_FLAG_UNORDERED_FABRIC)
             fabric_copy_kernel<true, 0, true><<<dim3(gx, rc), dim3(kCopyThreads), 0, st>>>(D, W, A, rb);
         else if (streaming)
@@ -392,17 +413,27 @@ int fl_moe_dispatch_recv(fl_moe_ctx *ctx, int rb, int rc, void *expert_x, float 
     // In unordered mode the receivers may be polling while senders still need
     // somewhere to run: they take at most half of the resident-block slots.
     const bool unordered = D.flags & FL_FLAG_UNORDERED_FABRIC;
-    unsigned gx = capped_grid((D.recv_cap + rbk - 1) / rbk, rc,
+    const long long worst_rows = (long long)D.N * D.T;       // received rows in use never exceed this
+    const long long max_rows = D.recv_rows < worst_rows ? D.recv_rows : worst_rows;
+    unsigned gx = capped_grid((max_rows + rbk - 1) / rbk, rc,
                               unordered ? (long long)ctx->cu_count * 4 : kMaxRowBlocks);
     if (gx < (unsigned)D.El) gx = D.El;      // the first El-1 blocks also clear padding rows
     {
         LaunchTimer t(ctx, KID_DISPATCH_UNPACK, st);
-        if (D.flags & FL_FLAG_UNORDERED_FABRIC)
-            dispatch_unpack_kernel<true><<<dim3(gx, rc), dim3(kCopyThreads), 0, st>>>(
-                D, ctx->W, rb, (char *)expert_x, expert_scales, tokens_per_expert, rbk);
+        const dim3 grid(gx, rc), block(kCopyThreads);
+        char *ex = (char *)expert_x;
+        if (unordered && D.P)
+            dispatch_unpack_kernel<true, true><<<grid, block, 0, st>>>(D, ctx->W, rb, ex, expert_scales,
+                                                                       tokens_per_expert, rbk);
+        else if (unordered)
+            dispatch_unpack_kernel<true, false><<<grid, block, 0, st>>>(D, ctx->W, rb, ex, expert_scales,
+                                                                        tokens_per_expert, rbk);
+        else if (D.P)
+            dispatch_unpack_kernel<false, true><<<grid, block, 0, st>>>(D, ctx->W, rb, ex, expert_scales,
+                                                                        tokens_per_expert, rbk);
         else
-            dispatch_unpack_kernel<false><<<dim3(gx, rc), dim3(kCopyThreads), 0, st>>>(
-                D, ctx->W, rb, (char *)expert_x, expert_scales, tokens_per_expert, rbk);
+            dispatch_unpack_kernel<false, false><<<grid, block, 0, st>>>(D, ctx->W, rb, ex, expert_scales,
+                                                                         tokens_per_expert, rbk);
     }
     return launch_status();
 }
@@ -428,6 +459,7 @@ int fl_moe_combine_send(fl_moe_ctx *ctx, int rb, int rc, const void *expert_y, v
     A.seg_off = W.cs_off; A.row_dst = W.fab_dst_comb; A.row_cap = D.expert_cap;
     A.src_meta = nullptr; A.src_meta_rank_stride = 0;
     A.dst_meta = nullptr; A.dst_meta_rank_stride = 0;
+    A.dst_row_lo = 0;
     A.arrive = W.arrive_comb;
     A.row_bytes = D.Bc; A.waves_per_row = waves_per_row(D.Bc, D.tune_waves);
     const int wpb = kCopyThreads / kWave;

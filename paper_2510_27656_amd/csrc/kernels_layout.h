@@ -252,6 +252,9 @@ __global__ __launch_bounds__(kPlanThreads) void route_plan_kernel(Dims D, Tables
         int inc = wave_incl_scan(m);
         if (s < N) W.recv_off[(size_t)r * (N + 1) + s] = inc - m;
         if (s == N - 1) W.recv_off[(size_t)r * (N + 1) + N] = inc;
+        const int beyond = max(m - D.P, 0);        // rows of s past its private slots
+        inc = wave_incl_scan(beyond);
+        if (s < N) W.recv_shared_off[(size_t)r * N + s] = inc - beyond;
         int len = 0;
         if (s < N)
             for (int j = 0; j < El; ++j) len += Cown[s * El + j];
@@ -267,8 +270,8 @@ __global__ __launch_bounds__(kPlanThreads) void route_plan_kernel(Dims D, Tables
             int before_me = 0;
             for (int s = 0; s < N; ++s) {
                 const int m = Mall[s * N + d];
-                if (s < r) before_me += m;
-                recv_rows += m;
+                if (s < r) before_me += max(m - D.P, 0);
+                recv_rows += max(m - D.P, 0);              // what d's shared range must hold
             }
             W.dst_off[(size_t)r * N + d] = before_me;
             int mine = 0;

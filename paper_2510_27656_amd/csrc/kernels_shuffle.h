@@ -33,15 +33,16 @@ __global__ __launch_bounds__(kPackThreads) void dispatch_pack_kernel(
     __shared__ int s_dst[FL_MAX_TOPK];
     __shared__ unsigned s_meta[FL_MAX_TOPK];
     const size_t pair0 = ((size_t)s * D.T + t) * K;
-    int my_row = -1, my_d = 0, delta = 0;
+    int my_row = -1, my_d = 0, target = 0;
     if (tid < K) {                             // independent loads first, then one dependent level
         my_row = W.send_row[pair0 + tid];
         my_d = indices[pair0 + tid] / El;
         s_meta[tid] = W.pair_meta[pair0 + tid];
         s_row[tid] = my_row;
         s_dst[tid] = my_d;
-        if (my_row >= 0)                       // this copy's row in d's buffer minus its row here
-            delta = W.dst_off[(size_t)s * D.N + my_d] - W.send_off[(size_t)s * (D.N + 1) + my_d];
+        if (my_row >= 0)                       // this copy's row in d's receive buffer
+            target = recv_buffer_row(D.N, D.P, s, my_row - W.send_off[(size_t)s * (D.N + 1) + my_d],
+                                     W.dst_off[(size_t)s * D.N + my_d]);
     }
     __syncthreads();
     if (slice == 0 && tid < K && my_row >= 0) {   // sidecar and fabric target of this copy
@@ -50,7 +51,7 @@ __global__ __launch_bounds__(kPackThreads) void dispatch_pack_kernel(
         for (int k = 0; k < K; ++k)
             if (s_dst[k] == my_d) meta[m++] = s_meta[k];
         for (; m < D.KM; ++m) meta[m] = kNoEntry;
-        W.fab_dst_disp[(size_t)s * D.send_cap + my_row] = make_int2(my_d, my_row + delta);
+        W.fab_dst_disp[(size_t)s * D.send_cap + my_row] = make_int2(my_d, target);
     }
     const int nvec = (int)(D.Bx / 16);
     const int per = (nvec + slices - 1) / slices;          // vectors of this slice: [v0, v1)
@@ -112,7 +113,7 @@ __global__ __launch_bounds__(kQuantThreads) void dispatch_pack_e4m3_kernel(
     __shared__ int s_dst[FL_MAX_TOPK];
     __shared__ unsigned s_meta[FL_MAX_TOPK];
     const size_t pair0 = ((size_t)s * D.T + t) * K;
-    int my_row = -1, my_d = 0, delta = 0;
+    int my_row = -1, my_d = 0, target = 0;
     if (tid < K) {
         my_row = W.send_row[pair0 + tid];
         my_d = indices[pair0 + tid] / El;
@@ -120,7 +121,8 @@ __global__ __launch_bounds__(kQuantThreads) void dispatch_pack_e4m3_kernel(
         s_row[tid] = my_row;
         s_dst[tid] = my_d;
         if (my_row >= 0)
-            delta = W.dst_off[(size_t)s * D.N + my_d] - W.send_off[(size_t)s * (D.N + 1) + my_d];
+            target = recv_buffer_row(D.N, D.P, s, my_row - W.send_off[(size_t)s * (D.N + 1) + my_d],
+                                     W.dst_off[(size_t)s * D.N + my_d]);
     }
     __syncthreads();
     if (slice == 0 && tid < K && my_row >= 0) {
@@ -129,7 +131,7 @@ __global__ __launch_bounds__(kQuantThreads) void dispatch_pack_e4m3_kernel(
         for (int k = 0; k < K; ++k)
             if (s_dst[k] == my_d) meta[m++] = s_meta[k];
         for (; m < D.KM; ++m) meta[m] = kNoEntry;
-        W.fab_dst_disp[(size_t)s * D.send_cap + my_row] = make_int2(my_d, my_row + delta);
+        W.fab_dst_disp[(size_t)s * D.send_cap + my_row] = make_int2(my_d, target);
     }
     const int nblk = D.scales_per_row;                          // 128-element blocks in the row
     const int blk = slice * (kQuantThreads / kQuantLanes) + tid / kQuantLanes;
@@ -205,7 +207,42 @@ struct FabricArgs {
     unsigned *arrive;     // [N dst][N src]
     long long row_bytes;
     int waves_per_row;    // 1..16
+    int dst_row_lo;       // rows whose target row is below this belong to the private-slot scatter
 };
+
+// One wave's share of one row: slice `sub` of `G` (vectors v with (v / 64) % G ==
+// sub), the sidecar when it is slice 0, then the count of 16-byte units it
+// delivered, added to arrive[destination][source].
+template <bool FENCED, bool STREAMING>
+__device__ inline void fabric_send_row(const Dims &D, const FabricArgs &A, int s, int src_row,
+                                       int dst_rank, int dst_row, int sub, int lane) {
+    const int G = A.waves_per_row, N = D.N;
+    const int nvec = (int)(A.row_bytes / 16);
+    const int step = G * kWave;
+    const v4u *src =
+        (const v4u *)(A.src_base + (size_t)s * A.src_rank_stride + (size_t)src_row * A.row_bytes);
+    v4u *dst = (v4u *)(A.dst_base + (size_t)dst_rank * A.dst_rank_stride + (size_t)dst_row * A.row_bytes);
+    for (int b = sub * kWave + lane; b < nvec; b += 4 * step) {
+        v4u v[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if (b + j * step < nvec) v[j] = ld_stream(src + b + j * step);
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if (b + j * step < nvec) st_payload<FENCED, STREAMING>(dst + b + j * step, v[j]);
+    }
+    if (A.src_meta && sub == 0) {          // the sidecar travels with the row
+        const int mv = D.KM / 4;
+        const v4u *ms =
+            (const v4u *)(A.src_meta + (size_t)s * A.src_meta_rank_stride) + (size_t)src_row * mv;
+        v4u *md = (v4u *)(A.dst_meta + (size_t)dst_rank * A.dst_meta_rank_stride) + (size_t)dst_row * mv;
+        if (lane < mv) st_payload<FENCED, STREAMING>(md + lane, ms[lane]);
+    }
+    const int full = nvec / step, rem = nvec - full * step;
+    const int mine = full * kWave + min(max(rem - sub * kWave, 0), kWave);
+    stores_done<FENCED>();
+    if (lane == 0 && mine > 0) add_counter(A.arrive + (size_t)dst_rank * N + s, (unsigned)mine);
+}
 
 template <bool FENCED, int PHASE, bool STREAMING>   // PHASE only names the launch: 0 dispatch, 1 combine
 __global__ __launch_bounds__(kCopyThreads) void fabric_copy_kernel(Dims D, Tables W,
@@ -218,40 +255,38 @@ __global__ __launch_bounds__(kCopyThreads) void fabric_copy_kernel(Dims D, Table
     const int row_stride = (int)(gridDim.x * (kCopyThreads / kWave)) / G;   // grid is a multiple of G waves
     const int ok = W.plan_ok[s];
     const int total = ok ? A.seg_off[(size_t)s * (N + 1) + N] : 0;   // step skipped: nothing sent
-    const int nvec = (int)(A.row_bytes / 16);
-    const int step = G * kWave;
     // The first row's target is fetched together with the two loads above; capacities
     // are upper bounds, so the grid may be smaller than the rows in use and a wave loops.
     int i = wave / G;
     int2 t = make_int2(0, 0);
     if (i < A.row_cap) t = A.row_dst[(size_t)s * A.row_cap + i];
     while (i < total) {
-        const v4u *src =
-            (const v4u *)(A.src_base + (size_t)s * A.src_rank_stride + (size_t)i * A.row_bytes);
-        v4u *dst = (v4u *)(A.dst_base + (size_t)t.x * A.dst_rank_stride + (size_t)t.y * A.row_bytes);
-        for (int b = sub * kWave + lane; b < nvec; b += 4 * step) {
-            v4u v[4];
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                if (b + j * step < nvec) v[j] = ld_stream(src + b + j * step);
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                if (b + j * step < nvec) st_payload<FENCED, STREAMING>(dst + b + j * step, v[j]);
-        }
-        if (A.src_meta && sub == 0) {          // the sidecar travels with the row
-            const int mv = D.KM / 4;
-            const v4u *ms =
-                (const v4u *)(A.src_meta + (size_t)s * A.src_meta_rank_stride) + (size_t)i * mv;
-            v4u *md = (v4u *)(A.dst_meta + (size_t)t.x * A.dst_meta_rank_stride) + (size_t)t.y * mv;
-            if (lane < mv) st_payload<FENCED, STREAMING>(md + lane, ms[lane]);
-        }
-        // units this wave delivered: vectors v < nvec with (v / 64) % G == sub
-        const int full = nvec / step, rem = nvec - full * step;
-        const int mine = full * kWave + min(max(rem - sub * kWave, 0), kWave);
-        stores_done<FENCED>();
-        if (lane == 0 && mine > 0) add_counter(A.arrive + (size_t)t.x * N + s, (unsigned)mine);
+        if (t.y >= A.dst_row_lo)           // rows below went out with the private-slot scatter
+            fabric_send_row<FENCED, STREAMING>(D, A, s, i, t.x, t.y, sub, lane);
         i += row_stride;
         if (i < total) t = A.row_dst[(size_t)s * A.row_cap + i];
+    }
+}
+
+// First scatter of a dispatch with private slots (section Dispatch: tokens up to
+// a fixed limit go to private buffers on every peer before the routes are
+// known).  Slot q = d * P + i of source s stands for the i-th row s sends to d;
+// it exists when i < M[s][d], a number s counted itself, and lands in row
+// s * P + i of d's receive buffer.  Nothing here was derived from a peer's counts.
+template <bool FENCED, bool STREAMING>
+__global__ __launch_bounds__(kCopyThreads) void fabric_private_kernel(Dims D, Tables W,
+                                                                      FabricArgs A, int rank_begin) {
+    const int s = rank_begin + blockIdx.y, N = D.N, P = D.P;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = blockIdx.x * (kCopyThreads / kWave) + threadIdx.x / kWave;
+    const int G = A.waves_per_row;
+    const int sub = wave % G;
+    const int slot_stride = (int)(gridDim.x * (kCopyThreads / kWave)) / G;
+    if (!W.plan_ok[s]) return;
+    for (int q = wave / G; q < N * P; q += slot_stride) {
+        const int d = q / P, i = q - d * P;
+        const int lo = A.seg_off[(size_t)s * (N + 1) + d], hi = A.seg_off[(size_t)s * (N + 1) + d + 1];
+        if (i < hi - lo) fabric_send_row<FENCED, STREAMING>(D, A, s, lo + i, d, s * P + i, sub, lane);
     }
 }
 
@@ -261,7 +296,7 @@ __global__ __launch_bounds__(kCopyThreads) void fabric_copy_kernel(Dims D, Table
 // writes every row once per local expert that wants it, at
 //   base_x[d][local expert][source] + rank carried in the sidecar,
 // which is the (expert, source rank, token) order of the grouped layout.
-template <bool FENCED>
+template <bool FENCED, bool PRIVATE>   // PRIVATE: the receive buffer has private slots (P > 0)
 __global__ __launch_bounds__(kCopyThreads) void dispatch_unpack_kernel(
     Dims D, Tables W, int rank_begin, char *__restrict__ expert_x,
     float *__restrict__ expert_scales, int *__restrict__ tokens_per_expert, int rows_per_block) {
@@ -269,6 +304,7 @@ __global__ __launch_bounds__(kCopyThreads) void dispatch_unpack_kernel(
     __shared__ int off[FL_MAX_RANKS + 1];
     __shared__ int dst_rows[kMaxRowsPerBlock][FL_MAX_TOPK];
     __shared__ int dst_cnt[kMaxRowsPerBlock];
+    __shared__ int src_phys[kMaxRowsPerBlock];      // with private slots: buffer row of each received row
     __shared__ int timed_out;
     if (!W.plan_ok[d]) return;
     if (blockIdx.x == 0)
@@ -314,7 +350,12 @@ __global__ __launch_bounds__(kCopyThreads) void dispatch_unpack_kernel(
         if (tid < r1 - r0) {                   // plan of one received row: its expert-major rows
             const int r = r0 + tid;
             const int s = seg_of(off, N, r);
-            const unsigned *meta = W.recv_meta + ((size_t)d * D.recv_cap + r) * D.KM;
+            int phys = r;
+            if (PRIVATE) {
+                phys = recv_buffer_row(N, D.P, s, r - off[s], W.recv_shared_off[(size_t)d * N + s]);
+                src_phys[tid] = phys;
+            }
+            const unsigned *meta = W.recv_meta + ((size_t)d * D.recv_rows + phys) * D.KM;
             int n = 0;
             for (int k = 0; k < K; ++k) {
                 const unsigned m = meta[k];
@@ -337,7 +378,8 @@ __global__ __launch_bounds__(kCopyThreads) void dispatch_unpack_kernel(
                 if (v < chunk) {
                     row[i] = v / rowvec;
                     col[i] = v - row[i] * rowvec;
-                    val[i] = ld_stream((const v4u *)(recv + (size_t)(r0 + row[i]) * D.Bw) + col[i]);
+                    const int pr = PRIVATE ? src_phys[row[i]] : r0 + row[i];
+                    val[i] = ld_stream((const v4u *)(recv + (size_t)pr * D.Bw) + col[i]);
                 }
             }
 #pragma unroll
@@ -360,7 +402,8 @@ __global__ __launch_bounds__(kCopyThreads) void dispatch_unpack_kernel(
             for (int r = r0; r < r1; ++r) {
                 const int n = dst_cnt[r - r0];
                 const int *dr = dst_rows[r - r0];
-                const float *ssrc = (const float *)(recv + (size_t)r * D.Bw + D.Be);
+                const float *ssrc =
+                    (const float *)(recv + (size_t)(PRIVATE ? src_phys[r - r0] : r) * D.Bw + D.Be);
                 for (int v = tid; v < D.scales_per_row; v += kCopyThreads) {
                     const float val = ssrc[v];
                     for (int i = 0; i < n; ++i)

@@ -18,7 +18,7 @@ FL_STATUS_BAD_INDEX, FL_STATUS_CAPACITY, FL_STATUS_TIMEOUT = 1, 2, 4
 FL_DTYPE_BF16, FL_DTYPE_E4M3_BLOCK128 = 0, 1
 FL_FLAG_ZERO_PAD = 1
 FL_FLAG_UNORDERED_FABRIC = 2
-FL_KERNEL_COUNT = 9
+FL_KERNEL_COUNT = 10
 
 
 class fl_moe_config(C.Structure):
@@ -26,7 +26,8 @@ class fl_moe_config(C.Structure):
                 ("top_k", C.c_int32), ("hidden", C.c_int32), ("dispatch_dtype", C.c_int32),
                 ("expert_align", C.c_int32), ("flags", C.c_int32),
                 ("recv_capacity_rows", C.c_int64), ("expert_capacity_rows", C.c_int64),
-                ("spin_limit", C.c_int64)]
+                ("spin_limit", C.c_int64), ("max_private_rows", C.c_int32),
+                ("reserved", C.c_int32)]
 
 
 class fl_moe_sizes(C.Structure):
@@ -34,7 +35,8 @@ class fl_moe_sizes(C.Structure):
                 ("expert_capacity_rows", C.c_int64), ("send_capacity_rows", C.c_int64),
                 ("x_row_bytes", C.c_int64), ("wire_row_bytes", C.c_int64),
                 ("expert_x_row_bytes", C.c_int64), ("scales_per_row", C.c_int64),
-                ("combine_row_bytes", C.c_int64)]
+                ("combine_row_bytes", C.c_int64), ("private_rows", C.c_int64),
+                ("recv_buffer_rows", C.c_int64)]
 
 
 class fl_moe_layout_view(C.Structure):
@@ -209,14 +211,14 @@ class MoEShuffle:
 
     def __init__(self, n_ranks, n_experts, max_tokens, top_k, hidden, dispatch_dtype="bf16",
                  expert_align=1, zero_pad=False, recv_capacity_rows=0, expert_capacity_rows=0,
-                 spin_limit=0, unordered_fabric=False, device="cuda:0"):
+                 spin_limit=0, unordered_fabric=False, max_private_rows=0, device="cuda:0"):
         self.device = torch.device(device)
         self.cfg = fl_moe_config(
             n_ranks, n_experts, max_tokens, top_k, hidden,
             FL_DTYPE_BF16 if dispatch_dtype == "bf16" else FL_DTYPE_E4M3_BLOCK128,
             expert_align, (FL_FLAG_ZERO_PAD if zero_pad else 0)
             | (FL_FLAG_UNORDERED_FABRIC if unordered_fabric else 0),
-            recv_capacity_rows, expert_capacity_rows, spin_limit)
+            recv_capacity_rows, expert_capacity_rows, spin_limit, max_private_rows, 0)
         self.sizes = fl_moe_query_sizes(self.cfg)
         self.N, self.E, self.T, self.K, self.H = n_ranks, n_experts, max_tokens, top_k, hidden
         self.El = n_experts // n_ranks

@@ -21,7 +21,7 @@ def to_device(inp: Inputs, device="cuda:0"):
 
 
 def make_shuffle(inp: Inputs, expert_align=1, zero_pad=False, capacity_factor=None,
-                 spin_limit=0, unordered_fabric=False, device="cuda:0"):
+                 spin_limit=0, unordered_fabric=False, max_private_rows=0, device="cuda:0"):
     """capacity_factor None = worst-case capacities, else factor x the mean rows per rank."""
     wl = inp.wl
     recv_cap = expert_cap = 0
@@ -33,7 +33,8 @@ def make_shuffle(inp: Inputs, expert_align=1, zero_pad=False, capacity_factor=No
                             dispatch_dtype=wl.dispatch_dtype, expert_align=expert_align,
                             zero_pad=zero_pad, recv_capacity_rows=recv_cap,
                             expert_capacity_rows=expert_cap, spin_limit=spin_limit,
-                            unordered_fabric=unordered_fabric, device=device)
+                            unordered_fabric=unordered_fabric,
+                            max_private_rows=max_private_rows, device=device)
 
 
 def row_gain(sh: flmoe.MoEShuffle, gain: torch.Tensor):

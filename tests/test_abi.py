@@ -56,6 +56,21 @@ def test_capacities_are_clamped_and_padding_counted():
     assert s.recv_capacity_rows == 32 * 128 and s.expert_capacity_rows == 2000
 
 
+def test_private_rows_extend_the_receive_buffer():
+    base = flmoe.fl_moe_query_sizes(cfg())
+    assert base.private_rows == 0 and base.recv_buffer_rows == base.recv_capacity_rows
+    s = flmoe.fl_moe_query_sizes(cfg(max_private_rows=32))
+    assert s.private_rows == 32
+    assert s.recv_buffer_rows == 32 * 32 + s.recv_capacity_rows
+    assert s.workspace_bytes > base.workspace_bytes
+    # a source never sends more than T rows to one destination
+    s = flmoe.fl_moe_query_sizes(cfg(max_private_rows=10 ** 6))
+    assert s.private_rows == 128
+    # the shared range can then be configured smaller
+    s = flmoe.fl_moe_query_sizes(cfg(max_private_rows=32, recv_capacity_rows=1024))
+    assert s.recv_buffer_rows == 32 * 32 + 1024
+
+
 @pytest.mark.parametrize("bad,code", [
     (dict(n_ranks=0), flmoe.FL_ERR_INVALID_ARG),
     (dict(n_ranks=65, n_experts=65), flmoe.FL_ERR_INVALID_ARG),
@@ -68,6 +83,8 @@ def test_capacities_are_clamped_and_padding_counted():
     (dict(expert_align=0), flmoe.FL_ERR_INVALID_ARG),
     (dict(flags=8), flmoe.FL_ERR_INVALID_ARG),
     (dict(max_tokens=0), flmoe.FL_ERR_INVALID_ARG),
+    (dict(max_private_rows=-1), flmoe.FL_ERR_INVALID_ARG),
+    (dict(reserved=1), flmoe.FL_ERR_INVALID_ARG),
 ])
 def test_query_sizes_rejects_bad_configs(bad, code):
     with pytest.raises(flmoe.FlMoeError) as ei:

@@ -44,13 +44,14 @@ def check_tables(sh, ref, N):
 
 
 def run_and_compare(inp, align=1, zero_pad=False, capacity_factor=None, ranks_split=False,
-                    unordered=False):
+                    unordered=False, private_rows=0):
     wl = inp.wl
     N, T = wl.n_ranks, wl.tokens
     ref = oracle_step(inp, align, zero_pad=True)
     dev = harness.to_device(inp)
     sh = harness.make_shuffle(inp, expert_align=align, zero_pad=zero_pad,
-                              capacity_factor=capacity_factor, unordered_fabric=unordered)
+                              capacity_factor=capacity_factor, unordered_fabric=unordered,
+                              max_private_rows=private_rows)
     try:
         if wl.dispatch_dtype == "bf16":
             sh.expert_x.view(torch.int16).fill_(POISON)
@@ -452,6 +453,111 @@ def test_unordered_fabric_with_concurrent_send_and_receive(name, shuffled):
         assert (dbg["arrive_comb"] == dbg["expect_comb"]).all()
     finally:
         sh.close()
+
+
+# ------------------------------------------------------------------ private slots + shared range
+def shared_range_rows(M, P):
+    """Rows each destination's shared range must hold: sum over sources of max(M - P, 0)."""
+    return np.maximum(M.astype(np.int64) - P, 0).sum(axis=0)
+
+
+@pytest.mark.parametrize("name,P", [("ragged_520", 1), ("ragged_520", 5), ("ragged_520", 1000),
+                                    ("multi_tile", 64), ("k16", 7), ("single_rank", 10)])
+def test_parity_with_private_slots(name, P):
+    """Section Dispatch: the first P rows per (source, destination) go to private
+    slots in a scatter of their own, the rest into the shared range; the receiver
+    reads both regions.  Every result of the step is unchanged."""
+    inp = wlmod.make_inputs(CASES[name]())
+    sh, _, _ = run_and_compare(inp, align=4, zero_pad=True, private_rows=P)
+    sh.close()
+
+
+def test_private_slots_with_e4m3_and_unordered_fabric():
+    inp = wlmod.make_inputs(FP8_CASES["fp8_small"]())
+    sh, _, _ = run_and_compare(inp, private_rows=9, unordered=True)
+    sh.close()
+    inp = wlmod.make_inputs(CASES["multi_tile"]())
+    sh, _, _ = run_and_compare(inp, private_rows=300, unordered=True, ranks_split=True)
+    sh.close()
+
+
+def test_private_slots_named_decode_workload():
+    inp = wlmod.make_inputs(wlmod.WORKLOADS["dsv3_decode"])
+    sh, _, _ = run_and_compare(inp, private_rows=32)
+    sh.close()
+
+
+@pytest.mark.parametrize("P", [3, 12, 1000])
+def test_receive_buffer_holds_private_slots_then_shared_range(P):
+    """Where the scatter put every row, read back from the receive buffers and
+    compared with the layout the interface documents: source s's first P rows for
+    rank d at rows s*P.., later ones at N*P + (rows of lower sources beyond their
+    P) + (i - P); every other row of the buffer untouched."""
+    inp = wlmod.make_inputs(CASES["ragged_520"]())
+    wl = inp.wl
+    N, E, K, H = wl.n_ranks, wl.n_experts, wl.top_k, wl.hidden
+    dev = harness.to_device(inp)
+    sh = harness.make_shuffle(inp, max_private_rows=P)
+    try:
+        Pr = int(sh.sizes.private_rows)
+        assert Pr == min(P, wl.tokens)
+        assert sh.sizes.recv_buffer_rows == N * Pr + sh.sizes.recv_capacity_rows
+        buf = sh.debug()["buf_b"]
+        buf.fill_(0xA5)
+        sh.layout(dev["indices"], dev["num_tokens"])
+        sh.dispatch_send(dev["x"])
+        torch.cuda.synchronize()
+        assert sh.status() == 0
+        got = buf.cpu().numpy()
+        Bw = 2 * H
+        xb = inp.x.view(np.uint8).reshape(N, wl.tokens, Bw)
+        M = orc.layout(N, E, K, inp.num_tokens, inp.indices).M
+        for d in range(N):
+            rows = got[d, :sh.sizes.recv_buffer_rows * Bw].reshape(-1, Bw)
+            touched = np.zeros(rows.shape[0], bool)
+            sr, st, _ = orc.recv_order(d, N, E, K, inp.num_tokens, inp.indices)
+            shared_start = 0
+            for s in range(N):
+                toks = st[sr == s]
+                assert len(toks) == M[s, d]
+                for i, t in enumerate(toks):
+                    phys = s * Pr + i if i < Pr else N * Pr + shared_start + (i - Pr)
+                    assert (rows[phys] == xb[s, t]).all(), (d, s, i)
+                    assert not touched[phys]
+                    touched[phys] = True
+                shared_start += max(len(toks) - Pr, 0)
+            assert (rows[~touched] == 0xA5).all(), f"rank {d}: rows outside the layout were written"
+    finally:
+        sh.close()
+
+
+def test_private_slots_shrink_the_shared_range_needed():
+    """recv_capacity_rows bounds the shared range only: exactly the rows beyond the
+    private slots fit, one row less is a capacity error."""
+    inp = wlmod.make_inputs(CASES["ragged_520"]())
+    wl = inp.wl
+    dev = harness.to_device(inp)
+    ref = oracle_step(inp)
+    P = 6
+    need = int(shared_range_rows(ref.lay.M, P).max())
+    assert 0 < need < int(ref.lay.M.sum(axis=0).max())
+    for cap, ok in [(need, True), (need - 1, False)]:
+        sh = flmoe.MoEShuffle(wl.n_ranks, wl.n_experts, wl.tokens, wl.top_k, wl.hidden,
+                              recv_capacity_rows=cap, max_private_rows=P)
+        try:
+            sh.expert_x.view(torch.int16).fill_(POISON)
+            out = harness.run_step(sh, dev)
+            torch.cuda.synchronize()
+            if ok:
+                assert sh.status() == 0
+                for s in range(wl.n_ranks):
+                    n = inp.num_tokens[s]
+                    assert (bits(out)[s, :n] == ref.out[s, :n]).all()
+            else:
+                assert sh.status() == flmoe.FL_STATUS_CAPACITY
+                assert (bits(sh.expert_x) == POISON).all()
+        finally:
+            sh.close()
 
 
 # ------------------------------------------------------------------ failure handling

@@ -19,8 +19,11 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBPS = 8000.0
 
 
-def algorithmic_bytes(wl, ttot, D, P, sizes):
-    """Bytes the staged method itself has to move (reads + writes), per kernel."""
+def algorithmic_bytes(wl, ttot, D, P, sizes, push=False):
+    """Bytes the method itself has to move (reads + writes), per kernel.  Staged
+    (default): pack into send buffers, scatter, unpack.  Push: the send kernels
+    write into the receive buffers, so the send-buffer write and the scatter's
+    read and write are not part of the method."""
     Bx, Bw, Be, Bc = (sizes.x_row_bytes, sizes.wire_row_bytes,
                       sizes.expert_x_row_bytes + 4 * sizes.scales_per_row, sizes.combine_row_bytes)
     k = {
@@ -31,6 +34,8 @@ def algorithmic_bytes(wl, ttot, D, P, sizes):
         "fabric_copy_kernel(combine)": 2 * P * Bc,
         "combine_reduce_kernel": P * Bc + ttot * Bc,
     }
+    if push:
+        del k["fabric_copy_kernel(dispatch)"], k["fabric_copy_kernel(combine)"]
     if wl.dispatch_dtype != "bf16":
         k["dispatch_pack_e4m3_kernel"] = k.pop("dispatch_pack_kernel")
     dispatch = sum(v for n, v in k.items() if n.startswith(("dispatch", "fabric_copy_kernel(d")))
@@ -52,6 +57,10 @@ def main():
     ap.add_argument("--overlap", action="store_true",
                     help="unordered fabric with send calls on a second stream: receivers poll the "
                          "arrival counters while the fabric copy runs (reports the step time only)")
+    ap.add_argument("--push", action="store_true",
+                    help="FL_FLAG_PEER_PUSH: send kernels store into the peers' receive buffers, no "
+                         "send buffer and no scatter; GB/s is then computed against the smaller byte "
+                         "count of that method")
     ap.add_argument("--private-rows", type=int, default=0,
                     help="first rows per (source, destination) sent to private slots in a scatter "
                          "of their own (ablation of section Ablation: Private Buffer Size)")
@@ -88,9 +97,9 @@ def main():
         cf = min(cf or 1.1, 1.1)        # 16 GB buffers at 1.1x the mean; the worst case would not fit
     sh = harness.make_shuffle(inp, capacity_factor=cf,
                               unordered_fabric=args.unordered or args.overlap,
-                              max_private_rows=args.private_rows)
+                              max_private_rows=args.private_rows, peer_push=args.push)
     ttot, D, P = stats["tokens_total"], stats["dedup_rows"], stats["pairs"]
-    per_kernel, bytes_dispatch, bytes_combine = algorithmic_bytes(wl, ttot, D, P, sh.sizes)
+    per_kernel, bytes_dispatch, bytes_combine = algorithmic_bytes(wl, ttot, D, P, sh.sizes, args.push)
     bytes_step = bytes_dispatch + bytes_combine
 
     expert_y = None
@@ -241,7 +250,9 @@ def main():
         "data": "synthetic",
         "config": {"workload": wl.name, "ranks_simulated": wl.n_ranks, "experts": wl.n_experts,
                    "tokens_per_rank": wl.tokens, "hidden": wl.hidden, "top_k": wl.top_k,
-                   "dedup_rows": D, "pairs": P, "capacity_factor": cf, "private_rows": int(sh.sizes.private_rows), "fabric": "unordered (release/acquire)" if args.unordered else "stream-ordered",
+                   "dedup_rows": D, "pairs": P, "capacity_factor": cf, "private_rows": int(sh.sizes.private_rows),
+                   "method": "peer push (no send buffer, no scatter)" if args.push else "staged (pack, scatter, unpack)",
+                   "fabric": "unordered (release/acquire)" if args.unordered else "stream-ordered",
                    "expert_stage": "identity (expert_y aliases expert_x)" if expert_y is None
                    else "none in the timed path (resident bf16 expert_y)"},
         "frac_of_hbm_peak": round(value / HBM_PEAK_GBPS, 4),

@@ -5,8 +5,9 @@
  * simulated ranks; the "fabric" between ranks is a device-side copy whose
  * completion is signalled only through per-source arrival counters (the
  * paper's ImmCounter idea, section TransferEngine / Completion Notification:
- * a counter advances as payload is delivered, a receiver compares it with what
- * the exchanged counts tell it to expect, and nothing else orders transfers).
+ * a counter advances when payload has been delivered, a receiver compares it
+ * with what the exchanged counts tell it to expect, and nothing else orders
+ * transfers).
  *
  * Problem statement (section MoE Dispatch/Combine, Architecture): N ranks host E
  * experts (expert e lives on rank e / (E/N)); every rank holds up to T tokens of
@@ -66,13 +67,27 @@ extern "C" {
 #define FL_FLAG_ZERO_PAD 1 /* dispatch_recv writes zeros into the padding rows between experts */
 /* Without this flag the caller keeps each send call before the matching receive
  * call in stream order (one stream, or events between streams); the arrival
- * counters are then bumped and checked with relaxed atomics and no cache
- * maintenance.  With it, send and receive kernels may overlap in time (other
+ * counters are then checked with relaxed atomics and no cache maintenance, and
+ * advanced once per (sender, receiver) transfer by a small kernel that follows
+ * the copy kernel in stream order, as a NIC delivers one immediate after a whole
+ * WRITE.  With it, send and receive kernels may overlap in time (other
  * streams, other orders): a sender writes its payload through to memory
  * (device-scope stores) and waits for the acknowledgement before it reports
- * progress, and a receiver invalidates its caches once after its counters
- * arrived, which is the ImmCounter contract with no ordering assumed. */
+ * progress (every wave adds what it delivered, so a receiver sees a source's
+ * range complete as early as possible), and a receiver invalidates its caches
+ * once after its counters arrived, which is the ImmCounter contract with no
+ * ordering assumed. */
 #define FL_FLAG_UNORDERED_FABRIC 2
+/* Every peer's receive buffer can be stored to directly, as between ranks of one
+ * node (section Dispatch: within a node the send kernel pushes payloads over the
+ * load/store interconnect instead of handing them to the NIC; here: always, all
+ * simulated ranks live on one GPU).  The send calls then write each row and its
+ * sidecar straight into the destination's receive buffer: no send buffer is
+ * filled and no scatter kernel runs; the arrival counters advance as in the
+ * staged path (after the kernel, or per workgroup with FL_FLAG_UNORDERED_FABRIC).  Receivers, counters, capacities and every result are
+ * unchanged; only the bytes moved per step shrink (one write per sent row instead
+ * of write + read + write).  Combines with the other flags and max_private_rows. */
+#define FL_FLAG_PEER_PUSH 4
 
 #define FL_MAX_RANKS 64
 #define FL_MAX_EXPERTS 1024
@@ -183,7 +198,7 @@ int fl_moe_layout(fl_moe_ctx *ctx, int rank_begin, int rank_count, const int32_t
  * source per peer, then scattered).  x [N][T][H] bf16.  Packs one copy of each
  * token per distinct destination rank (quantising to e4m3 when configured),
  * copies every (source, destination) segment into the destination's receive
- * buffer and adds what it delivered (in 16-byte units) to
+ * buffer and adds what was delivered (in 16-byte units) to
  * arrive_disp[destination][source]. */
 int fl_moe_dispatch_send(fl_moe_ctx *ctx, int rank_begin, int rank_count, const void *x,
                          void *stream);
@@ -200,7 +215,7 @@ int fl_moe_dispatch_recv(fl_moe_ctx *ctx, int rank_begin, int rank_count, void *
 /* Step 4 (section Combine: a single scatter per peer re-using the routing
  * information).  expert_y [N][expert_capacity_rows][H] bf16, same row layout as
  * expert_x.  Packs each peer's rows contiguously, copies them into the peer's
- * combine receive buffer and adds what it delivered to arrive_comb[peer][this
+ * combine receive buffer and adds what was delivered to arrive_comb[peer][this
  * rank].  Call it once per fl_moe_layout, after fl_moe_dispatch_recv. */
 int fl_moe_combine_send(fl_moe_ctx *ctx, int rank_begin, int rank_count, const void *expert_y,
                         void *stream);
@@ -242,7 +257,7 @@ int fl_moe_debug_copy(void *dst, const void *src, size_t bytes, void *stream);
  * fl_moe_profile_collect synchronises, adds the elapsed times of the launches
  * since the last collect to per-kernel totals, and fl_moe_profile_read returns
  * totals (ms) and launch counts for kernel ids 0..FL_KERNEL_COUNT-1. */
-#define FL_KERNEL_COUNT 10
+#define FL_KERNEL_COUNT 11
 int fl_moe_profile_enable(fl_moe_ctx *ctx, int on);
 int fl_moe_profile_collect(fl_moe_ctx *ctx, void *stream);
 int fl_moe_profile_read(fl_moe_ctx *ctx, double *total_ms /*host [FL_KERNEL_COUNT]*/,

@@ -44,9 +44,11 @@ struct Tables {
     int *status;
     unsigned *epoch_route;                                    // [N] layout calls of each rank
     unsigned *arrive_route;                                   // [N dst][N src] route records received
-    // Payload counters, monotone, in 16-byte units: arrive_* is bumped by the fabric
-    // as data lands, expect_* by the receiver's own planning kernel from the counts
-    // it was sent, so a receiver waits for arrive >= expect per source.
+    // Payload counters, monotone, in 16-byte units: arrive_* advances when data has
+    // landed (stream-ordered: once per transfer, by the kernel that follows the copy;
+    // unordered: by every copying wave), expect_* is advanced by the receiver's own
+    // planning kernel from the counts it was sent, so a receiver waits for
+    // arrive >= expect per source.
     unsigned *arrive_disp, *arrive_comb;                      // [N dst][N src]
     unsigned *expect_disp, *expect_comb;                      // [N dst][N src]
     int *routes;          // [N receiver][N source][route_len]
@@ -213,7 +215,7 @@ __device__ inline void st_payload(v4u *p, v4u v) {
 // A block copies `nrows` rows of `nvec` vectors each; vector v of the chunk lies
 // in row v / nvec.  src_of(row) / dst_of(row) return the row's byte address.
 // All loads of a batch are issued before its stores.
-template <int NT, class SrcFn, class DstFn>
+template <int NT, bool FENCED = false, class SrcFn, class DstFn>
 __device__ inline void copy_rows_flat(int nrows, int nvec, int tid, SrcFn src_of, DstFn dst_of) {
     if (nrows == 1) {                          // one row per block: addresses are uniform
         const v4u *s = (const v4u *)src_of(0);
@@ -225,7 +227,7 @@ __device__ inline void copy_rows_flat(int nrows, int nvec, int tid, SrcFn src_of
                 if (b + i * NT < nvec) r[i] = ld_stream(s + b + i * NT);
 #pragma unroll
             for (int i = 0; i < 4; ++i)
-                if (b + i * NT < nvec) st_stream(d + b + i * NT, r[i]);
+                if (b + i * NT < nvec) st_payload<FENCED, true>(d + b + i * NT, r[i]);
         }
         return;
     }
@@ -245,7 +247,7 @@ __device__ inline void copy_rows_flat(int nrows, int nvec, int tid, SrcFn src_of
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int v = b + i * NT;
-            if (v < total) st_stream((v4u *)dst_of(row[i]) + col[i], r[i]);
+            if (v < total) st_payload<FENCED, true>((v4u *)dst_of(row[i]) + col[i], r[i]);
         }
     }
 }

@@ -18,12 +18,13 @@ namespace {
 enum KernelId {
     KID_ROUTE_COUNT = 0, KID_ROUTE_PLAN, KID_DISPATCH_PACK, KID_DISPATCH_FABRIC,
     KID_DISPATCH_UNPACK, KID_COMBINE_PACK, KID_COMBINE_FABRIC, KID_COMBINE_REDUCE,
-    KID_DISPATCH_PACK_E4M3, KID_DISPATCH_FABRIC_PRIVATE
+    KID_DISPATCH_PACK_E4M3, KID_DISPATCH_FABRIC_PRIVATE, KID_TRANSFER_DONE
 };
 const char *kKernelNames[FL_KERNEL_COUNT] = {
     "route_count_kernel", "route_plan_kernel", "dispatch_pack_kernel", "fabric_copy_kernel(dispatch)",
     "dispatch_unpack_kernel", "combine_pack_kernel", "fabric_copy_kernel(combine)",
-    "combine_reduce_kernel", "dispatch_pack_e4m3_kernel", "fabric_copy_kernel(dispatch, private slots)"};
+    "combine_reduce_kernel", "dispatch_pack_e4m3_kernel", "fabric_copy_kernel(dispatch, private slots)",
+    "transfer_done_kernel"};
 
 constexpr int kEventPool = 64;
 constexpr long long kMaxFabricBlocks = 1 << 16;   // waves loop cheaply (no barriers)
@@ -59,7 +60,7 @@ int resolve(const fl_moe_config *c, Dims *D) {
         return FL_ERR_INVALID_ARG;
     if (c->dispatch_dtype == FL_DTYPE_E4M3_BLOCK128 && c->hidden % 128 != 0) return FL_ERR_ALIGNMENT;
     if (c->expert_align < 1 || c->expert_align > (1 << 16)) return FL_ERR_INVALID_ARG;
-    if (c->flags & ~(FL_FLAG_ZERO_PAD | FL_FLAG_UNORDERED_FABRIC)) return FL_ERR_INVALID_ARG;
+    if (c->flags & ~(FL_FLAG_ZERO_PAD | FL_FLAG_UNORDERED_FABRIC | FL_FLAG_PEER_PUSH)) return FL_ERR_INVALID_ARG;
     if (c->recv_capacity_rows < 0 || c->expert_capacity_rows < 0 || c->spin_limit < 0)
         return FL_ERR_INVALID_ARG;
     if (c->max_private_rows < 0 || c->reserved != 0) return FL_ERR_INVALID_ARG;
@@ -347,17 +348,45 @@ int fl_moe_dispatch_send(fl_moe_ctx *ctx, int rb, int rc, const void *x, void *s
     hipStream_t st = (hipStream_t)stream;
     const Dims &D = ctx->D;
     const Tables &W = ctx->W;
+    const bool push = D.flags & FL_FLAG_PEER_PUSH, fenced = D.flags & FL_FLAG_UNORDERED_FABRIC;
     if (D.dtype == FL_DTYPE_E4M3_BLOCK128) {
         LaunchTimer t(ctx, KID_DISPATCH_PACK_E4M3, st);
         const int per_block = kQuantThreads / kQuantLanes;       // quantisation blocks per workgroup
         const int slices = (D.scales_per_row + per_block - 1) / per_block;
-        dispatch_pack_e4m3_kernel<<<dim3((unsigned)D.T * slices, rc), dim3(kQuantThreads), 0, st>>>(
-            D, W, rb, (const char *)x, ctx->indices, ctx->num_tokens, slices);
+        const dim3 grid((unsigned)D.T * slices, rc), block(kQuantThreads);
+        const char *xp = (const char *)x;
+        if (push && fenced)
+            dispatch_pack_e4m3_kernel<true, true><<<grid, block, 0, st>>>(D, W, rb, xp, ctx->indices,
+                                                                          ctx->num_tokens, slices);
+        else if (push)
+            dispatch_pack_e4m3_kernel<true, false><<<grid, block, 0, st>>>(D, W, rb, xp, ctx->indices,
+                                                                           ctx->num_tokens, slices);
+        else
+            dispatch_pack_e4m3_kernel<false, false><<<grid, block, 0, st>>>(D, W, rb, xp, ctx->indices,
+                                                                            ctx->num_tokens, slices);
     } else {
         LaunchTimer t(ctx, KID_DISPATCH_PACK, st);
         const int slices = pack_slices(D.Bx, D.tune_slices);
-        dispatch_pack_kernel<<<dim3((unsigned)D.T * slices, rc), dim3(kPackThreads), 0, st>>>(
-            D, W, rb, (const char *)x, ctx->indices, ctx->num_tokens, slices);
+        const dim3 grid((unsigned)D.T * slices, rc), block(kPackThreads);
+        const char *xp = (const char *)x;
+        if (push && fenced)
+            dispatch_pack_kernel<true, true><<<grid, block, 0, st>>>(D, W, rb, xp, ctx->indices,
+                                                                     ctx->num_tokens, slices);
+        else if (push)
+            dispatch_pack_kernel<true, false><<<grid, block, 0, st>>>(D, W, rb, xp, ctx->indices,
+                                                                      ctx->num_tokens, slices);
+        else
+            dispatch_pack_kernel<false, false><<<grid, block, 0, st>>>(D, W, rb, xp, ctx->indices,
+                                                                       ctx->num_tokens, slices);
+    }
+    auto announce = [&](int combine) {         // stream-ordered: one add per finished transfer
+        if (fenced) return;                    // unordered: the copy kernels announce as they go
+        LaunchTimer t(ctx, KID_TRANSFER_DONE, st);
+        transfer_done_kernel<<<dim3(rc), dim3(kWave), 0, st>>>(D, W, rb, combine);
+    };
+    if (push) {                                // the rows are already in the peers' receive buffers
+        announce(0);
+        return launch_status();
     }
     FabricArgs A;
     A.src_base = W.bufA; A.src_rank_stride = D.bufA_rank_bytes;
@@ -396,6 +425,7 @@ int fl_moe_dispatch_send(fl_moe_ctx *ctx, int rb, int rc, const void *x, void *s
         else
             fabric_copy_kernel<false, 0, false><<<dim3(gx, rc), dim3(kCopyThreads), 0, st>>>(D, W, A, rb);
     }
+    announce(0);
     return launch_status();
 }
 
@@ -448,10 +478,23 @@ int fl_moe_combine_send(fl_moe_ctx *ctx, int rb, int rc, const void *expert_y, v
     const Tables &W = ctx->W;
     const int rbk = rows_per_block(D.Bc, D.tune_rows);
     const unsigned gx = capped_grid((D.expert_cap + rbk - 1) / rbk, rc, kMaxRowBlocks);
+    const bool push = D.flags & FL_FLAG_PEER_PUSH, fenced = D.flags & FL_FLAG_UNORDERED_FABRIC;
     {
         LaunchTimer t(ctx, KID_COMBINE_PACK, st);
-        combine_pack_kernel<<<dim3(gx, rc), dim3(kCopyThreads), 0, st>>>(
-            D, W, rb, (const char *)expert_y, rbk);
+        const dim3 grid(gx, rc), block(kCopyThreads);
+        const char *yp = (const char *)expert_y;
+        if (push && fenced) combine_pack_kernel<true, true><<<grid, block, 0, st>>>(D, W, rb, yp, rbk);
+        else if (push) combine_pack_kernel<true, false><<<grid, block, 0, st>>>(D, W, rb, yp, rbk);
+        else combine_pack_kernel<false, false><<<grid, block, 0, st>>>(D, W, rb, yp, rbk);
+    }
+    auto announce = [&]() {
+        if (fenced) return;
+        LaunchTimer t(ctx, KID_TRANSFER_DONE, st);
+        transfer_done_kernel<<<dim3(rc), dim3(kWave), 0, st>>>(D, W, rb, 1);
+    };
+    if (push) {                                // the rows are already in the sources' receive buffers
+        announce();
+        return launch_status();
     }
     FabricArgs A;
     A.src_base = W.bufB; A.src_rank_stride = D.bufB_rank_bytes;
@@ -476,6 +519,7 @@ int fl_moe_combine_send(fl_moe_ctx *ctx, int rb, int rc, const void *expert_y, v
         else
             fabric_copy_kernel<false, 1, false><<<dim3(gxf, rc), dim3(kCopyThreads), 0, st>>>(D, W, A, rb);
     }
+    announce();
     return launch_status();
 }
 

@@ -22,6 +22,13 @@ constexpr int kMaxRowsPerBlock = 64;
 // bound for d).  Each copy carries a sidecar of K words naming, for every expert
 // of the token that lives on d, the local expert and the token's rank among s's
 // tokens of that expert; the receiver turns that into an expert-major row.
+//
+// PUSH (every peer's receive buffer can be stored to, section Dispatch: within a
+// node payloads are pushed from the send kernel): the copies and their sidecars
+// go straight into the destinations' receive buffers, and the block adds the
+// 16-byte units it wrote to arrive[destination][source] itself; no send buffer is
+// filled and no scatter follows.  FENCED applies to PUSH only (unordered fabric).
+template <bool PUSH, bool FENCED>
 __global__ __launch_bounds__(kPackThreads) void dispatch_pack_kernel(
     Dims D, Tables W, int rank_begin, const char *__restrict__ x,
     const int *__restrict__ indices, const int *__restrict__ num_tokens, int slices) {
@@ -38,20 +45,21 @@ __global__ __launch_bounds__(kPackThreads) void dispatch_pack_kernel(
         my_row = W.send_row[pair0 + tid];
         my_d = indices[pair0 + tid] / El;
         s_meta[tid] = W.pair_meta[pair0 + tid];
-        s_row[tid] = my_row;
         s_dst[tid] = my_d;
         if (my_row >= 0)                       // this copy's row in d's receive buffer
             target = recv_buffer_row(D.N, D.P, s, my_row - W.send_off[(size_t)s * (D.N + 1) + my_d],
                                      W.dst_off[(size_t)s * D.N + my_d]);
+        s_row[tid] = (PUSH && my_row >= 0) ? target : my_row;
     }
     __syncthreads();
     if (slice == 0 && tid < K && my_row >= 0) {   // sidecar and fabric target of this copy
-        unsigned *meta = W.send_meta + ((size_t)s * D.send_cap + my_row) * D.KM;
+        unsigned *meta = PUSH ? W.recv_meta + ((size_t)my_d * D.recv_rows + target) * D.KM
+                              : W.send_meta + ((size_t)s * D.send_cap + my_row) * D.KM;
         int m = 0;
         for (int k = 0; k < K; ++k)
-            if (s_dst[k] == my_d) meta[m++] = s_meta[k];
-        for (; m < D.KM; ++m) meta[m] = kNoEntry;
-        W.fab_dst_disp[(size_t)s * D.send_cap + my_row] = make_int2(my_d, target);
+            if (s_dst[k] == my_d) st_word<PUSH && FENCED>((int *)meta + m++, (int)s_meta[k]);
+        for (; m < D.KM; ++m) st_word<PUSH && FENCED>((int *)meta + m, (int)kNoEntry);
+        if (!PUSH) W.fab_dst_disp[(size_t)s * D.send_cap + my_row] = make_int2(my_d, target);
     }
     const int nvec = (int)(D.Bx / 16);
     const int per = (nvec + slices - 1) / slices;          // vectors of this slice: [v0, v1)
@@ -66,11 +74,19 @@ __global__ __launch_bounds__(kPackThreads) void dispatch_pack_kernel(
         for (int k = 0; k < K; ++k) {
             const int row = s_row[k];          // uniform: one copy per distinct destination
             if (row < 0) continue;
-            v4u *dst = (v4u *)(sendbuf + (size_t)row * D.Bw);
+            char *base = PUSH ? W.bufB + (size_t)s_dst[k] * D.bufB_rank_bytes : sendbuf;
+            v4u *dst = (v4u *)(base + (size_t)row * D.Bw);
 #pragma unroll
             for (int i = 0; i < 4; ++i)
-                if (b + i * kPackThreads < v1) st_stream(dst + b + i * kPackThreads, r[i]);
+                if (b + i * kPackThreads < v1)
+                    st_payload<PUSH && FENCED, true>(dst + b + i * kPackThreads, r[i]);
         }
+    }
+    if (PUSH && FENCED) {                      // what this block delivered, per destination
+        stores_done<FENCED>();
+        __syncthreads();
+        if (tid < K && my_row >= 0 && v1 > v0)
+            add_counter(W.arrive_disp + (size_t)my_d * D.N + s, (unsigned)(v1 - v0));
     }
 }
 
@@ -102,6 +118,7 @@ constexpr int kQuantThreads = 256; // 32 quantisation blocks per workgroup
 // One block of kQuantThreads threads takes 32 quantisation blocks of one token;
 // every lane loads 32 bytes, takes part in an 8-lane max, and stores 16 bytes of
 // e4m3 per destination copy; the group's first lane stores the scale.
+template <bool PUSH, bool FENCED>   // as in dispatch_pack_kernel
 __global__ __launch_bounds__(kQuantThreads) void dispatch_pack_e4m3_kernel(
     Dims D, Tables W, int rank_begin, const char *__restrict__ x,
     const int *__restrict__ indices, const int *__restrict__ num_tokens, int slices) {
@@ -118,20 +135,21 @@ __global__ __launch_bounds__(kQuantThreads) void dispatch_pack_e4m3_kernel(
         my_row = W.send_row[pair0 + tid];
         my_d = indices[pair0 + tid] / El;
         s_meta[tid] = W.pair_meta[pair0 + tid];
-        s_row[tid] = my_row;
         s_dst[tid] = my_d;
         if (my_row >= 0)
             target = recv_buffer_row(D.N, D.P, s, my_row - W.send_off[(size_t)s * (D.N + 1) + my_d],
                                      W.dst_off[(size_t)s * D.N + my_d]);
+        s_row[tid] = (PUSH && my_row >= 0) ? target : my_row;
     }
     __syncthreads();
     if (slice == 0 && tid < K && my_row >= 0) {
-        unsigned *meta = W.send_meta + ((size_t)s * D.send_cap + my_row) * D.KM;
+        unsigned *meta = PUSH ? W.recv_meta + ((size_t)my_d * D.recv_rows + target) * D.KM
+                              : W.send_meta + ((size_t)s * D.send_cap + my_row) * D.KM;
         int m = 0;
         for (int k = 0; k < K; ++k)
-            if (s_dst[k] == my_d) meta[m++] = s_meta[k];
-        for (; m < D.KM; ++m) meta[m] = kNoEntry;
-        W.fab_dst_disp[(size_t)s * D.send_cap + my_row] = make_int2(my_d, target);
+            if (s_dst[k] == my_d) st_word<PUSH && FENCED>((int *)meta + m++, (int)s_meta[k]);
+        for (; m < D.KM; ++m) st_word<PUSH && FENCED>((int *)meta + m, (int)kNoEntry);
+        if (!PUSH) W.fab_dst_disp[(size_t)s * D.send_cap + my_row] = make_int2(my_d, target);
     }
     const int nblk = D.scales_per_row;                          // 128-element blocks in the row
     const int blk = slice * (kQuantThreads / kQuantLanes) + tid / kQuantLanes;
@@ -174,13 +192,25 @@ __global__ __launch_bounds__(kQuantThreads) void dispatch_pack_e4m3_kernel(
     for (int k = 0; k < K; ++k) {
         const int row = s_row[k];
         if (row < 0) continue;
-        char *dst = sendbuf + (size_t)row * D.Bw;
-        if (live) st_stream((v4u *)dst + (size_t)blk * kQuantLanes + sub, out);
+        char *dst = (PUSH ? W.bufB + (size_t)s_dst[k] * D.bufB_rank_bytes : sendbuf) + (size_t)row * D.Bw;
+        if (live) st_payload<PUSH && FENCED, true>((v4u *)dst + (size_t)blk * kQuantLanes + sub, out);
         if (scale_vectors) {
-            if (tid < nsv) st_stream((v4u *)(dst + D.Be) + blk0 / 4 + tid, ((const v4u *)s_scale)[tid]);
+            if (tid < nsv)
+                st_payload<PUSH && FENCED, true>((v4u *)(dst + D.Be) + blk0 / 4 + tid,
+                                                 ((const v4u *)s_scale)[tid]);
         } else if (live && sub == 0) {
-            ((float *)(dst + D.Be))[blk] = scale;
+            st_word<PUSH && FENCED>((int *)(dst + D.Be) + blk, __float_as_int(scale));
         }
+    }
+    if (PUSH && FENCED) {
+        // Units of the row this block wrote: 8 per quantisation block of codes, and the
+        // 16-byte units its scales fall into (blocks start on multiples of 32 scales, so
+        // no unit is shared between blocks; the row's last unit may be part padding).
+        const int n_live = min(nblk - blk0, kQuantThreads / kQuantLanes);
+        stores_done<FENCED>();
+        __syncthreads();
+        if (tid < K && my_row >= 0 && n_live > 0)
+            add_counter(W.arrive_disp + (size_t)my_d * D.N + s, (unsigned)(n_live * 8 + (n_live + 3) / 4));
     }
 }
 
@@ -191,11 +221,13 @@ __global__ __launch_bounds__(kQuantThreads) void dispatch_pack_e4m3_kernel(
 // packed, so a wave needs one small load before its payload loads; a version
 // that searched the offset tables per wave measured 25 % slower).  Waves work on
 // their own: a row is shared by `waves_per_row` waves, each copies its slice
-// with four loads in flight, then adds the number of 16-byte units it delivered
-// to arrive[destination][source] with an atomic whose result nobody waits for.
-// No barrier, no shared memory, no ticket: the counters only ever say "this much
-// of source s's payload has landed", in whatever order waves finish, and a
-// receiver compares them with what the counts told it to expect.
+// with four loads in flight.  No barrier, no shared memory, no ticket.  In
+// unordered mode (FENCED) a wave then adds the number of 16-byte units it
+// delivered to arrive[destination][source] with an atomic whose result nobody
+// waits for: the counters only ever say "this much of source s's payload has
+// landed", in whatever order waves finish.  In stream-ordered mode nobody may
+// look before the kernel has ended, and transfer_done_kernel announces each
+// whole transfer afterwards.
 struct FabricArgs {
     const char *src_base; long long src_rank_stride;
     char *dst_base;       long long dst_rank_stride;
@@ -238,10 +270,12 @@ __device__ inline void fabric_send_row(const Dims &D, const FabricArgs &A, int s
         v4u *md = (v4u *)(A.dst_meta + (size_t)dst_rank * A.dst_meta_rank_stride) + (size_t)dst_row * mv;
         if (lane < mv) st_payload<FENCED, STREAMING>(md + lane, ms[lane]);
     }
-    const int full = nvec / step, rem = nvec - full * step;
-    const int mine = full * kWave + min(max(rem - sub * kWave, 0), kWave);
-    stores_done<FENCED>();
-    if (lane == 0 && mine > 0) add_counter(A.arrive + (size_t)dst_rank * N + s, (unsigned)mine);
+    if (FENCED) {          // stream-ordered launches are followed by transfer_done_kernel instead
+        const int full = nvec / step, rem = nvec - full * step;
+        const int mine = full * kWave + min(max(rem - sub * kWave, 0), kWave);
+        stores_done<FENCED>();
+        if (lane == 0 && mine > 0) add_counter(A.arrive + (size_t)dst_rank * N + s, (unsigned)mine);
+    }
 }
 
 template <bool FENCED, int PHASE, bool STREAMING>   // PHASE only names the launch: 0 dispatch, 1 combine
@@ -287,6 +321,29 @@ __global__ __launch_bounds__(kCopyThreads) void fabric_private_kernel(Dims D, Ta
         const int d = q / P, i = q - d * P;
         const int lo = A.seg_off[(size_t)s * (N + 1) + d], hi = A.seg_off[(size_t)s * (N + 1) + d + 1];
         if (i < hi - lo) fabric_send_row<FENCED, STREAMING>(D, A, s, lo + i, d, s * P + i, sub, lane);
+    }
+}
+
+// ------------------------------------------------------------------ completion of whole transfers
+// Stream-ordered mode: launched right after the kernel(s) that moved the payload
+// of ranks [rank_begin, ...), so every byte is in place when it runs.  One add
+// per (sender, receiver) announces the whole transfer, like the single immediate
+// a NIC delivers after a WRITE (section TransferEngine, ImmCounter): lane = peer.
+// Per-wave announcements from inside the copy kernels cost more than they give
+// in this mode: adds to one counter from many compute dies serialise (about
+// 0.2 us each), which made skewed routing several times slower.
+__global__ __launch_bounds__(kWave) void transfer_done_kernel(Dims D, Tables W, int rank_begin,
+                                                              int combine) {
+    const int r = rank_begin + blockIdx.x, N = D.N;
+    const int *off = (combine ? W.cs_off : W.send_off) + (size_t)r * (N + 1);
+    unsigned *arrive = combine ? W.arrive_comb : W.arrive_disp;
+    const unsigned units = (unsigned)((combine ? D.Bc : D.Bw) / 16);
+    const int ok = W.plan_ok[r];               // all three loads are issued together
+    for (int p = threadIdx.x; p < N; p += kWave) {
+        // dispatch: r sent M[r][p] rows to p; combine: r replied to p with every row of
+        // r's experts that came from p
+        const int rows = off[p + 1] - off[p];
+        if (ok && rows) add_counter(arrive + (size_t)p * N + r, (unsigned)rows * units);
     }
 }
 
@@ -420,11 +477,16 @@ __global__ __launch_bounds__(kCopyThreads) void dispatch_unpack_kernel(
 // (contiguous per expert in the grouped layout) into one contiguous reply:
 // combine-send row q of source s and local expert j comes from expert-major row
 // base_x[d][j][s] + (q - cs_base[d][s][j]).
+//
+// PUSH: the rows go straight into the sources' combine receive buffers and the
+// block adds each row's units to arrive[source][this rank]; FENCED as above.
+template <bool PUSH, bool FENCED>
 __global__ __launch_bounds__(kCopyThreads) void combine_pack_kernel(
     Dims D, Tables W, int rank_begin, const char *__restrict__ expert_y, int rows_per_block) {
     const int d = rank_begin + blockIdx.y, tid = threadIdx.x, N = D.N, El = D.El;
     __shared__ int off[FL_MAX_RANKS + 1];
     __shared__ int src_row[kMaxRowsPerBlock];
+    __shared__ int2 push_to[kMaxRowsPerBlock];     // PUSH: (source rank, row of its combine receive buffer)
     if (!W.plan_ok[d]) return;
     // grids are sized from capacities: blocks beyond the rows in use leave at once
     const int total = W.cs_off[(size_t)d * (N + 1) + N];
@@ -442,16 +504,32 @@ __global__ __launch_bounds__(kCopyThreads) void combine_pack_kernel(
             const int *csb = W.cs_base + ((size_t)d * N + s) * El;
             const int j = seg_of(csb, El, q);
             src_row[tid] = W.base_x[((size_t)d * El + j) * N + s] + (q - csb[j]);
-            W.fab_dst_comb[(size_t)d * D.expert_cap + q] =
-                make_int2(s, W.comb_dst_off[(size_t)d * N + s] + (q - off[s]));
+            const int2 to = make_int2(s, W.comb_dst_off[(size_t)d * N + s] + (q - off[s]));
+            if (PUSH) push_to[tid] = to;
+            else W.fab_dst_comb[(size_t)d * D.expert_cap + q] = to;
         }
         __syncthreads();
-        char *out = W.bufB + (size_t)d * D.bufB_rank_bytes + (size_t)q0 * D.Bc;
-        copy_rows_flat<kCopyThreads>(
-            q1 - q0, nvec, tid,
-            [&](int r) { return yd + (size_t)src_row[r] * D.Bc; },
-            [&](int r) { return out + (size_t)r * D.Bc; });
-        __syncthreads();                       // src_row is rewritten by the next chunk
+        if (PUSH) {
+            copy_rows_flat<kCopyThreads, FENCED>(
+                q1 - q0, nvec, tid,
+                [&](int r) { return yd + (size_t)src_row[r] * D.Bc; },
+                [&](int r) {
+                    return W.bufA + (size_t)push_to[r].x * D.bufA_rank_bytes + (size_t)push_to[r].y * D.Bc;
+                });
+            if (FENCED) {
+                stores_done<FENCED>();
+                __syncthreads();
+                if (tid < q1 - q0)
+                    add_counter(W.arrive_comb + (size_t)push_to[tid].x * N + d, (unsigned)nvec);
+            }
+        } else {
+            char *out = W.bufB + (size_t)d * D.bufB_rank_bytes + (size_t)q0 * D.Bc;
+            copy_rows_flat<kCopyThreads>(
+                q1 - q0, nvec, tid,
+                [&](int r) { return yd + (size_t)src_row[r] * D.Bc; },
+                [&](int r) { return out + (size_t)r * D.Bc; });
+        }
+        __syncthreads();                       // the row plan is rewritten by the next chunk
     }
 }
 

@@ -18,7 +18,8 @@ FL_STATUS_BAD_INDEX, FL_STATUS_CAPACITY, FL_STATUS_TIMEOUT = 1, 2, 4
 FL_DTYPE_BF16, FL_DTYPE_E4M3_BLOCK128 = 0, 1
 FL_FLAG_ZERO_PAD = 1
 FL_FLAG_UNORDERED_FABRIC = 2
-FL_KERNEL_COUNT = 10
+FL_FLAG_PEER_PUSH = 4
+FL_KERNEL_COUNT = 11
 
 
 class fl_moe_config(C.Structure):
@@ -211,13 +212,15 @@ class MoEShuffle:
 
     def __init__(self, n_ranks, n_experts, max_tokens, top_k, hidden, dispatch_dtype="bf16",
                  expert_align=1, zero_pad=False, recv_capacity_rows=0, expert_capacity_rows=0,
-                 spin_limit=0, unordered_fabric=False, max_private_rows=0, device="cuda:0"):
+                 spin_limit=0, unordered_fabric=False, max_private_rows=0, peer_push=False,
+                 device="cuda:0"):
         self.device = torch.device(device)
         self.cfg = fl_moe_config(
             n_ranks, n_experts, max_tokens, top_k, hidden,
             FL_DTYPE_BF16 if dispatch_dtype == "bf16" else FL_DTYPE_E4M3_BLOCK128,
             expert_align, (FL_FLAG_ZERO_PAD if zero_pad else 0)
-            | (FL_FLAG_UNORDERED_FABRIC if unordered_fabric else 0),
+            | (FL_FLAG_UNORDERED_FABRIC if unordered_fabric else 0)
+            | (FL_FLAG_PEER_PUSH if peer_push else 0),
             recv_capacity_rows, expert_capacity_rows, spin_limit, max_private_rows, 0)
         self.sizes = fl_moe_query_sizes(self.cfg)
         self.N, self.E, self.T, self.K, self.H = n_ranks, n_experts, max_tokens, top_k, hidden

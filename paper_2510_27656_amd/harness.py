@@ -21,7 +21,8 @@ def to_device(inp: Inputs, device="cuda:0"):
 
 
 def make_shuffle(inp: Inputs, expert_align=1, zero_pad=False, capacity_factor=None,
-                 spin_limit=0, unordered_fabric=False, max_private_rows=0, device="cuda:0"):
+                 spin_limit=0, unordered_fabric=False, max_private_rows=0, peer_push=False,
+                 device="cuda:0"):
     """capacity_factor None = worst-case capacities, else factor x the mean rows per rank."""
     wl = inp.wl
     recv_cap = expert_cap = 0
@@ -34,7 +35,7 @@ def make_shuffle(inp: Inputs, expert_align=1, zero_pad=False, capacity_factor=No
                             zero_pad=zero_pad, recv_capacity_rows=recv_cap,
                             expert_capacity_rows=expert_cap, spin_limit=spin_limit,
                             unordered_fabric=unordered_fabric,
-                            max_private_rows=max_private_rows, device=device)
+                            max_private_rows=max_private_rows, peer_push=peer_push, device=device)
 
 
 def row_gain(sh: flmoe.MoEShuffle, gain: torch.Tensor):

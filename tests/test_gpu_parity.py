@@ -44,14 +44,14 @@ def check_tables(sh, ref, N):
 
 
 def run_and_compare(inp, align=1, zero_pad=False, capacity_factor=None, ranks_split=False,
-                    unordered=False, private_rows=0):
+                    unordered=False, private_rows=0, push=False):
     wl = inp.wl
     N, T = wl.n_ranks, wl.tokens
     ref = oracle_step(inp, align, zero_pad=True)
     dev = harness.to_device(inp)
     sh = harness.make_shuffle(inp, expert_align=align, zero_pad=zero_pad,
                               capacity_factor=capacity_factor, unordered_fabric=unordered,
-                              max_private_rows=private_rows)
+                              max_private_rows=private_rows, peer_push=push)
     try:
         if wl.dispatch_dtype == "bf16":
             sh.expert_x.view(torch.int16).fill_(POISON)
@@ -415,10 +415,12 @@ def test_unordered_mode_with_e4m3_dispatch():
 
 
 # ------------------------------------------------------------------ senders and receivers overlapping in time
-@pytest.mark.parametrize("name,shuffled", [("ragged_520", False), ("ragged_520", True),
-                                           ("overlap_7168", False), ("overlap_7168", True),
-                                           ("dsv3_decode", False)])
-def test_unordered_fabric_with_concurrent_send_and_receive(name, shuffled):
+@pytest.mark.parametrize("name,shuffled,push", [("ragged_520", False, False), ("ragged_520", True, False),
+                                                ("overlap_7168", False, False), ("overlap_7168", True, False),
+                                                ("dsv3_decode", False, False),
+                                                ("ragged_520", True, True), ("overlap_7168", False, True),
+                                                ("dsv3_decode", True, True)])
+def test_unordered_fabric_with_concurrent_send_and_receive(name, shuffled, push):
     if name == "overlap_7168":
         wl = wlmod.custom("overlap_7168", 8, 64, 128, 7168, 8, seed=61)
     elif name == "dsv3_decode":
@@ -429,7 +431,8 @@ def test_unordered_fabric_with_concurrent_send_and_receive(name, shuffled):
     N = wl.n_ranks
     ref = oracle_step(inp)
     dev = harness.to_device(inp)
-    sh = harness.make_shuffle(inp, unordered_fabric=True, capacity_factor=2.0 if N >= 8 else None)
+    sh = harness.make_shuffle(inp, unordered_fabric=True, capacity_factor=2.0 if N >= 8 else None,
+                              peer_push=push)
     try:
         order = None
         if shuffled:      # one launch per sender, in a seeded random order
@@ -558,6 +561,75 @@ def test_private_slots_shrink_the_shared_range_needed():
                 assert (bits(sh.expert_x) == POISON).all()
         finally:
             sh.close()
+
+
+# ------------------------------------------------------------------ peer push: no send buffer, no scatter
+@pytest.mark.parametrize("name", list(CASES))
+def test_parity_peer_push_small(name):
+    """FL_FLAG_PEER_PUSH: the send kernels store into the peers' receive buffers
+    themselves (section Dispatch, pushes within a node).  Same results."""
+    inp = wlmod.make_inputs(CASES[name]())
+    sh, _, _ = run_and_compare(inp, push=True, align=4, zero_pad=True)
+    sh.close()
+
+
+@pytest.mark.parametrize("kw", [dict(unordered=True), dict(private_rows=7), dict(ranks_split=True),
+                                dict(unordered=True, private_rows=1000, ranks_split=True),
+                                dict(capacity_factor=2.0)])
+def test_parity_peer_push_with_the_other_modes(kw):
+    inp = wlmod.make_inputs(CASES["ragged_520"]())
+    sh, _, _ = run_and_compare(inp, push=True, **kw)
+    sh.close()
+
+
+@pytest.mark.parametrize("name", list(FP8_CASES))
+@pytest.mark.parametrize("unordered", [False, True])
+def test_parity_peer_push_e4m3(name, unordered):
+    inp = wlmod.make_inputs(FP8_CASES[name]())
+    sh, _, _ = run_and_compare(inp, push=True, unordered=unordered)
+    sh.close()
+
+
+@pytest.mark.parametrize("name", ["dsv3_decode", "qwen3_skew", "dsv3_fp8"])
+def test_parity_peer_push_named_workloads(name):
+    inp = wlmod.make_inputs(wlmod.WORKLOADS[name])
+    sh, _, _ = run_and_compare(inp, push=True)
+    sh.close()
+
+
+@pytest.mark.parametrize("name", ["ragged_520", "fp8_k16"])
+def test_peer_push_counters_and_untouched_send_buffer(name):
+    """Pushed rows are counted in the same units as scattered ones (arrive ==
+    expect == rows x 16-byte units per wire row, also for e4m3 rows whose scale
+    tail is not a whole vector), and dispatch_send leaves the send buffer alone."""
+    wl = CASES[name]() if name in CASES else FP8_CASES[name]()
+    inp = wlmod.make_inputs(wl)
+    dev = harness.to_device(inp)
+    ref = oracle_step(inp)
+    sh = harness.make_shuffle(inp, peer_push=True)
+    try:
+        buf_a = sh.debug()["buf_a"]
+        buf_a.fill_(0x5A)
+        sh.layout(dev["indices"], dev["num_tokens"])
+        sh.dispatch_send(dev["x"])
+        torch.cuda.synchronize()
+        assert bool((buf_a == 0x5A).all()), "push mode wrote a send buffer"
+        sh.dispatch_recv()
+        y = harness.expert_stage(sh, dev["gain"], wl.expert == "identity")
+        sh.combine_send(y)
+        sh.combine_reduce(dev["weights"])
+        torch.cuda.synchronize()
+        assert sh.status() == 0
+        dbg = sh.debug()
+        units = int(sh.sizes.wire_row_bytes) // 16
+        assert (dbg["arrive_disp"].cpu().numpy() == ref.lay.M.T.astype(np.int64) * units).all()
+        assert (dbg["expect_disp"].cpu().numpy() == ref.lay.M.T.astype(np.int64) * units).all()
+        pairs = ref.lay.C.reshape(wl.n_ranks, wl.n_ranks, -1).sum(2)
+        cunits = wl.hidden * 2 // 16
+        assert (dbg["arrive_comb"].cpu().numpy() == pairs * cunits).all()
+        assert (dbg["expect_comb"].cpu().numpy() == pairs * cunits).all()
+    finally:
+        sh.close()
 
 
 # ------------------------------------------------------------------ failure handling

@@ -46,8 +46,8 @@ def algorithmic_bytes(wl, ttot, D, P, sizes, push=False):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=0, help="0 = 200, or 10 for the prefill workload")
-    ap.add_argument("--warmup", type=int, default=-1, help="-1 = 20, or 2 for the prefill workload")
+    ap.add_argument("--steps", type=int, default=0, help="0 = 1000, or 10 for the prefill workload")
+    ap.add_argument("--warmup", type=int, default=-1, help="-1 = 200, or 2 for the prefill workload")
     ap.add_argument("--workload", default="dsv3_decode")
     ap.add_argument("--capacity-factor", type=float, default=1.5,
                     help="per-rank buffer capacity as a multiple of the mean load (0 = worst case)")
@@ -64,6 +64,9 @@ def main():
     ap.add_argument("--private-rows", type=int, default=0,
                     help="first rows per (source, destination) sent to private slots in a scatter "
                          "of their own (ablation of section Ablation: Private Buffer Size)")
+    ap.add_argument("--headline-only", action="store_true",
+                    help="skip the side measurements that launch the kernels at other sizes or in "
+                         "other modes (single-rank split, peer-push variant); for profiler runs")
     ap.add_argument("--profile-steps", type=int, default=200)
     ap.add_argument("--counters", action="store_true",
                     help="short run for `rocprofv3 --pmc`: a few steps plus one plain 1 GiB copy "
@@ -81,9 +84,9 @@ def main():
     wl = workloads.WORKLOADS[args.workload]
     big = wl.tokens >= 2048
     if args.steps <= 0:
-        args.steps = 10 if big else 200
+        args.steps = 10 if big else 1000
     if args.warmup < 0:
-        args.warmup = 2 if big else 20
+        args.warmup = 2 if big else 200
     if big:
         args.profile_steps = min(args.profile_steps, 5)
         args.no_cpu_baseline = True      # the oracle cannot lay this workload out in seconds
@@ -185,6 +188,32 @@ def main():
     dispatch_us = call_us["layout"] + call_us["dispatch_send"] + call_us["dispatch_recv"]
     combine_us = call_us["combine_send"] + call_us["combine_reduce"]
 
+    # One real rank's share (rank_count = 1): rank 0's four payload calls timed alone, the
+    # other ranks' launches issued around them outside the brackets.  The layout call
+    # cannot be split this way (its planning kernel waits for every peer's counts).
+    single_rank_us = None
+    if wl.n_ranks > 1 and not big and not args.headline_only:
+        me, rest = (0, 1), (1, wl.n_ranks - 1)
+        y = sh.expert_x if expert_y is None else expert_y
+        reps = min(args.profile_steps, 50)
+        sev = [[torch.cuda.Event(enable_timing=True) for _ in range(8)] for _ in range(reps)]
+        for i in range(reps):
+            e = sev[i]
+            sh.layout(dev["indices"], dev["num_tokens"])
+            sh.dispatch_send(dev["x"], rest)
+            e[0].record(); sh.dispatch_send(dev["x"], me); e[1].record()
+            e[2].record(); sh.dispatch_recv(me); e[3].record()
+            sh.dispatch_recv(rest)
+            sh.combine_send(y, rest)
+            e[4].record(); sh.combine_send(y, me); e[5].record()
+            e[6].record(); sh.combine_reduce(dev["weights"], me); e[7].record()
+            sh.combine_reduce(dev["weights"], rest)
+        torch.cuda.synchronize()
+        assert sh.status() == 0
+        single_rank_us = {c: round(float(np.median([sev[i][2 * j].elapsed_time(sev[i][2 * j + 1])
+                                                    for i in range(reps)])) * 1e3, 1)
+                          for j, c in enumerate(calls[1:])}
+
     # per-kernel durations (HIP events inside the library, on the same stream)
     flmoe.fl_moe_profile_enable(sh.ctx, 1)
     for _ in range(args.profile_steps):
@@ -226,6 +255,27 @@ def main():
     copy_gbps = 2 * (1 << 30) / (float(np.median([a.elapsed_time(b) for a, b in ce[2:]])) * 1e-3) / 1e9
     del flush_src, flush_dst
 
+    # The same step with FL_FLAG_PEER_PUSH, beside the headline: fewer bytes by
+    # construction, so its GB/s is computed against its own byte count.
+    push_line = None
+    if not args.push and not big and not args.unordered and not args.headline_only:
+        shp = harness.make_shuffle(inp, capacity_factor=cf, max_private_rows=args.private_rows,
+                                   peer_push=True)
+        _, pd, pc = algorithmic_bytes(wl, ttot, D, P, shp.sizes, True)
+        for _ in range(args.warmup):
+            harness.run_hot_path(shp, dev, expert_y)
+        torch.cuda.synchronize()
+        p0 = time.perf_counter()
+        for _ in range(args.steps):
+            harness.run_hot_path(shp, dev, expert_y)
+        torch.cuda.synchronize()
+        pms = (time.perf_counter() - p0) * 1e3 / args.steps
+        assert shp.status() == 0
+        shp.close()
+        push_line = {"ms_per_step": round(pms, 4), "algorithmic_bytes": pd + pc,
+                     "value": round((pd + pc) / (pms * 1e-3) / 1e9, 1), "unit": "GB/s",
+                     "frac_of_hbm_peak": round((pd + pc) / (pms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)}
+
     cpu = None
     if not args.no_cpu_baseline:
         from oracle.reference_step import oracle_step
@@ -264,9 +314,11 @@ def main():
         "frac_of_copy_ceiling": round(value / copy_gbps, 4),
         "latency_us": latency_us,
         "call_us": {k: round(v, 1) for k, v in call_us.items()},
+        "single_rank_call_us": single_rank_us,
         "kernel_us": {k: round(v, 2) for k, v in kern_us.items()},
         "kernel_gbps": {k: round(per_kernel[k] / (kern_us[k] * 1e-6) / 1e9, 1)
                         for k in kern_us if k in per_kernel},
+        "peer_push_variant": push_line,
         "roofline": roofline, "cpu_baseline": cpu,
     }
     sh.close()

@@ -232,6 +232,47 @@ void orc_combine(int N, int E, int Tmax, int K, int H,
         }
 }
 
+/* ---------- O5b: combine with sender-side partial sums (section Comparison with
+ * DeepEP and section Performance, prefill: tokens are pre-accumulated on the
+ * sending side, which moves fewer bytes but reduces the accumulation precision
+ * to bf16 between the two stages).  The paper names the idea, not the
+ * arithmetic; the definition taken here:
+ *   group the K experts of token (s,t) by the rank that hosts them;
+ *   partial(d) = bf16( fp32 fused multiply-add chain from +0 over the token's
+ *                experts on rank d, in ascending k, weight times row )
+ *   out[s][t]  = bf16( fp32 sum from +0 of float(partial(d)), ranks taken in
+ *                the order of their first k )
+ * Weights are applied on the expert's rank, so the receiver only adds.       */
+void orc_combine_partial(int N, int E, int Tmax, int K, int H,
+                         const int32_t *num_tokens, const int32_t *indices,
+                         const int32_t *slot, const float *weights, const uint16_t *Y,
+                         int64_t y_rank_stride, uint16_t *out) {
+    int El = E / N;
+    for (int s = 0; s < N; ++s)
+        for (int t = 0; t < num_tokens[s]; ++t) {
+            size_t tok = (size_t)s * Tmax + t;
+            for (int h = 0; h < H; ++h) {
+                float total = 0.0f;
+                for (int k = 0; k < K; ++k) {
+                    int d = owner_of(indices[tok * K + k], El);
+                    int first = 1;              /* is k the first expert of the token on rank d? */
+                    for (int k2 = 0; k2 < k; ++k2)
+                        if (owner_of(indices[tok * K + k2], El) == d) first = 0;
+                    if (!first) continue;
+                    float part = 0.0f;          /* rank d's share, accumulated on rank d */
+                    for (int k2 = k; k2 < K; ++k2) {
+                        if (owner_of(indices[tok * K + k2], El) != d) continue;
+                        const uint16_t *row =
+                            Y + (size_t)d * y_rank_stride + (size_t)slot[tok * K + k2] * H;
+                        part = fmaf(weights[tok * K + k2], bf16_to_f32(row[h]), part);
+                    }
+                    total = total + bf16_to_f32(f32_to_bf16_rne(part));
+                }
+                out[tok * H + h] = f32_to_bf16_rne(total);
+            }
+        }
+}
+
 /* Stand-in expert (harness stage between dispatch and combine, not part of the
  * shuffle): every row of expert e is scaled by g[e]; y = bf16(float(x) * g).
  * Applied in place over one rank's layout, padding rows untouched.             */

@@ -115,6 +115,19 @@ def combine(N, E, K, num_tokens, indices, slot, weights, Y, y_rank_stride_rows, 
     return (out, acc) if return_acc else out
 
 
+
+def combine_partial(N, E, K, num_tokens, indices, slot, weights, Y, y_rank_stride_rows, H):
+    """Combine with one bf16 partial sum per (token, expert rank); same arguments as combine."""
+    Tmax = indices.shape[1]
+    _chk(indices, np.int32, (N, Tmax, K))
+    _chk(slot, np.int32, (N, Tmax, K))
+    _chk(weights, np.float32, (N, Tmax, K))
+    _chk(Y, np.uint16)
+    out = np.zeros((N, Tmax, H), np.uint16)
+    lib().orc_combine_partial(N, E, Tmax, K, H, _p(num_tokens), _p(indices), _p(slot), _p(weights),
+                              _p(Y), C.c_int64(y_rank_stride_rows * H), _p(out))
+    return out
+
 def expert_scale_rank(d, N, E, lay, g, H, rows):
     _chk(rows, np.uint16)
     _chk(g, np.float32, (E,))

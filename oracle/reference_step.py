@@ -15,9 +15,10 @@ class OracleStep:
     expert_y: np.ndarray       # [N][stride][H] uint16 (after the stand-in expert)
     stride: int
     out: np.ndarray            # [N][T][H] uint16
+    out_partial: np.ndarray = None   # same, combine with sender-side partial sums (on request)
 
 
-def oracle_step(inp, align=1, zero_pad=True) -> OracleStep:
+def oracle_step(inp, align=1, zero_pad=True, partial=False) -> OracleStep:
     wl = inp.wl
     N, E, K, H = wl.n_ranks, wl.n_experts, wl.top_k, wl.hidden
     nt = inp.num_tokens
@@ -44,4 +45,7 @@ def oracle_step(inp, align=1, zero_pad=True) -> OracleStep:
         if wl.expert != "identity":
             orc.expert_scale_rank(d, N, E, lay, inp.expert_gain, H, Y[d])
     out = orc.combine(N, E, K, nt, inp.indices, lay.slot, inp.weights, Y, stride, H)
-    return OracleStep(lay, orc.comb_pos(N, E, K, nt, inp.indices), rows, scales, Y, stride, out)
+    outp = None
+    if partial:
+        outp = orc.combine_partial(N, E, K, nt, inp.indices, lay.slot, inp.weights, Y, stride, H)
+    return OracleStep(lay, orc.comb_pos(N, E, K, nt, inp.indices), rows, scales, Y, stride, out, outp)

@@ -379,6 +379,134 @@ def test_combine_order_is_k_order_not_sorted():
     assert (acc_f != acc_r).any()
 
 
+# ----------------------------------------------------------------- combine with sender-side partial sums
+def partial_reference(indices, weights, yk, El):
+    """Independent evaluation of the partial-sum combine for a flat list of tokens:
+    indices [n][K], weights [n][K] fp32, yk [n][K][H] fp32.  A rank's share is the fp32
+    fused multiply-add chain with the other ranks' weights set to zero (adding 0*y
+    leaves an fp32 accumulator unchanged), rounded to bf16; shares are added in fp32
+    with numpy's float32 arithmetic in the order of each rank's first k."""
+    n, K, H = yk.shape
+    owner = indices // El
+    total = np.zeros((n, H), np.float32)
+    exact = np.ones((n, H), bool)
+    for k in range(K):
+        first = np.ones(n, bool)
+        for k2 in range(k):
+            first &= owner[:, k2] != owner[:, k]
+        wmask = np.where(owner == owner[:, k:k + 1], weights, np.float32(0)).astype(np.float32)
+        part, ex = emulate_fma_chain(wmask, yk)
+        part_b = bf16_to_f32(f32_to_bf16_torch(part))
+        total = np.where(first[:, None], total + part_b, total).astype(np.float32)
+        exact &= ex | ~first[:, None]
+    return f32_to_bf16_torch(total), exact
+
+
+def test_partial_combine_equals_exact_combine_when_one_rank_hosts_everything():
+    """With a single rank there is one partial sum per token, the full chain, and
+    rounding it twice to bf16 changes nothing."""
+    N, E, T, K, H = 1, 16, 40, 6, 64
+    inp = small_case(N, E, T, K, H, seed=71)
+    g = (1.0 + np.arange(E, dtype=np.float32) / 256.0).astype(np.float32)
+    lay, Y, stride = run_dispatch_all(inp, N, E, K)
+    orc.expert_scale_rank(0, N, E, lay, g, H, Y[0])
+    a = orc.combine(N, E, K, inp.num_tokens, inp.indices, lay.slot, inp.weights, Y, stride, H)
+    b = orc.combine_partial(N, E, K, inp.num_tokens, inp.indices, lay.slot, inp.weights, Y, stride, H)
+    assert (a == b).all()
+
+
+def test_partial_combine_with_one_expert_per_rank_is_a_sum_of_rounded_products():
+    """E = N: every share is a single product w*y rounded to fp32 and then to bf16,
+    and the receiver adds K bf16 numbers in fp32 in k order."""
+    N, E, T, K, H = 8, 8, 32, 5, 64
+    inp = small_case(N, E, T, K, H, seed=72)
+    lay, Y, stride = run_dispatch_all(inp, N, E, K)
+    out = orc.combine_partial(N, E, K, inp.num_tokens, inp.indices, lay.slot, inp.weights, Y, stride, H)
+    yk = bf16_to_f32(Y[inp.indices, lay.slot]).astype(np.float64)          # owner == expert
+    prod = (inp.weights.astype(np.float64)[..., None] * yk).astype(np.float32)   # exact product, one rounding
+    shares = bf16_to_f32(f32_to_bf16_torch(prod))
+    total = np.zeros((N, T, H), np.float32)
+    for k in range(K):
+        total = (total + shares[:, :, k]).astype(np.float32)
+    assert (out == f32_to_bf16_torch(total)).all()
+
+
+def test_partial_combine_hand_example_differs_from_exact_combine():
+    """Worked by hand.  One token, weights 1, experts 0 and 1 on rank 0 and expert 2
+    on rank 1, y = (1, 2^-8, 2^-9); one bf16 step at 1.0 is 2^-7.
+    Exact combine: 1 + 2^-8 + 2^-9 = 1 + 0.75 steps -> 1 + 2^-7 (0x3F81).
+    Partial sums: rank 0 holds 1 + 2^-8 = 1 + half a step, a tie that rounds to the
+    even neighbour 1.0; adding rank 1's 2^-9 gives 1 + a quarter step -> 1.0 (0x3F80)."""
+    N, E, T, K, H = 2, 4, 1, 3, 8
+    idx = np.array([[[0, 1, 2]], [[0, 1, 2]]], np.int32)
+    nt = np.array([1, 0], np.int32)
+    w = np.ones((N, T, K), np.float32)
+    lay = orc.layout(N, E, K, nt, idx)
+    stride = 4
+    Y = np.zeros((N, stride, H), np.uint16)
+    vals = [1.0, 2.0 ** -8, 2.0 ** -9]
+    for k in range(K):
+        Y[idx[0, 0, k] // 2, lay.slot[0, 0, k]] = f32_to_bf16_torch(np.full(H, vals[k], np.float32))
+    exact = orc.combine(N, E, K, nt, idx, lay.slot, w, Y, stride, H)
+    part = orc.combine_partial(N, E, K, nt, idx, lay.slot, w, Y, stride, H)
+    assert (exact[0, 0] == 0x3F81).all()
+    assert (part[0, 0] == 0x3F80).all()
+    # the same three experts listed with rank 1 first: 2^-9 + 1.0 is again a quarter step
+    idx2 = np.ascontiguousarray(idx[:, :, [2, 0, 1]])
+    lay2 = orc.layout(N, E, K, nt, idx2)
+    Y2 = np.zeros_like(Y)
+    for k, v in enumerate([vals[2], vals[0], vals[1]]):
+        Y2[idx2[0, 0, k] // 2, lay2.slot[0, 0, k]] = f32_to_bf16_torch(np.full(H, v, np.float32))
+    part2 = orc.combine_partial(N, E, K, nt, idx2, lay2.slot, w, Y2, stride, H)
+    assert (part2[0, 0] == 0x3F80).all()
+
+
+def test_partial_combine_adds_shares_in_order_of_first_k():
+    """Worked by hand.  Three ranks with one expert each, the token lists experts
+    (2, 0, 1) with rows 1, 2^-24, -1 and weights 1.  In the order of first k:
+    1 + 2^-24 is a tie in fp32 and rounds to 1 (even), then 1 - 1 = +0.  Any order
+    that adds 1 and -1 first, or starts from 2^-24 (ascending rank: 2^-24 - 1 + 1),
+    ends at 2^-24 instead."""
+    N, E, T, K, H = 3, 3, 1, 3, 8
+    idx = np.zeros((N, T, K), np.int32)
+    idx[:] = [2, 0, 1]
+    nt = np.array([1, 0, 0], np.int32)
+    w = np.ones((N, T, K), np.float32)
+    lay = orc.layout(N, E, K, nt, idx)
+    Y = np.zeros((N, 2, H), np.uint16)
+    for k, v in enumerate([1.0, 2.0 ** -24, -1.0]):
+        Y[idx[0, 0, k], lay.slot[0, 0, k]] = f32_to_bf16_torch(np.full(H, v, np.float32))
+    out = orc.combine_partial(N, E, K, nt, idx, lay.slot, w, Y, 2, H)
+    assert (out[0, 0] == 0x0000).all()
+    # the exact combine adds products in the same k order and agrees here
+    assert (orc.combine(N, E, K, nt, idx, lay.slot, w, Y, 2, H)[0, 0] == 0x0000).all()
+
+
+@pytest.mark.parametrize("N,E,K", [(4, 32, 8), (2, 16, 6), (8, 16, 4)])
+def test_partial_combine_matches_grouped_evaluation(N, E, K):
+    T, H = 24, 64
+    inp = small_case(N, E, T, K, H, seed=80 + N)
+    g = (1.0 + np.arange(E, dtype=np.float32) / 256.0).astype(np.float32)
+    lay, Y, stride = run_dispatch_all(inp, N, E, K)
+    for d in range(N):
+        orc.expert_scale_rank(d, N, E, lay, g, H, Y[d])
+    out = orc.combine_partial(N, E, K, inp.num_tokens, inp.indices, lay.slot, inp.weights, Y, stride, H)
+    El = E // N
+    yk = bf16_to_f32(Y[inp.indices // El, lay.slot])
+    ref, exact = partial_reference(inp.indices.reshape(-1, K), inp.weights.reshape(-1, K),
+                                   yk.reshape(-1, K, H), El)
+    ref, exact = ref.reshape(N, T, H), exact.reshape(N, T, H)
+    assert exact.mean() > 0.9
+    assert (out[exact] == ref[exact]).all()
+    # against the exact combine: each share is rounded to bf16 once more, so the two
+    # differ by a few bf16 steps at most, and they do differ somewhere
+    full = orc.combine(N, E, K, inp.num_tokens, inp.indices, lay.slot, inp.weights, Y, stride, H)
+    dist = bf16_ulp_distance(out, full)
+    assert dist.max() <= K
+    if N > 1:
+        assert dist.max() >= 1
+
+
 def test_unnormalised_weights_scale_the_output():
     N, E, T, K, H = 2, 8, 16, 2, 64
     inp = small_case(N, E, T, K, H, seed=33)

@@ -19,7 +19,7 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBPS = 8000.0
 
 
-def algorithmic_bytes(wl, ttot, D, P, sizes, push=False):
+def algorithmic_bytes(wl, ttot, D, P, sizes, push=False, partial=False):
     """Bytes the method itself has to move (reads + writes), per kernel.  Staged
     (default): pack into send buffers, scatter, unpack.  Push: the send kernels
     write into the receive buffers, so the send-buffer write and the scatter's
@@ -34,6 +34,11 @@ def algorithmic_bytes(wl, ttot, D, P, sizes, push=False):
         "fabric_copy_kernel(combine)": 2 * P * Bc,
         "combine_reduce_kernel": P * Bc + ttot * Bc,
     }
+    if partial:      # one reply row per received row: P rows read, D written, D moved, D read
+        del k["combine_pack_kernel"]
+        k["combine_partial_pack_kernel"] = P * Bc + D * Bc
+        k["fabric_copy_kernel(combine)"] = 2 * D * Bc
+        k["combine_reduce_kernel"] = D * Bc + ttot * Bc
     if push:
         del k["fabric_copy_kernel(dispatch)"], k["fabric_copy_kernel(combine)"]
     if wl.dispatch_dtype != "bf16":
@@ -61,6 +66,9 @@ def main():
                     help="FL_FLAG_PEER_PUSH: send kernels store into the peers' receive buffers, no "
                          "send buffer and no scatter; GB/s is then computed against the smaller byte "
                          "count of that method")
+    ap.add_argument("--partial-sums", action="store_true",
+                    help="FL_FLAG_PARTIAL_SUMS: combine sends one bf16 partial sum per (token, expert "
+                         "rank); another arithmetic than the default, fewer bytes")
     ap.add_argument("--private-rows", type=int, default=0,
                     help="first rows per (source, destination) sent to private slots in a scatter "
                          "of their own (ablation of section Ablation: Private Buffer Size)")
@@ -100,9 +108,10 @@ def main():
         cf = min(cf or 1.1, 1.1)        # 16 GB buffers at 1.1x the mean; the worst case would not fit
     sh = harness.make_shuffle(inp, capacity_factor=cf,
                               unordered_fabric=args.unordered or args.overlap,
-                              max_private_rows=args.private_rows, peer_push=args.push)
+                              max_private_rows=args.private_rows, peer_push=args.push,
+                              partial_sums=args.partial_sums)
     ttot, D, P = stats["tokens_total"], stats["dedup_rows"], stats["pairs"]
-    per_kernel, bytes_dispatch, bytes_combine = algorithmic_bytes(wl, ttot, D, P, sh.sizes, args.push)
+    per_kernel, bytes_dispatch, bytes_combine = algorithmic_bytes(wl, ttot, D, P, sh.sizes, args.push, args.partial_sums)
     bytes_step = bytes_dispatch + bytes_combine
 
     expert_y = None
@@ -170,7 +179,7 @@ def main():
     for i in range(args.profile_steps):
         ev[i][0].record()
         sh.layout(dev["indices"], dev["num_tokens"]); ev[i][1].record()
-        sh.dispatch_send(dev["x"]); ev[i][2].record()
+        sh.dispatch_send(dev["x"], weights=harness.send_weights(sh, dev)); ev[i][2].record()
         sh.dispatch_recv(); ev[i][3].record()
         sh.combine_send(sh.expert_x if expert_y is None else expert_y); ev[i][4].record()
         sh.combine_reduce(dev["weights"]); ev[i][5].record()
@@ -200,8 +209,9 @@ def main():
         for i in range(reps):
             e = sev[i]
             sh.layout(dev["indices"], dev["num_tokens"])
-            sh.dispatch_send(dev["x"], rest)
-            e[0].record(); sh.dispatch_send(dev["x"], me); e[1].record()
+            sw = harness.send_weights(sh, dev)
+            sh.dispatch_send(dev["x"], rest, weights=sw)
+            e[0].record(); sh.dispatch_send(dev["x"], me, weights=sw); e[1].record()
             e[2].record(); sh.dispatch_recv(me); e[3].record()
             sh.dispatch_recv(rest)
             sh.combine_send(y, rest)
@@ -258,7 +268,7 @@ def main():
     # The same step with FL_FLAG_PEER_PUSH, beside the headline: fewer bytes by
     # construction, so its GB/s is computed against its own byte count.
     push_line = None
-    if not args.push and not big and not args.unordered and not args.headline_only:
+    if not args.push and not big and not args.unordered and not args.headline_only and not args.partial_sums:
         shp = harness.make_shuffle(inp, capacity_factor=cf, max_private_rows=args.private_rows,
                                    peer_push=True)
         _, pd, pc = algorithmic_bytes(wl, ttot, D, P, shp.sizes, True)
@@ -302,6 +312,7 @@ def main():
                    "tokens_per_rank": wl.tokens, "hidden": wl.hidden, "top_k": wl.top_k,
                    "dedup_rows": D, "pairs": P, "capacity_factor": cf, "private_rows": int(sh.sizes.private_rows),
                    "method": "peer push (no send buffer, no scatter)" if args.push else "staged (pack, scatter, unpack)",
+                   "combine": "sender-side bf16 partial sums" if args.partial_sums else "fp32 sum in k order",
                    "fabric": "unordered (release/acquire)" if args.unordered else "stream-ordered",
                    "expert_stage": "identity (expert_y aliases expert_x)" if expert_y is None
                    else "none in the timed path (resident bf16 expert_y)"},

@@ -88,6 +88,19 @@ extern "C" {
  * unchanged; only the bytes moved per step shrink (one write per sent row instead
  * of write + read + write).  Combines with the other flags and max_private_rows. */
 #define FL_FLAG_PEER_PUSH 4
+/* Combine with sender-side partial sums (section Comparison with DeepEP and the
+ * prefill results of section Performance: pre-accumulating on the sending side
+ * moves fewer bytes, at the price of bf16 precision between the two stages and of
+ * a result that is no longer one fp32 sum in a fixed order).  NOT bit-identical
+ * to the default combine; its own definition, which the oracle states the same way:
+ *   partial(d) = bf16( fp32 fused multiply-add chain from +0, ascending k, of
+ *                weights[k] * y over the token's experts hosted by rank d )
+ *   out        = bf16( fp32 sum from +0 of float(partial(d)), ranks in the order
+ *                of their first k )
+ * The weights are applied on the expert ranks, so they travel with the tokens:
+ * dispatch must be issued with fl_moe_dispatch_send_weighted, and every rank
+ * answers each row it received with one row (D rows per step instead of P). */
+#define FL_FLAG_PARTIAL_SUMS 8
 
 #define FL_MAX_RANKS 64
 #define FL_MAX_EXPERTS 1024
@@ -203,6 +216,15 @@ int fl_moe_layout(fl_moe_ctx *ctx, int rank_begin, int rank_count, const int32_t
 int fl_moe_dispatch_send(fl_moe_ctx *ctx, int rank_begin, int rank_count, const void *x,
                          void *stream);
 
+/* Step 2 for a context created with FL_FLAG_PARTIAL_SUMS (fl_moe_dispatch_send
+ * returns FL_ERR_INVALID_ARG there, and this call does without the flag): the
+ * same dispatch, and each copy's sidecar also carries weights [N][T][K] fp32 of
+ * the token's experts on the destination rank, which forms the partial sum in
+ * fl_moe_combine_send.  fl_moe_combine_reduce then only adds; it still takes the
+ * weights pointer (unused, non-NULL). */
+int fl_moe_dispatch_send_weighted(fl_moe_ctx *ctx, int rank_begin, int rank_count, const void *x,
+                                  const float *weights, void *stream);
+
 /* Step 3 (section Dispatch: wait for all transfers, then reorder tokens with
  * optional padding into a layout suitable for grouped GEMM).  expert_x
  * [N][expert_capacity_rows][H] (bf16 or e4m3 bytes): rows of rank d ordered by
@@ -257,7 +279,7 @@ int fl_moe_debug_copy(void *dst, const void *src, size_t bytes, void *stream);
  * fl_moe_profile_collect synchronises, adds the elapsed times of the launches
  * since the last collect to per-kernel totals, and fl_moe_profile_read returns
  * totals (ms) and launch counts for kernel ids 0..FL_KERNEL_COUNT-1. */
-#define FL_KERNEL_COUNT 11
+#define FL_KERNEL_COUNT 12
 int fl_moe_profile_enable(fl_moe_ctx *ctx, int on);
 int fl_moe_profile_collect(fl_moe_ctx *ctx, void *stream);
 int fl_moe_profile_read(fl_moe_ctx *ctx, double *total_ms /*host [FL_KERNEL_COUNT]*/,

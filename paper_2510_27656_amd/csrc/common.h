@@ -22,7 +22,8 @@ struct Dims {
     long long Bx, Bw, Be, Bc;                   // row bytes: input, wire, expert_x, combine
     long long bufA_rank_bytes, bufB_rank_bytes;
     long long spin_limit;
-    int KM;               // words per sidecar row: K rounded up to a multiple of 4
+    int KM;               // sidecar entries per row: K rounded up to a multiple of 4
+    int MW;               // words per sidecar row: KM, or 2*KM when the routing weights travel too
     int tune_rows;        // rows per block of the copy kernels (0 = by row size)
     int tune_reduce;      // loads in flight per thread in the reduce kernel (0 = all K)
     int tune_waves;       // waves per row in the fabric kernel (0 = by row size)
@@ -68,12 +69,15 @@ struct Tables {
     int *dst_off;         // [N src][N dst]   the same number as seen by the sender: where src's rows
                           //                  beyond its private slots start in dst's shared range
     int *comb_dst_off;    // [N d][N s]       row in s's combine receive buffer where d's reply starts
+    int *ret_off;         // [N d][N s]       partial sums: row in s's buffer where d's shares start,
+                          //                  = rows s sent to lower ranks, so a share returns to the
+                          //                  row of s's send buffer its token copy left from
     int *base_x;          // [N][El][N]       first expert-major row of (local expert, source)
     int *cs_base;         // [N][N][El]       first combine-send row of (source, local expert)
     int *cs_off;          // [N][N+1]         first combine-send row of each source
     int *plan_ok;         // [N]
-    unsigned *send_meta;  // [N][send_cap][KM]
-    unsigned *recv_meta;  // [N][recv_cap][KM]
+    unsigned *send_meta;  // [N][send_cap][MW]
+    unsigned *recv_meta;  // [N][recv_rows][MW]
     int2 *fab_dst_disp;   // [N][send_cap]    (destination rank, row there) of every send row
     int2 *fab_dst_comb;   // [N][expert_cap]  same for the combine send rows
     char *bufA;           // [N][bufA_rank_bytes]  dispatch send / combine receive

@@ -18,13 +18,13 @@ namespace {
 enum KernelId {
     KID_ROUTE_COUNT = 0, KID_ROUTE_PLAN, KID_DISPATCH_PACK, KID_DISPATCH_FABRIC,
     KID_DISPATCH_UNPACK, KID_COMBINE_PACK, KID_COMBINE_FABRIC, KID_COMBINE_REDUCE,
-    KID_DISPATCH_PACK_E4M3, KID_DISPATCH_FABRIC_PRIVATE, KID_TRANSFER_DONE
+    KID_DISPATCH_PACK_E4M3, KID_DISPATCH_FABRIC_PRIVATE, KID_TRANSFER_DONE, KID_COMBINE_PARTIAL_PACK
 };
 const char *kKernelNames[FL_KERNEL_COUNT] = {
     "route_count_kernel", "route_plan_kernel", "dispatch_pack_kernel", "fabric_copy_kernel(dispatch)",
     "dispatch_unpack_kernel", "combine_pack_kernel", "fabric_copy_kernel(combine)",
     "combine_reduce_kernel", "dispatch_pack_e4m3_kernel", "fabric_copy_kernel(dispatch, private slots)",
-    "transfer_done_kernel"};
+    "transfer_done_kernel", "combine_partial_pack_kernel"};
 
 constexpr int kEventPool = 64;
 constexpr long long kMaxFabricBlocks = 1 << 16;   // waves loop cheaply (no barriers)
@@ -60,7 +60,8 @@ int resolve(const fl_moe_config *c, Dims *D) {
         return FL_ERR_INVALID_ARG;
     if (c->dispatch_dtype == FL_DTYPE_E4M3_BLOCK128 && c->hidden % 128 != 0) return FL_ERR_ALIGNMENT;
     if (c->expert_align < 1 || c->expert_align > (1 << 16)) return FL_ERR_INVALID_ARG;
-    if (c->flags & ~(FL_FLAG_ZERO_PAD | FL_FLAG_UNORDERED_FABRIC | FL_FLAG_PEER_PUSH)) return FL_ERR_INVALID_ARG;
+    if (c->flags & ~(FL_FLAG_ZERO_PAD | FL_FLAG_UNORDERED_FABRIC | FL_FLAG_PEER_PUSH | FL_FLAG_PARTIAL_SUMS))
+        return FL_ERR_INVALID_ARG;
     if (c->recv_capacity_rows < 0 || c->expert_capacity_rows < 0 || c->spin_limit < 0)
         return FL_ERR_INVALID_ARG;
     if (c->max_private_rows < 0 || c->reserved != 0) return FL_ERR_INVALID_ARG;
@@ -69,6 +70,7 @@ int resolve(const fl_moe_config *c, Dims *D) {
     D->H = c->hidden; D->dtype = c->dispatch_dtype; D->align = c->expert_align; D->flags = c->flags;
     D->route_len = D->E + 2 * D->N + 1;
     D->KM = (D->K + 3) / 4 * 4;
+    D->MW = (c->flags & FL_FLAG_PARTIAL_SUMS) ? 2 * D->KM : D->KM;
     const long long NT = (long long)D->N * D->T;
     const long long minKEl = D->K < El ? D->K : El;
     const long long worst_recv = NT;
@@ -133,6 +135,7 @@ size_t carve(const Dims &D, void *base, Tables *W, size_t *total) {
     W->recv_shared_off = c.take<int>(N * N);
     W->dst_off = c.take<int>(N * N);
     W->comb_dst_off = c.take<int>(N * N);
+    W->ret_off = c.take<int>(N * N);
     W->base_x = c.take<int>(N * El * N);
     W->cs_base = c.take<int>(N * N * El);
     W->cs_off = c.take<int>(N * (N + 1));
@@ -140,8 +143,8 @@ size_t carve(const Dims &D, void *base, Tables *W, size_t *total) {
     W->send_row = c.take<int>(N * T * K);
     W->pair_meta = c.take<unsigned>(N * T * K);
     W->comb_pos = c.take<int>(N * T * K);
-    W->send_meta = c.take<unsigned>(N * (size_t)D.send_cap * D.KM);
-    W->recv_meta = c.take<unsigned>(N * (size_t)D.recv_rows * D.KM);
+    W->send_meta = c.take<unsigned>(N * (size_t)D.send_cap * D.MW);
+    W->recv_meta = c.take<unsigned>(N * (size_t)D.recv_rows * D.MW);
     W->fab_dst_disp = c.take<int2>(N * (size_t)D.send_cap);
     W->fab_dst_comb = c.take<int2>(N * (size_t)D.expert_cap);
     W->bufA = c.take<char>(N * (size_t)D.bufA_rank_bytes);
@@ -340,11 +343,14 @@ int fl_moe_layout(fl_moe_ctx *ctx, int rb, int rc, const int32_t *indices,
     return launch_status();
 }
 
-int fl_moe_dispatch_send(fl_moe_ctx *ctx, int rb, int rc, const void *x, void *stream) {
+static int dispatch_send_impl(fl_moe_ctx *ctx, int rb, int rc, const void *x, const float *weights,
+                              void *stream) {
     int e = check_ranks(ctx, rb, rc);
     if (e != FL_OK) return e;
     if (!x || !ctx->indices) return FL_ERR_INVALID_ARG;
-    if (!aligned16(x)) return FL_ERR_ALIGNMENT;
+    // the weights travel with the tokens exactly when the expert ranks need them
+    if (((ctx->D.flags & FL_FLAG_PARTIAL_SUMS) != 0) != (weights != nullptr)) return FL_ERR_INVALID_ARG;
+    if (!aligned16(x) || ((uintptr_t)weights & 3)) return FL_ERR_ALIGNMENT;
     hipStream_t st = (hipStream_t)stream;
     const Dims &D = ctx->D;
     const Tables &W = ctx->W;
@@ -357,13 +363,13 @@ int fl_moe_dispatch_send(fl_moe_ctx *ctx, int rb, int rc, const void *x, void *s
         const char *xp = (const char *)x;
         if (push && fenced)
             dispatch_pack_e4m3_kernel<true, true><<<grid, block, 0, st>>>(D, W, rb, xp, ctx->indices,
-                                                                          ctx->num_tokens, slices);
+                                                                          ctx->num_tokens, slices, weights);
         else if (push)
             dispatch_pack_e4m3_kernel<true, false><<<grid, block, 0, st>>>(D, W, rb, xp, ctx->indices,
-                                                                           ctx->num_tokens, slices);
+                                                                           ctx->num_tokens, slices, weights);
         else
             dispatch_pack_e4m3_kernel<false, false><<<grid, block, 0, st>>>(D, W, rb, xp, ctx->indices,
-                                                                            ctx->num_tokens, slices);
+                                                                            ctx->num_tokens, slices, weights);
     } else {
         LaunchTimer t(ctx, KID_DISPATCH_PACK, st);
         const int slices = pack_slices(D.Bx, D.tune_slices);
@@ -371,13 +377,13 @@ int fl_moe_dispatch_send(fl_moe_ctx *ctx, int rb, int rc, const void *x, void *s
         const char *xp = (const char *)x;
         if (push && fenced)
             dispatch_pack_kernel<true, true><<<grid, block, 0, st>>>(D, W, rb, xp, ctx->indices,
-                                                                     ctx->num_tokens, slices);
+                                                                     ctx->num_tokens, slices, weights);
         else if (push)
             dispatch_pack_kernel<true, false><<<grid, block, 0, st>>>(D, W, rb, xp, ctx->indices,
-                                                                      ctx->num_tokens, slices);
+                                                                      ctx->num_tokens, slices, weights);
         else
             dispatch_pack_kernel<false, false><<<grid, block, 0, st>>>(D, W, rb, xp, ctx->indices,
-                                                                       ctx->num_tokens, slices);
+                                                                       ctx->num_tokens, slices, weights);
     }
     auto announce = [&](int combine) {         // stream-ordered: one add per finished transfer
         if (fenced) return;                    // unordered: the copy kernels announce as they go
@@ -392,8 +398,8 @@ int fl_moe_dispatch_send(fl_moe_ctx *ctx, int rb, int rc, const void *x, void *s
     A.src_base = W.bufA; A.src_rank_stride = D.bufA_rank_bytes;
     A.dst_base = W.bufB; A.dst_rank_stride = D.bufB_rank_bytes;
     A.seg_off = W.send_off; A.row_dst = W.fab_dst_disp; A.row_cap = D.send_cap;
-    A.src_meta = W.send_meta; A.src_meta_rank_stride = D.send_cap * D.KM;
-    A.dst_meta = W.recv_meta; A.dst_meta_rank_stride = D.recv_rows * D.KM;
+    A.src_meta = W.send_meta; A.src_meta_rank_stride = D.send_cap * D.MW;
+    A.dst_meta = W.recv_meta; A.dst_meta_rank_stride = D.recv_rows * D.MW;
     A.dst_row_lo = 0;
     A.arrive = W.arrive_disp;
     A.row_bytes = D.Bw; A.waves_per_row = waves_per_row(D.Bw, D.tune_waves);
@@ -427,6 +433,16 @@ int fl_moe_dispatch_send(fl_moe_ctx *ctx, int rb, int rc, const void *x, void *s
     }
     announce(0);
     return launch_status();
+}
+
+int fl_moe_dispatch_send(fl_moe_ctx *ctx, int rb, int rc, const void *x, void *stream) {
+    return dispatch_send_impl(ctx, rb, rc, x, nullptr, stream);
+}
+
+int fl_moe_dispatch_send_weighted(fl_moe_ctx *ctx, int rb, int rc, const void *x, const float *weights,
+                                  void *stream) {
+    if (!weights) return FL_ERR_INVALID_ARG;
+    return dispatch_send_impl(ctx, rb, rc, x, weights, stream);
 }
 
 int fl_moe_dispatch_recv(fl_moe_ctx *ctx, int rb, int rc, void *expert_x, float *expert_scales,
@@ -477,20 +493,32 @@ int fl_moe_combine_send(fl_moe_ctx *ctx, int rb, int rc, const void *expert_y, v
     const Dims &D = ctx->D;
     const Tables &W = ctx->W;
     const int rbk = rows_per_block(D.Bc, D.tune_rows);
-    const unsigned gx = capped_grid((D.expert_cap + rbk - 1) / rbk, rc, kMaxRowBlocks);
     const bool push = D.flags & FL_FLAG_PEER_PUSH, fenced = D.flags & FL_FLAG_UNORDERED_FABRIC;
+    const bool partial = D.flags & FL_FLAG_PARTIAL_SUMS;
+    // rows a rank sends back: one per pair, or with partial sums one per received row
+    const long long worst_recv = (long long)D.N * D.T;
+    const long long reply_rows = partial ? (D.recv_rows < worst_recv ? D.recv_rows : worst_recv)
+                                         : D.expert_cap;
+    const unsigned gx = capped_grid((reply_rows + rbk - 1) / rbk, rc, kMaxRowBlocks);
     {
-        LaunchTimer t(ctx, KID_COMBINE_PACK, st);
         const dim3 grid(gx, rc), block(kCopyThreads);
         const char *yp = (const char *)expert_y;
-        if (push && fenced) combine_pack_kernel<true, true><<<grid, block, 0, st>>>(D, W, rb, yp, rbk);
-        else if (push) combine_pack_kernel<true, false><<<grid, block, 0, st>>>(D, W, rb, yp, rbk);
-        else combine_pack_kernel<false, false><<<grid, block, 0, st>>>(D, W, rb, yp, rbk);
+        if (partial) {
+            LaunchTimer t(ctx, KID_COMBINE_PARTIAL_PACK, st);
+            if (push && fenced) combine_partial_pack_kernel<true, true><<<grid, block, 0, st>>>(D, W, rb, yp, rbk);
+            else if (push) combine_partial_pack_kernel<true, false><<<grid, block, 0, st>>>(D, W, rb, yp, rbk);
+            else combine_partial_pack_kernel<false, false><<<grid, block, 0, st>>>(D, W, rb, yp, rbk);
+        } else {
+            LaunchTimer t(ctx, KID_COMBINE_PACK, st);
+            if (push && fenced) combine_pack_kernel<true, true><<<grid, block, 0, st>>>(D, W, rb, yp, rbk);
+            else if (push) combine_pack_kernel<true, false><<<grid, block, 0, st>>>(D, W, rb, yp, rbk);
+            else combine_pack_kernel<false, false><<<grid, block, 0, st>>>(D, W, rb, yp, rbk);
+        }
     }
     auto announce = [&]() {
         if (fenced) return;
         LaunchTimer t(ctx, KID_TRANSFER_DONE, st);
-        transfer_done_kernel<<<dim3(rc), dim3(kWave), 0, st>>>(D, W, rb, 1);
+        transfer_done_kernel<<<dim3(rc), dim3(kWave), 0, st>>>(D, W, rb, partial ? 2 : 1);
     };
     if (push) {                                // the rows are already in the sources' receive buffers
         announce();
@@ -499,14 +527,14 @@ int fl_moe_combine_send(fl_moe_ctx *ctx, int rb, int rc, const void *expert_y, v
     FabricArgs A;
     A.src_base = W.bufB; A.src_rank_stride = D.bufB_rank_bytes;
     A.dst_base = W.bufA; A.dst_rank_stride = D.bufA_rank_bytes;
-    A.seg_off = W.cs_off; A.row_dst = W.fab_dst_comb; A.row_cap = D.expert_cap;
+    A.seg_off = partial ? W.recv_off : W.cs_off; A.row_dst = W.fab_dst_comb; A.row_cap = D.expert_cap;
     A.src_meta = nullptr; A.src_meta_rank_stride = 0;
     A.dst_meta = nullptr; A.dst_meta_rank_stride = 0;
     A.dst_row_lo = 0;
     A.arrive = W.arrive_comb;
     A.row_bytes = D.Bc; A.waves_per_row = waves_per_row(D.Bc, D.tune_waves);
     const int wpb = kCopyThreads / kWave;
-    const unsigned gxf = capped_grid((D.expert_cap * A.waves_per_row + wpb - 1) / wpb, rc,
+    const unsigned gxf = capped_grid((reply_rows * A.waves_per_row + wpb - 1) / wpb, rc,
                                       kMaxFabricBlocks, A.waves_per_row);
     {
         LaunchTimer t(ctx, KID_COMBINE_FABRIC, st);
@@ -536,13 +564,18 @@ int fl_moe_combine_reduce(fl_moe_ctx *ctx, int rb, int rc, const float *weights,
         int nt = (int)((D.Bc / 16 + kWave - 1) / kWave * kWave);
         if (nt > kReduceMaxThreads) nt = kReduceMaxThreads;
         if (nt < 2 * kWave) nt = 2 * kWave;      // wave 0 waits, wave 1 fetches positions and weights
-        if (D.flags & FL_FLAG_UNORDERED_FABRIC)  // polling receivers: at most half of the machine
-            combine_reduce_kernel<true><<<dim3(capped_grid(D.T, rc, (long long)ctx->cu_count * 1024 / nt), rc),
-                                          dim3(nt), 0, st>>>(
-                D, ctx->W, rb, weights, (char *)out, ctx->num_tokens);
+        const bool unordered = D.flags & FL_FLAG_UNORDERED_FABRIC, partial = D.flags & FL_FLAG_PARTIAL_SUMS;
+        // polling receivers (unordered mode) take at most half of the machine
+        const dim3 grid(unordered ? capped_grid(D.T, rc, (long long)ctx->cu_count * 1024 / nt) : (unsigned)D.T, rc);
+        char *o = (char *)out;
+        if (unordered && partial)
+            combine_reduce_kernel<true, true><<<grid, dim3(nt), 0, st>>>(D, ctx->W, rb, weights, o, ctx->num_tokens);
+        else if (unordered)
+            combine_reduce_kernel<true, false><<<grid, dim3(nt), 0, st>>>(D, ctx->W, rb, weights, o, ctx->num_tokens);
+        else if (partial)
+            combine_reduce_kernel<false, true><<<grid, dim3(nt), 0, st>>>(D, ctx->W, rb, weights, o, ctx->num_tokens);
         else
-            combine_reduce_kernel<false><<<dim3(D.T, rc), dim3(nt), 0, st>>>(
-                D, ctx->W, rb, weights, (char *)out, ctx->num_tokens);
+            combine_reduce_kernel<false, false><<<grid, dim3(nt), 0, st>>>(D, ctx->W, rb, weights, o, ctx->num_tokens);
     }
     return launch_status();
 }

@@ -261,6 +261,11 @@ __global__ __launch_bounds__(kPlanThreads) void route_plan_kernel(Dims D, Tables
         inc = wave_incl_scan(len);
         if (s < N) { csoff[s] = inc - len; W.cs_off[(size_t)r * (N + 1) + s] = inc - len; }
         if (s == N - 1) W.cs_off[(size_t)r * (N + 1) + N] = inc;
+        if ((D.flags & FL_FLAG_PARTIAL_SUMS) && s < N) {   // rows s sent to ranks below r
+            int before = 0;
+            for (int d2 = 0; d2 < r; ++d2) before += Mall[s * N + d2];
+            W.ret_off[(size_t)r * N + s] = before;
+        }
     } else if (wid == 1) {
         // lane = rank d: capacity verdict for every rank, start of r's segment at d,
         // size of d's reply to rank r
@@ -276,6 +281,7 @@ __global__ __launch_bounds__(kPlanThreads) void route_plan_kernel(Dims D, Tables
             W.dst_off[(size_t)r * N + d] = before_me;
             int mine = 0;
             for (int j = 0; j < El; ++j) mine += rt[(size_t)r * RL + d * El + j];
+            if (D.flags & FL_FLAG_PARTIAL_SUMS) mine = Mall[r * N + d];   // one share per row r sent to d
             exp_units = (unsigned)mine * (unsigned)(D.Bc / 16);
             long long p = 0;
             for (int j = 0; j < El; ++j) {

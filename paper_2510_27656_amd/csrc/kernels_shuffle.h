@@ -31,7 +31,8 @@ constexpr int kMaxRowsPerBlock = 64;
 template <bool PUSH, bool FENCED>
 __global__ __launch_bounds__(kPackThreads) void dispatch_pack_kernel(
     Dims D, Tables W, int rank_begin, const char *__restrict__ x,
-    const int *__restrict__ indices, const int *__restrict__ num_tokens, int slices) {
+    const int *__restrict__ indices, const int *__restrict__ num_tokens, int slices,
+    const float *__restrict__ weights /* [N][T][K], only when the sidecar carries them */) {
     const int s = rank_begin + blockIdx.y, t = blockIdx.x / slices, slice = blockIdx.x % slices;
     const int tid = threadIdx.x;
     const int K = D.K, El = D.El;
@@ -53,11 +54,16 @@ __global__ __launch_bounds__(kPackThreads) void dispatch_pack_kernel(
     }
     __syncthreads();
     if (slice == 0 && tid < K && my_row >= 0) {   // sidecar and fabric target of this copy
-        unsigned *meta = PUSH ? W.recv_meta + ((size_t)my_d * D.recv_rows + target) * D.KM
-                              : W.send_meta + ((size_t)s * D.send_cap + my_row) * D.KM;
+        unsigned *meta = PUSH ? W.recv_meta + ((size_t)my_d * D.recv_rows + target) * D.MW
+                              : W.send_meta + ((size_t)s * D.send_cap + my_row) * D.MW;
         int m = 0;
         for (int k = 0; k < K; ++k)
-            if (s_dst[k] == my_d) st_word<PUSH && FENCED>((int *)meta + m++, (int)s_meta[k]);
+            if (s_dst[k] == my_d) {
+                st_word<PUSH && FENCED>((int *)meta + m, (int)s_meta[k]);
+                if (D.MW > D.KM)   // the weight of that expert, for the expert rank's partial sum
+                    st_word<PUSH && FENCED>((int *)meta + D.KM + m, __float_as_int(weights[pair0 + k]));
+                ++m;
+            }
         for (; m < D.KM; ++m) st_word<PUSH && FENCED>((int *)meta + m, (int)kNoEntry);
         if (!PUSH) W.fab_dst_disp[(size_t)s * D.send_cap + my_row] = make_int2(my_d, target);
     }
@@ -121,7 +127,8 @@ constexpr int kQuantThreads = 256; // 32 quantisation blocks per workgroup
 template <bool PUSH, bool FENCED>   // as in dispatch_pack_kernel
 __global__ __launch_bounds__(kQuantThreads) void dispatch_pack_e4m3_kernel(
     Dims D, Tables W, int rank_begin, const char *__restrict__ x,
-    const int *__restrict__ indices, const int *__restrict__ num_tokens, int slices) {
+    const int *__restrict__ indices, const int *__restrict__ num_tokens, int slices,
+    const float *__restrict__ weights /* [N][T][K], only when the sidecar carries them */) {
     const int s = rank_begin + blockIdx.y, t = blockIdx.x / slices, slice = blockIdx.x % slices;
     const int tid = threadIdx.x;
     const int K = D.K, El = D.El;
@@ -143,11 +150,16 @@ __global__ __launch_bounds__(kQuantThreads) void dispatch_pack_e4m3_kernel(
     }
     __syncthreads();
     if (slice == 0 && tid < K && my_row >= 0) {
-        unsigned *meta = PUSH ? W.recv_meta + ((size_t)my_d * D.recv_rows + target) * D.KM
-                              : W.send_meta + ((size_t)s * D.send_cap + my_row) * D.KM;
+        unsigned *meta = PUSH ? W.recv_meta + ((size_t)my_d * D.recv_rows + target) * D.MW
+                              : W.send_meta + ((size_t)s * D.send_cap + my_row) * D.MW;
         int m = 0;
         for (int k = 0; k < K; ++k)
-            if (s_dst[k] == my_d) st_word<PUSH && FENCED>((int *)meta + m++, (int)s_meta[k]);
+            if (s_dst[k] == my_d) {
+                st_word<PUSH && FENCED>((int *)meta + m, (int)s_meta[k]);
+                if (D.MW > D.KM)   // the weight of that expert, for the expert rank's partial sum
+                    st_word<PUSH && FENCED>((int *)meta + D.KM + m, __float_as_int(weights[pair0 + k]));
+                ++m;
+            }
         for (; m < D.KM; ++m) st_word<PUSH && FENCED>((int *)meta + m, (int)kNoEntry);
         if (!PUSH) W.fab_dst_disp[(size_t)s * D.send_cap + my_row] = make_int2(my_d, target);
     }
@@ -264,7 +276,7 @@ __device__ inline void fabric_send_row(const Dims &D, const FabricArgs &A, int s
             if (b + j * step < nvec) st_payload<FENCED, STREAMING>(dst + b + j * step, v[j]);
     }
     if (A.src_meta && sub == 0) {          // the sidecar travels with the row
-        const int mv = D.KM / 4;
+        const int mv = D.MW / 4;
         const v4u *ms =
             (const v4u *)(A.src_meta + (size_t)s * A.src_meta_rank_stride) + (size_t)src_row * mv;
         v4u *md = (v4u *)(A.dst_meta + (size_t)dst_rank * A.dst_meta_rank_stride) + (size_t)dst_row * mv;
@@ -335,13 +347,13 @@ __global__ __launch_bounds__(kCopyThreads) void fabric_private_kernel(Dims D, Ta
 __global__ __launch_bounds__(kWave) void transfer_done_kernel(Dims D, Tables W, int rank_begin,
                                                               int combine) {
     const int r = rank_begin + blockIdx.x, N = D.N;
-    const int *off = (combine ? W.cs_off : W.send_off) + (size_t)r * (N + 1);
+    const int *off = (combine == 2 ? W.recv_off : combine ? W.cs_off : W.send_off) + (size_t)r * (N + 1);
     unsigned *arrive = combine ? W.arrive_comb : W.arrive_disp;
     const unsigned units = (unsigned)((combine ? D.Bc : D.Bw) / 16);
     const int ok = W.plan_ok[r];               // all three loads are issued together
     for (int p = threadIdx.x; p < N; p += kWave) {
         // dispatch: r sent M[r][p] rows to p; combine: r replied to p with every row of
-        // r's experts that came from p
+        // r's experts that came from p, or (2, partial sums) one share per row p sent to r
         const int rows = off[p + 1] - off[p];
         if (ok && rows) add_counter(arrive + (size_t)p * N + r, (unsigned)rows * units);
     }
@@ -412,7 +424,7 @@ __global__ __launch_bounds__(kCopyThreads) void dispatch_unpack_kernel(
                 phys = recv_buffer_row(N, D.P, s, r - off[s], W.recv_shared_off[(size_t)d * N + s]);
                 src_phys[tid] = phys;
             }
-            const unsigned *meta = W.recv_meta + ((size_t)d * D.recv_rows + phys) * D.KM;
+            const unsigned *meta = W.recv_meta + ((size_t)d * D.recv_rows + phys) * D.MW;
             int n = 0;
             for (int k = 0; k < K; ++k) {
                 const unsigned m = meta[k];
@@ -533,16 +545,109 @@ __global__ __launch_bounds__(kCopyThreads) void combine_pack_kernel(
     }
 }
 
-// ------------------------------------------------------------------ combine: reduce
-// One block per token (s, t):
-//   out[s][t] = bf16( sum_k w[k] * float(row comb_pos[s][t][k]) ), fp32 fused
-// multiply-add, k ascending, one final rounding.
+// acc[0..7] += wk * (the eight bf16 values of y), fused
 __device__ inline void fma8(float *acc, float wk, v4u y) {
     acc[0] = fmaf(wk, bf16_lo(y.x), acc[0]); acc[1] = fmaf(wk, bf16_hi(y.x), acc[1]);
     acc[2] = fmaf(wk, bf16_lo(y.y), acc[2]); acc[3] = fmaf(wk, bf16_hi(y.y), acc[3]);
     acc[4] = fmaf(wk, bf16_lo(y.z), acc[4]); acc[5] = fmaf(wk, bf16_hi(y.z), acc[5]);
     acc[6] = fmaf(wk, bf16_lo(y.w), acc[6]); acc[7] = fmaf(wk, bf16_hi(y.w), acc[7]);
 }
+
+// ------------------------------------------------------------------ combine: pack with sender-side partial sums
+// Section Comparison with DeepEP: tokens can be pre-accumulated on the sending
+// side, which moves fewer rows at the price of a bf16 rounding between the two
+// stages.  Rank d answers every row it received with ONE row: the fp32 fused
+// multiply-add chain, in the order of the row's sidecar (ascending k), of
+// weight * expert output over the token's experts on d, rounded to bf16.  The
+// share of received row number i from source s goes back to row
+// ret_off[d][s] + i of s's buffer, the row of s's send buffer the token copy
+// left from, so s finds it through its own send_row table.
+template <bool PUSH, bool FENCED>
+__global__ __launch_bounds__(kCopyThreads) void combine_partial_pack_kernel(
+    Dims D, Tables W, int rank_begin, const char *__restrict__ expert_y, int rows_per_block) {
+    const int d = rank_begin + blockIdx.y, tid = threadIdx.x, N = D.N, El = D.El, K = D.K;
+    __shared__ int off[FL_MAX_RANKS + 1];
+    __shared__ int src_rows[kMaxRowsPerBlock][FL_MAX_TOPK];
+    __shared__ float src_w[kMaxRowsPerBlock][FL_MAX_TOPK];
+    __shared__ int src_cnt[kMaxRowsPerBlock];
+    __shared__ int2 share_to[kMaxRowsPerBlock];
+    if (!W.plan_ok[d]) return;
+    const int total = W.recv_off[(size_t)d * (N + 1) + N];
+    if ((int)blockIdx.x * rows_per_block >= total) return;
+    if (tid <= N) off[tid] = W.recv_off[(size_t)d * (N + 1) + tid];
+    __syncthreads();
+    const int nvec = (int)(D.Bc / 16);
+    const char *yd = expert_y + (size_t)d * D.expert_cap * D.Bc;
+    for (int r0 = blockIdx.x * rows_per_block; r0 < total; r0 += gridDim.x * rows_per_block) {
+        const int r1 = min(r0 + rows_per_block, total);
+        if (tid < r1 - r0) {
+            const int r = r0 + tid;
+            const int s = seg_of(off, N, r);
+            const int i = r - off[s];
+            const int phys = D.P ? recv_buffer_row(N, D.P, s, i, W.recv_shared_off[(size_t)d * N + s]) : r;
+            const unsigned *meta = W.recv_meta + ((size_t)d * D.recv_rows + phys) * D.MW;
+            int n = 0;
+            for (int k = 0; k < K; ++k) {
+                const unsigned m = meta[k];
+                if (m == kNoEntry) break;
+                src_rows[tid][n] = W.base_x[((size_t)d * El + (int)(m >> 24)) * N + s] + (int)(m & 0xFFFFFFu);
+                src_w[tid][n] = __uint_as_float(meta[D.KM + k]);
+                ++n;
+            }
+            src_cnt[tid] = n;
+            const int2 to = make_int2(s, W.ret_off[(size_t)d * N + s] + i);
+            share_to[tid] = to;
+            if (!PUSH) W.fab_dst_comb[(size_t)d * D.expert_cap + r] = to;
+        }
+        __syncthreads();
+        const int chunk = (r1 - r0) * nvec;
+        for (int b = tid; b < chunk; b += 4 * kCopyThreads) {
+            v4u y0[4];
+            int row[4], col[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {          // the first expert row of four items in flight
+                const int v = b + u * kCopyThreads;
+                if (v < chunk) {
+                    row[u] = v / nvec;
+                    col[u] = v - row[u] * nvec;
+                    y0[u] = ld_stream((const v4u *)(yd + (size_t)src_rows[row[u]][0] * D.Bc) + col[u]);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int v = b + u * kCopyThreads;
+                if (v >= chunk) continue;
+                float acc[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) acc[e] = 0.f;
+                fma8(acc, src_w[row[u]][0], y0[u]);
+                const int n = src_cnt[row[u]];
+                for (int k = 1; k < n; ++k)
+                    fma8(acc, src_w[row[u]][k],
+                         ld_stream((const v4u *)(yd + (size_t)src_rows[row[u]][k] * D.Bc) + col[u]));
+                v4u o;
+                o.x = pack_bf16x2(acc[0], acc[1]); o.y = pack_bf16x2(acc[2], acc[3]);
+                o.z = pack_bf16x2(acc[4], acc[5]); o.w = pack_bf16x2(acc[6], acc[7]);
+                char *dst = PUSH ? W.bufA + (size_t)share_to[row[u]].x * D.bufA_rank_bytes +
+                                       (size_t)share_to[row[u]].y * D.Bc
+                                 : W.bufB + (size_t)d * D.bufB_rank_bytes + (size_t)(r0 + row[u]) * D.Bc;
+                st_payload<PUSH && FENCED, true>((v4u *)dst + col[u], o);
+            }
+        }
+        if (PUSH && FENCED) {
+            stores_done<FENCED>();
+            __syncthreads();
+            if (tid < r1 - r0)
+                add_counter(W.arrive_comb + (size_t)share_to[tid].x * N + d, (unsigned)nvec);
+        }
+        __syncthreads();                       // the row plan is rewritten by the next chunk
+    }
+}
+
+// ------------------------------------------------------------------ combine: reduce
+// One block per token (s, t):
+//   out[s][t] = bf16( sum_k w[k] * float(row comb_pos[s][t][k]) ), fp32 fused
+// multiply-add, k ascending, one final rounding.
 
 // KT = number of row loads issued together (then consumed in k order); the sum
 // itself always runs k = 0..K-1.
@@ -571,11 +676,41 @@ __device__ inline void reduce_row(const char *__restrict__ recv, const int *pos,
     }
 }
 
+// The same sum for a row count only known on the device (partial sums: one row per
+// distinct expert rank of the token): batches of up to 8 loads, predicated.
+__device__ inline void reduce_row_counted(const char *__restrict__ recv, const int *pos,
+                                          const float *w, int n, long long Bc, int nvec,
+                                          v4u *__restrict__ out, int tid) {
+    for (int v = tid; v < nvec; v += (int)blockDim.x) {
+        float acc[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[i] = 0.f;
+        for (int k0 = 0; k0 < n; k0 += 8) {
+            v4u y[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k)
+                if (k0 + k < n) y[k] = ld_stream((const v4u *)(recv + (size_t)pos[k0 + k] * Bc) + v);
+#pragma unroll
+            for (int k = 0; k < 8; ++k)
+                if (k0 + k < n) fma8(acc, w[k0 + k], y[k]);
+        }
+        v4u o;
+        o.x = pack_bf16x2(acc[0], acc[1]); o.y = pack_bf16x2(acc[2], acc[3]);
+        o.z = pack_bf16x2(acc[4], acc[5]); o.w = pack_bf16x2(acc[6], acc[7]);
+        st_stream(out + v, o);
+    }
+}
+
 // The block has min(1024, vectors per row rounded up to a wave) threads, so a
 // 7168-wide row is one vector per thread and all K loads of a thread are in
 // flight at once.
 constexpr int kReduceMaxThreads = 1024;
-template <bool FENCED>
+//
+// PARTIAL (sender-side partial sums): the token's rows are the shares of its
+// distinct expert ranks, found at send_row[s][t][k] for every k that is the first
+// of its rank; they are added in that order in fp32 (a fused multiply-add with
+// weight 1 is an exact add), the weights having been applied on the expert ranks.
+template <bool FENCED, bool PARTIAL>
 __global__ __launch_bounds__(kReduceMaxThreads, 7) void combine_reduce_kernel(
     Dims D, Tables W, int rank_begin, const float *__restrict__ weights, char *__restrict__ out,
     const int *__restrict__ num_tokens) {
@@ -583,6 +718,7 @@ __global__ __launch_bounds__(kReduceMaxThreads, 7) void combine_reduce_kernel(
     __shared__ int pos[FL_MAX_TOPK];
     __shared__ float w[FL_MAX_TOPK];
     __shared__ int timed_out;
+    __shared__ int n_shares;
     if (!W.plan_ok[s]) return;
     const int Ts = num_tokens[s];
     if ((int)blockIdx.x >= Ts) return;
@@ -600,7 +736,19 @@ __global__ __launch_bounds__(kReduceMaxThreads, 7) void combine_reduce_kernel(
     const int kt = D.tune_reduce ? D.tune_reduce : K;
     // one token per block unless the grid was made smaller than the token count
     for (int t = blockIdx.x; t < Ts; t += gridDim.x) {
-        if (tid >= kWave && tid < kWave + K) {
+        if (PARTIAL) {
+            if (tid >= kWave && tid < 2 * kWave) {     // wave 1 compacts the token's share rows
+                const int k = tid - kWave;
+                const int p = k < K ? W.send_row[((size_t)s * D.T + t) * K + k] : -1;
+                const unsigned long long have = __ballot(p >= 0);
+                if (p >= 0) {
+                    const int at = __popcll(have & ((1ull << k) - 1));
+                    pos[at] = p;
+                    w[at] = 1.0f;
+                }
+                if (k == 0) n_shares = __popcll(have);
+            }
+        } else if (tid >= kWave && tid < kWave + K) {
             const int k = tid - kWave;
             pos[k] = W.comb_pos[((size_t)s * D.T + t) * K + k];
             w[k] = weights[((size_t)s * D.T + t) * K + k];
@@ -608,7 +756,8 @@ __global__ __launch_bounds__(kReduceMaxThreads, 7) void combine_reduce_kernel(
         __syncthreads();
         if (timed_out) return;
         v4u *o = (v4u *)(out + ((size_t)s * D.T + t) * D.Bc);
-        if (kt >= 8) reduce_row<8>(recv, pos, w, K, D.Bc, nvec, o, tid);
+        if (PARTIAL) reduce_row_counted(recv, pos, w, n_shares, D.Bc, nvec, o, tid);
+        else if (kt >= 8) reduce_row<8>(recv, pos, w, K, D.Bc, nvec, o, tid);
         else if (kt >= 4) reduce_row<4>(recv, pos, w, K, D.Bc, nvec, o, tid);
         else if (kt >= 2) reduce_row<2>(recv, pos, w, K, D.Bc, nvec, o, tid);
         else reduce_row<1>(recv, pos, w, K, D.Bc, nvec, o, tid);

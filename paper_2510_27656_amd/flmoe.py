@@ -19,7 +19,8 @@ FL_DTYPE_BF16, FL_DTYPE_E4M3_BLOCK128 = 0, 1
 FL_FLAG_ZERO_PAD = 1
 FL_FLAG_UNORDERED_FABRIC = 2
 FL_FLAG_PEER_PUSH = 4
-FL_KERNEL_COUNT = 11
+FL_FLAG_PARTIAL_SUMS = 8
+FL_KERNEL_COUNT = 12
 
 
 class fl_moe_config(C.Structure):
@@ -55,7 +56,8 @@ class fl_moe_debug_view(C.Structure):
 
 
 EXPORTS = ["fl_moe_query_sizes", "fl_moe_create", "fl_moe_destroy", "fl_moe_layout",
-           "fl_moe_dispatch_send", "fl_moe_dispatch_recv", "fl_moe_combine_send",
+           "fl_moe_dispatch_send", "fl_moe_dispatch_send_weighted", "fl_moe_dispatch_recv",
+           "fl_moe_combine_send",
            "fl_moe_combine_reduce", "fl_moe_status", "fl_moe_strerror", "fl_moe_debug_views",
            "fl_moe_debug_tune", "fl_moe_debug_copy", "fl_moe_profile_enable", "fl_moe_profile_collect", "fl_moe_profile_read",
            "fl_moe_kernel_name"]
@@ -77,6 +79,7 @@ def lib():
         L.fl_moe_destroy.argtypes = [vp]
         L.fl_moe_layout.argtypes = [vp, i32, i32, vp, vp, C.POINTER(fl_moe_layout_view), vp]
         L.fl_moe_dispatch_send.argtypes = [vp, i32, i32, vp, vp]
+        L.fl_moe_dispatch_send_weighted.argtypes = [vp, i32, i32, vp, vp, vp]
         L.fl_moe_dispatch_recv.argtypes = [vp, i32, i32, vp, vp, vp, vp]
         L.fl_moe_combine_send.argtypes = [vp, i32, i32, vp, vp]
         L.fl_moe_combine_reduce.argtypes = [vp, i32, i32, vp, vp, vp]
@@ -152,6 +155,11 @@ def fl_moe_dispatch_send(ctx, rank_begin, rank_count, x, stream=None):
            "fl_moe_dispatch_send")
 
 
+def fl_moe_dispatch_send_weighted(ctx, rank_begin, rank_count, x, weights, stream=None):
+    _check(lib().fl_moe_dispatch_send_weighted(ctx, rank_begin, rank_count, _ptr(x), _ptr(weights),
+                                               _stream(stream)), "fl_moe_dispatch_send_weighted")
+
+
 def fl_moe_dispatch_recv(ctx, rank_begin, rank_count, expert_x, expert_scales, tokens_per_expert,
                          stream=None):
     _check(lib().fl_moe_dispatch_recv(ctx, rank_begin, rank_count, _ptr(expert_x),
@@ -213,15 +221,17 @@ class MoEShuffle:
     def __init__(self, n_ranks, n_experts, max_tokens, top_k, hidden, dispatch_dtype="bf16",
                  expert_align=1, zero_pad=False, recv_capacity_rows=0, expert_capacity_rows=0,
                  spin_limit=0, unordered_fabric=False, max_private_rows=0, peer_push=False,
-                 device="cuda:0"):
+                 partial_sums=False, device="cuda:0"):
         self.device = torch.device(device)
         self.cfg = fl_moe_config(
             n_ranks, n_experts, max_tokens, top_k, hidden,
             FL_DTYPE_BF16 if dispatch_dtype == "bf16" else FL_DTYPE_E4M3_BLOCK128,
             expert_align, (FL_FLAG_ZERO_PAD if zero_pad else 0)
             | (FL_FLAG_UNORDERED_FABRIC if unordered_fabric else 0)
-            | (FL_FLAG_PEER_PUSH if peer_push else 0),
+            | (FL_FLAG_PEER_PUSH if peer_push else 0)
+            | (FL_FLAG_PARTIAL_SUMS if partial_sums else 0),
             recv_capacity_rows, expert_capacity_rows, spin_limit, max_private_rows, 0)
+        self.partial_sums = bool(partial_sums)
         self.sizes = fl_moe_query_sizes(self.cfg)
         self.N, self.E, self.T, self.K, self.H = n_ranks, n_experts, max_tokens, top_k, hidden
         self.El = n_experts // n_ranks
@@ -266,9 +276,12 @@ class MoEShuffle:
         self.view = fl_moe_layout(self.ctx, rb, rc, indices, num_tokens, stream)
         return self.view
 
-    def dispatch_send(self, x, ranks=None, stream=None):
+    def dispatch_send(self, x, ranks=None, stream=None, weights=None):
         rb, rc = self._ranks(ranks)
-        fl_moe_dispatch_send(self.ctx, rb, rc, x, stream)
+        if weights is None:
+            fl_moe_dispatch_send(self.ctx, rb, rc, x, stream)
+        else:
+            fl_moe_dispatch_send_weighted(self.ctx, rb, rc, x, weights, stream)
 
     def dispatch_recv(self, ranks=None, stream=None):
         rb, rc = self._ranks(ranks)

@@ -22,7 +22,7 @@ def to_device(inp: Inputs, device="cuda:0"):
 
 def make_shuffle(inp: Inputs, expert_align=1, zero_pad=False, capacity_factor=None,
                  spin_limit=0, unordered_fabric=False, max_private_rows=0, peer_push=False,
-                 device="cuda:0"):
+                 partial_sums=False, device="cuda:0"):
     """capacity_factor None = worst-case capacities, else factor x the mean rows per rank."""
     wl = inp.wl
     recv_cap = expert_cap = 0
@@ -35,7 +35,8 @@ def make_shuffle(inp: Inputs, expert_align=1, zero_pad=False, capacity_factor=No
                             zero_pad=zero_pad, recv_capacity_rows=recv_cap,
                             expert_capacity_rows=expert_cap, spin_limit=spin_limit,
                             unordered_fabric=unordered_fabric,
-                            max_private_rows=max_private_rows, peer_push=peer_push, device=device)
+                            max_private_rows=max_private_rows, peer_push=peer_push,
+                            partial_sums=partial_sums, device=device)
 
 
 def row_gain(sh: flmoe.MoEShuffle, gain: torch.Tensor):
@@ -73,9 +74,14 @@ def expert_stage(sh: flmoe.MoEShuffle, gain: torch.Tensor, identity=False):
     return y
 
 
+def send_weights(sh: flmoe.MoEShuffle, dev):
+    """The routing weights travel with the tokens only in partial-sum mode."""
+    return dev["weights"] if sh.partial_sums else None
+
+
 def run_step(sh: flmoe.MoEShuffle, dev, identity=False, ranks=None):
     sh.layout(dev["indices"], dev["num_tokens"], ranks)
-    sh.dispatch_send(dev["x"], ranks)
+    sh.dispatch_send(dev["x"], ranks, weights=send_weights(sh, dev))
     sh.dispatch_recv(ranks)
     y = expert_stage(sh, dev["gain"], identity)
     sh.combine_send(y, ranks)
@@ -87,7 +93,7 @@ def run_hot_path(sh: flmoe.MoEShuffle, dev, expert_y=None):
     expert_x.  e4m3 dispatch: the caller passes a resident bf16 expert_y of the layout's
     shape (the stand-in expert is not part of the timed path)."""
     sh.layout(dev["indices"], dev["num_tokens"])
-    sh.dispatch_send(dev["x"])
+    sh.dispatch_send(dev["x"], weights=send_weights(sh, dev))
     sh.dispatch_recv()
     sh.combine_send(sh.expert_x if expert_y is None else expert_y)
     return sh.combine_reduce(dev["weights"])
@@ -114,7 +120,7 @@ def run_step_two_streams(sh: flmoe.MoEShuffle, dev, identity=False, send_order=N
     with torch.cuda.stream(b):
         b.wait_event(planned)
         for rg in order:
-            sh.dispatch_send(dev["x"], rg)
+            sh.dispatch_send(dev["x"], rg, weights=send_weights(sh, dev))
     with torch.cuda.stream(a):
         sh.dispatch_recv()                       # polls per source while stream B delivers
         y = expert_y if expert_y is not None else expert_stage(sh, dev["gain"], identity)

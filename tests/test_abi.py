@@ -81,7 +81,7 @@ def test_private_rows_extend_the_receive_buffer():
     (dict(hidden=192, dispatch_dtype=1), flmoe.FL_ERR_ALIGNMENT),
     (dict(dispatch_dtype=7), flmoe.FL_ERR_INVALID_ARG),
     (dict(expert_align=0), flmoe.FL_ERR_INVALID_ARG),
-    (dict(flags=8), flmoe.FL_ERR_INVALID_ARG),
+    (dict(flags=16), flmoe.FL_ERR_INVALID_ARG),
     (dict(max_tokens=0), flmoe.FL_ERR_INVALID_ARG),
     (dict(max_private_rows=-1), flmoe.FL_ERR_INVALID_ARG),
     (dict(reserved=1), flmoe.FL_ERR_INVALID_ARG),

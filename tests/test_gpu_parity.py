@@ -44,12 +44,14 @@ def check_tables(sh, ref, N):
 
 
 def run_and_compare(inp, align=1, zero_pad=False, capacity_factor=None, ranks_split=False,
-                    unordered=False, private_rows=0, push=False):
+                    unordered=False, private_rows=0, push=False, partial=False):
     wl = inp.wl
     N, T = wl.n_ranks, wl.tokens
-    ref = oracle_step(inp, align, zero_pad=True)
+    ref = oracle_step(inp, align, zero_pad=True, partial=partial)
+    if partial:                      # the combined output follows the partial-sum definition
+        ref.out = ref.out_partial
     dev = harness.to_device(inp)
-    sh = harness.make_shuffle(inp, expert_align=align, zero_pad=zero_pad,
+    sh = harness.make_shuffle(inp, expert_align=align, zero_pad=zero_pad, partial_sums=partial,
                               capacity_factor=capacity_factor, unordered_fabric=unordered,
                               max_private_rows=private_rows, peer_push=push)
     try:
@@ -63,7 +65,7 @@ def run_and_compare(inp, align=1, zero_pad=False, capacity_factor=None, ranks_sp
             h = N // 2
             sh.layout(dev["indices"], dev["num_tokens"])
             for rg in [(h, N - h), (0, h)]:
-                sh.dispatch_send(dev["x"], rg)
+                sh.dispatch_send(dev["x"], rg, weights=harness.send_weights(sh, dev))
             for rg in [(0, h), (h, N - h)]:
                 sh.dispatch_recv(rg)
             y = harness.expert_stage(sh, dev["gain"], identity)
@@ -630,6 +632,77 @@ def test_peer_push_counters_and_untouched_send_buffer(name):
         assert (dbg["expect_comb"].cpu().numpy() == pairs * cunits).all()
     finally:
         sh.close()
+
+
+# ------------------------------------------------------------------ combine with sender-side partial sums
+@pytest.mark.parametrize("name", list(CASES))
+def test_parity_partial_sums_small(name):
+    """FL_FLAG_PARTIAL_SUMS: one bf16 share per (token, expert rank), added in fp32 on
+    the token's rank; compared with the oracle's statement of the same definition.
+    Dispatch is unchanged (and checked as in every other test)."""
+    inp = wlmod.make_inputs(CASES[name]())
+    sh, _, _ = run_and_compare(inp, partial=True, align=4, zero_pad=True)
+    sh.close()
+
+
+@pytest.mark.parametrize("kw", [dict(unordered=True), dict(private_rows=7), dict(ranks_split=True),
+                                dict(push=True), dict(push=True, unordered=True, private_rows=3),
+                                dict(capacity_factor=2.0, ranks_split=True, push=True)])
+def test_parity_partial_sums_with_the_other_modes(kw):
+    inp = wlmod.make_inputs(CASES["ragged_520"]())
+    sh, _, _ = run_and_compare(inp, partial=True, **kw)
+    sh.close()
+
+
+@pytest.mark.parametrize("name", ["fp8_small", "fp8_k16"])
+def test_parity_partial_sums_e4m3(name):
+    inp = wlmod.make_inputs(FP8_CASES[name]())
+    sh, _, _ = run_and_compare(inp, partial=True)
+    sh.close()
+
+
+@pytest.mark.parametrize("name,push", [("dsv3_decode", False), ("dsv3_decode", True), ("qwen3_skew", False)])
+def test_parity_partial_sums_named_workloads(name, push):
+    inp = wlmod.make_inputs(wlmod.WORKLOADS[name])
+    sh, _, _ = run_and_compare(inp, partial=True, push=push)
+    sh.close()
+
+
+def test_partial_sums_differ_from_the_exact_combine_and_need_the_weighted_dispatch():
+    """The mode really is another arithmetic (so the parity above has teeth), a step
+    moves one reply row per received row, and the plain dispatch call is refused."""
+    inp = wlmod.make_inputs(CASES["k16"]())
+    wl = inp.wl
+    ref = oracle_step(inp, partial=True)
+    assert (ref.out != ref.out_partial).any()
+    dev = harness.to_device(inp)
+    sh = harness.make_shuffle(inp, partial_sums=True)
+    try:
+        out = harness.run_step(sh, dev)
+        torch.cuda.synchronize()
+        assert sh.status() == 0
+        for s in range(wl.n_ranks):
+            n = inp.num_tokens[s]
+            assert (bits(out)[s, :n] == ref.out_partial[s, :n]).all()
+        dbg = sh.debug()
+        units = wl.hidden * 2 // 16
+        # one share per de-duplicated row: arrive_comb[s][d] counts M[s][d] rows
+        assert (dbg["arrive_comb"].cpu().numpy() == ref.lay.M.astype(np.int64) * units).all()
+        assert (dbg["expect_comb"].cpu().numpy() == ref.lay.M.astype(np.int64) * units).all()
+        with pytest.raises(flmoe.FlMoeError) as ei:       # refused on the host, nothing enqueued
+            sh.dispatch_send(dev["x"])
+        assert ei.value.code == flmoe.FL_ERR_INVALID_ARG
+    finally:
+        sh.close()
+    plain = harness.make_shuffle(inp)
+    try:
+        harness.run_step(plain, dev)
+        with pytest.raises(flmoe.FlMoeError) as ei:
+            plain.dispatch_send(dev["x"], weights=dev["weights"])
+        assert ei.value.code == flmoe.FL_ERR_INVALID_ARG
+        torch.cuda.synchronize()
+    finally:
+        plain.close()
 
 
 # ------------------------------------------------------------------ failure handling

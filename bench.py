@@ -265,6 +265,26 @@ def main():
     copy_gbps = 2 * (1 << 30) / (float(np.median([a.elapsed_time(b) for a, b in ce[2:]])) * 1e-3) / 1e9
     del flush_src, flush_dst
 
+    # The same step captured once in a HIP graph and replayed (the five calls only
+    # enqueue kernels); what it saves is host launch work, which shows on small shapes.
+    graph_line = None
+    if not big and not args.headline_only:
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            step()
+        for _ in range(min(args.warmup, 20)):
+            g.replay()
+        torch.cuda.synchronize()
+        g0 = time.perf_counter()
+        for _ in range(args.steps):
+            g.replay()
+        torch.cuda.synchronize()
+        gms = (time.perf_counter() - g0) * 1e3 / args.steps
+        assert sh.status() == 0
+        graph_line = {"ms_per_step": round(gms, 4), "value": round(bytes_step / (gms * 1e-3) / 1e9, 1),
+                      "unit": "GB/s"}
+        del g
+
     # The same step with FL_FLAG_PEER_PUSH, beside the headline: fewer bytes by
     # construction, so its GB/s is computed against its own byte count.
     push_line = None
@@ -329,6 +349,7 @@ def main():
         "kernel_us": {k: round(v, 2) for k, v in kern_us.items()},
         "kernel_gbps": {k: round(per_kernel[k] / (kern_us[k] * 1e-6) / 1e9, 1)
                         for k in kern_us if k in per_kernel},
+        "hip_graph_replay": graph_line,
         "peer_push_variant": push_line,
         "roofline": roofline, "cpu_baseline": cpu,
     }

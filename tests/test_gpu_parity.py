@@ -344,6 +344,29 @@ def test_parity_random_shapes():
         sh.close()
 
 
+def test_parity_random_shapes_and_mode_combinations():
+    """Forty more seeded random shapes, each with a random combination of the optional
+    modes: private slots, peer push, partial sums, unordered fabric, calls split by rank."""
+    rng = np.random.default_rng(4242)
+    for trial in range(40):
+        N = int(rng.choice([1, 2, 3, 4, 8, 16, 32]))
+        El = int(rng.choice([1, 2, 4, 8]))
+        E = N * El
+        K = int(rng.integers(1, min(E, 12) + 1))
+        T = int(rng.integers(1, 150))
+        fp8 = trial % 4 == 3
+        H = int(rng.integers(1, 7)) * 128 if fp8 else int(rng.integers(1, 200)) * 8
+        modes = dict(private_rows=int(rng.choice([0, 0, 1, 5, 40, 1000])), push=bool(rng.integers(2)),
+                     partial=bool(rng.integers(2)), unordered=bool(rng.integers(2)),
+                     ranks_split=bool(N >= 2 and rng.integers(2)))
+        wl = wlmod.custom(f"mix{trial}", N, E, T, H, K, seed=5000 + trial, ragged=bool(trial % 2),
+                          dispatch_dtype="e4m3" if fp8 else "bf16")
+        inp = wlmod.make_inputs(wl)
+        print(f"trial {trial}: N={N} El={El} K={K} T={T} H={H} fp8={fp8} {modes}", flush=True)
+        sh, _, _ = run_and_compare(inp, align=int(rng.choice([1, 4])), zero_pad=True, **modes)
+        sh.close()
+
+
 def test_no_tokens_anywhere_is_a_clean_no_op():
     inp = wlmod.make_inputs(CASES["ragged_520"]())
     inp.num_tokens[:] = 0

@@ -69,6 +69,9 @@ def main():
     ap.add_argument("--partial-sums", action="store_true",
                     help="FL_FLAG_PARTIAL_SUMS: combine sends one bf16 partial sum per (token, expert "
                          "rank); another arithmetic than the default, fewer bytes")
+    ap.add_argument("--chunk-tokens", type=int, default=0,
+                    help="chunked prefill: step a context sized for this many tokens per rank over the "
+                         "workload's batch (reports time per whole batch and the workspace size)")
     ap.add_argument("--private-rows", type=int, default=0,
                     help="first rows per (source, destination) sent to private slots in a scatter "
                          "of their own (ablation of section Ablation: Private Buffer Size)")
@@ -121,6 +124,38 @@ def main():
 
     def step():
         harness.run_hot_path(sh, dev, expert_y)
+
+    if args.chunk_tokens:
+        C = args.chunk_tokens
+        whole_bytes = int(sh.sizes.workspace_bytes)
+        sh.close()
+        pieces = [(t0, workloads.token_chunk(inp, t0, C)) for t0 in range(0, wl.tokens, C)]
+        chunks = [(t0, harness.to_device(p, "cuda:0")) for t0, p in pieces]
+        # small chunks fluctuate more around the mean load than the whole batch does
+        cfc = cf if cf is None or C >= 1024 else max(cf, 1.5)
+        shc = harness.make_shuffle(pieces[0][1], capacity_factor=cfc, peer_push=args.push,
+                                   partial_sums=args.partial_sums)
+        out_full = torch.empty((wl.n_ranks, wl.tokens, wl.hidden), dtype=torch.bfloat16, device="cuda:0")
+        for _ in range(max(1, args.warmup // 2)):
+            harness.run_chunked(shc, chunks, out_full, with_expert=False)
+        torch.cuda.synchronize()
+        assert shc.status() == 0
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            harness.run_chunked(shc, chunks, out_full, with_expert=False)
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / args.steps
+        assert shc.status() == 0
+        print(json.dumps({"metric": f"dispatch+combine achieved HBM GB/s, workload {wl.name} in chunks of "
+                                    f"{C} tokens per rank",
+                          "value": round(bytes_step / (ms * 1e-3) / 1e9, 1), "unit": "GB/s", "n_gpus": 1,
+                          "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4),
+                          "higher_is_better": True,
+                          "config": {"workload": wl.name, "chunk_tokens": C, "chunks": len(chunks),
+                                     "workspace_bytes": int(shc.sizes.workspace_bytes),
+                                     "workspace_bytes_one_shot": whole_bytes}}))
+        shc.close()
+        return
 
     if args.overlap:
         streams = (torch.cuda.Stream(), torch.cuda.Stream())

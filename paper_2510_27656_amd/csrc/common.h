@@ -29,6 +29,9 @@ struct Dims {
     int tune_waves;       // waves per row in the fabric kernel (0 = by row size)
     int tune_slices;      // blocks per token in the pack kernel (0 = by row size)
     int tune_stream_mb;   // fabric uses streaming stores when a launch may write more than this many MiB
+    int tune_grid_pct;    // row-kernel grids cover this percentage of the rows uniform routing would
+                          // bring (0 = the whole capacity); kernels loop over whatever is beyond
+    long long typ_recv_rows, typ_pair_rows;   // per rank, under uniform routing: received rows, pairs
 };
 
 // Row of a dispatch receive buffer that holds the i-th row source s sent to this

@@ -109,6 +109,13 @@ int resolve(const fl_moe_config *c, Dims *D) {
     D->tune_waves = 0;
     D->tune_slices = 0;
     D->tune_stream_mb = 1024;
+    D->tune_grid_pct = 200;
+    {   // a token reaches a given rank with probability 1 - (1 - 1/N)^K when experts are drawn uniformly
+        double miss = 1.0;
+        for (int k = 0; k < D->K; ++k) miss *= 1.0 - 1.0 / D->N;
+        D->typ_recv_rows = (long long)(NT * (1.0 - miss)) + 1;
+        D->typ_pair_rows = (long long)D->T * D->K;
+    }
     return FL_OK;
 }
 
@@ -182,6 +189,14 @@ unsigned capped_grid(long long blocks_needed, int rank_count, long long max_bloc
     long long g = blocks_needed < limit ? blocks_needed : limit;
     g = (g + multiple_of - 1) / multiple_of * multiple_of;
     return (unsigned)(g < 1 ? 1 : g);
+}
+
+// Rows a row-kernel's grid is sized for: the capacity, or (tune_grid_pct) a percentage of
+// what uniform routing would bring; the kernels loop when a rank holds more.
+long long grid_rows(const Dims &D, long long capacity, long long typical) {
+    if (D.tune_grid_pct <= 0) return capacity;
+    const long long want = typical * D.tune_grid_pct / 100 + 1;
+    return want < capacity ? want : capacity;
 }
 
 int rows_per_block(long long row_bytes, int tune_rows) {
@@ -461,7 +476,7 @@ int fl_moe_dispatch_recv(fl_moe_ctx *ctx, int rb, int rc, void *expert_x, float 
     const bool unordered = D.flags & FL_FLAG_UNORDERED_FABRIC;
     const long long worst_rows = (long long)D.N * D.T;       // received rows in use never exceed this
     const long long max_rows = D.recv_rows < worst_rows ? D.recv_rows : worst_rows;
-    unsigned gx = capped_grid((max_rows + rbk - 1) / rbk, rc,
+    unsigned gx = capped_grid((grid_rows(D, max_rows, D.typ_recv_rows) + rbk - 1) / rbk, rc,
                               unordered ? (long long)ctx->cu_count * 4 : kMaxRowBlocks);
     if (gx < (unsigned)D.El) gx = D.El;      // the first El-1 blocks also clear padding rows
     {
@@ -499,7 +514,8 @@ int fl_moe_combine_send(fl_moe_ctx *ctx, int rb, int rc, const void *expert_y, v
     const long long worst_recv = (long long)D.N * D.T;
     const long long reply_rows = partial ? (D.recv_rows < worst_recv ? D.recv_rows : worst_recv)
                                          : D.expert_cap;
-    const unsigned gx = capped_grid((reply_rows + rbk - 1) / rbk, rc, kMaxRowBlocks);
+    const long long reply_grid = grid_rows(D, reply_rows, partial ? D.typ_recv_rows : D.typ_pair_rows);
+    const unsigned gx = capped_grid((reply_grid + rbk - 1) / rbk, rc, kMaxRowBlocks);
     {
         const dim3 grid(gx, rc), block(kCopyThreads);
         const char *yp = (const char *)expert_y;
@@ -534,7 +550,7 @@ int fl_moe_combine_send(fl_moe_ctx *ctx, int rb, int rc, const void *expert_y, v
     A.arrive = W.arrive_comb;
     A.row_bytes = D.Bc; A.waves_per_row = waves_per_row(D.Bc, D.tune_waves);
     const int wpb = kCopyThreads / kWave;
-    const unsigned gxf = capped_grid((reply_rows * A.waves_per_row + wpb - 1) / wpb, rc,
+    const unsigned gxf = capped_grid((reply_grid * A.waves_per_row + wpb - 1) / wpb, rc,
                                       kMaxFabricBlocks, A.waves_per_row);
     {
         LaunchTimer t(ctx, KID_COMBINE_FABRIC, st);
@@ -622,6 +638,7 @@ int fl_moe_debug_tune(fl_moe_ctx *ctx, int knob, int value) {
         case 0: if (value > kMaxRowsPerBlock) return FL_ERR_INVALID_ARG; ctx->D.tune_rows = value; break;
         case 2: ctx->D.tune_waves = value; break;
         case 4: ctx->D.tune_stream_mb = value; break;
+        case 5: if (value > 1000) return FL_ERR_INVALID_ARG; ctx->D.tune_grid_pct = value; break;
         case 3: if (value > 16) return FL_ERR_INVALID_ARG; ctx->D.tune_slices = value; break;
         case 1: if (value > 8) return FL_ERR_INVALID_ARG; ctx->D.tune_reduce = value; break;
         default: return FL_ERR_INVALID_ARG;

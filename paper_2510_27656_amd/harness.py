@@ -135,3 +135,21 @@ def run_step_two_streams(sh: flmoe.MoEShuffle, dev, identity=False, send_order=N
     cur.wait_stream(a)
     cur.wait_stream(b)
     return out
+
+
+def run_chunked(sh: flmoe.MoEShuffle, chunks, out_full: torch.Tensor, identity=False, with_expert=True):
+    """Chunked prefill: one context sized for `sh.T` tokens per rank is stepped over a
+    list of (first token, uploaded chunk) pairs, so that the staging buffers hold one
+    chunk instead of the whole batch (section Performance, prefill: transfers are not
+    chunked there, and buffer memory limits which models can be deployed).  Every
+    token's combined row lands in out_full [N][T_total][H]."""
+    for t0, dev in chunks:
+        n = min(sh.T, out_full.shape[1] - t0)
+        sh.layout(dev["indices"], dev["num_tokens"])
+        sh.dispatch_send(dev["x"], weights=send_weights(sh, dev))
+        sh.dispatch_recv()
+        y = expert_stage(sh, dev["gain"], identity) if with_expert else sh.expert_x
+        sh.combine_send(y)
+        out = sh.combine_reduce(dev["weights"])
+        out_full[:, t0:t0 + n].copy_(out[:, :n])
+    return out_full

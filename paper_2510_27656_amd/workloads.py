@@ -143,3 +143,21 @@ def describe(inp: Inputs) -> dict:
 
 def custom(name, n_ranks, n_experts, tokens, hidden, top_k, seed, **kw) -> Workload:
     return Workload(name, n_ranks, n_experts, tokens, hidden, top_k, seed=seed, **kw)
+
+
+def token_chunk(inp: Inputs, t0: int, chunk: int) -> Inputs:
+    """Tokens [t0, t0 + chunk) of every rank as a workload of its own (same routing,
+    same hidden states): what one pass of a chunked prefill hands to the shuffle.
+    A last, shorter chunk is padded with absent tokens to the same shape."""
+    from dataclasses import replace
+    wl = replace(inp.wl, name=f"{inp.wl.name}[{t0}:{t0 + chunk}]", tokens=chunk)
+    n = min(chunk, inp.wl.tokens - t0)
+    nt = np.clip(inp.num_tokens - t0, 0, n).astype(np.int32)
+
+    def cut(a):
+        out = np.zeros((a.shape[0], chunk) + a.shape[2:], a.dtype)
+        out[:, :n] = a[:, t0:t0 + n]
+        return out
+    idx = cut(inp.indices)
+    idx[:, n:] = np.arange(inp.wl.top_k, dtype=np.int32)     # absent tokens still need valid-looking ids
+    return Inputs(wl, cut(inp.x), idx, cut(inp.weights), nt, inp.expert_gain, inp.popularity_rank)

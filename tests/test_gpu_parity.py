@@ -367,6 +367,22 @@ def test_parity_random_shapes_and_mode_combinations():
         sh.close()
 
 
+@pytest.mark.parametrize("kw", [dict(), dict(push=True), dict(partial=True, private_rows=50),
+                                dict(unordered=True)])
+def test_every_token_to_one_rank_is_served_by_the_row_loops(kw):
+    """Grids are sized for twice the rows uniform routing would bring; here one rank
+    hosts every chosen expert and receives N*T rows and N*T*K pairs, several times
+    that, so its kernels loop over their grids."""
+    inp = wlmod.make_inputs(wlmod.custom("hot_rank", 8, 64, 300, 256, 4, seed=77, ragged=True))
+    rng = np.random.default_rng(77)
+    hot = 3
+    for s in range(8):
+        for t in range(300):
+            inp.indices[s, t] = hot * 8 + rng.permutation(8)[:4]
+    sh, _, _ = run_and_compare(inp, zero_pad=True, **kw)
+    sh.close()
+
+
 def test_no_tokens_anywhere_is_a_clean_no_op():
     inp = wlmod.make_inputs(CASES["ragged_520"]())
     inp.num_tokens[:] = 0
@@ -726,6 +742,48 @@ def test_partial_sums_differ_from_the_exact_combine_and_need_the_weighted_dispat
         torch.cuda.synchronize()
     finally:
         plain.close()
+
+
+# ------------------------------------------------------------------ chunked prefill
+@pytest.mark.parametrize("chunk", [32, 100, 7])
+def test_chunked_steps_give_the_same_combined_output(chunk):
+    """A context sized for `chunk` tokens per rank stepped over the batch: every chunk
+    matches the oracle run on that chunk (tables, dispatched rows, combined rows), and
+    the combined rows of all tokens equal those of the one-shot step, since a token's
+    sum does not depend on its neighbours.  The staging buffers shrink with the chunk."""
+    inp = wlmod.make_inputs(wlmod.custom("chunked", 4, 32, 100, 520, 4, seed=91, ragged=True))
+    wl = inp.wl
+    N, T = wl.n_ranks, wl.tokens
+    whole = oracle_step(inp)
+    pieces = [(t0, wlmod.token_chunk(inp, t0, chunk)) for t0 in range(0, T, chunk)]
+    one_shot = harness.make_shuffle(inp)
+    full_bytes = one_shot.sizes.workspace_bytes
+    one_shot.close()
+    sh = harness.make_shuffle(pieces[0][1])
+    try:
+        assert chunk >= T or sh.sizes.workspace_bytes < full_bytes
+        out_full = torch.zeros((N, T, wl.hidden), dtype=torch.bfloat16, device="cuda")
+        out_full.view(torch.int16).fill_(POISON)
+        for t0, piece in pieces:
+            harness.run_chunked(sh, [(t0, harness.to_device(piece))], out_full)
+            torch.cuda.synchronize()
+            assert sh.status() == 0
+            ref = oracle_step(piece)
+            check_tables(sh, ref, N)
+            ex = bits(sh.expert_x[:, :ref.stride])
+            for d in range(N):
+                n = ref.expert_rows[d].shape[0]
+                assert (ex[d, :n] == ref.expert_rows[d]).all(), (t0, d)
+            ob = bits(sh.out)
+            for s in range(N):
+                k = int(piece.num_tokens[s])
+                assert (ob[s, :k] == ref.out[s, :k]).all()
+        ofb = bits(out_full)
+        for s in range(N):
+            k = int(inp.num_tokens[s])
+            assert (ofb[s, :k] == whole.out[s, :k]).all(), "chunking changed a token's result"
+    finally:
+        sh.close()
 
 
 # ------------------------------------------------------------------ failure handling

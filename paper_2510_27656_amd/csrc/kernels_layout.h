@@ -19,7 +19,7 @@ __host__ __device__ inline int route_row_stride(int TT) { return (TT / 32) | 1; 
 
 __host__ __device__ inline size_t route_count_lds_bytes(int E, int N, int TT) {
     size_t rows = (size_t)E + N;
-    return rows * route_row_stride(TT) * 2 * sizeof(unsigned) + rows * 3 * sizeof(int) +
+    return rows * route_row_stride(TT) * 2 * sizeof(unsigned) + rows * 4 * sizeof(int) +
            32 * sizeof(int);
 }
 
@@ -58,7 +58,8 @@ __global__ __launch_bounds__(kRouteThreads) void route_count_kernel(
     int *count = (int *)(pre + (size_t)rows * Wd);         // [rows] hits over all tiles (C | M)
     int *start = count + rows;                             // [rows] exclusive scan of count
     int *base = start + rows;                              // [rows] hits in the tiles before the current one
-    int *scan_tmp = base + rows;                           // [32]
+    int *total_hits = base + rows;                         // [rows] copy of the totals (pass 2 reuses count)
+    int *scan_tmp = total_hits + rows;                     // [32]
     __shared__ int bad;
 
     int Ts = num_tokens[s];
@@ -106,8 +107,8 @@ __global__ __launch_bounds__(kRouteThreads) void route_count_kernel(
         const int b = 2 * tid + 1 < rows ? count[2 * tid + 1] : 0;
         int total;
         const int ex = block_excl_scan(a + b, scan_tmp, &total);
-        if (2 * tid < rows) start[2 * tid] = ex;
-        if (2 * tid + 1 < rows) start[2 * tid + 1] = ex + a;
+        if (2 * tid < rows) { start[2 * tid] = ex; total_hits[2 * tid] = a; }
+        if (2 * tid + 1 < rows) { start[2 * tid + 1] = ex + a; total_hits[2 * tid + 1] = b; }
     }
     __syncthreads();
     // start[e] = first combine-receive row of expert e; start[E + d] = pairs + send_off[d]
@@ -160,16 +161,14 @@ __global__ __launch_bounds__(kRouteThreads) void route_count_kernel(
     const int valid = bad ? 0 : 1;
     if (bad && tid == 0) latch_status(W.status, FL_STATUS_BAD_INDEX);
 
-    // Route exchange: push this rank's record into every peer's table, then notify.
-    // The record is read back from the rank's own tables, which this block wrote above
-    // (count[] may have been reused by pass 2).
+    // Route exchange: push this rank's record (C | M | comb_off | valid, all still in
+    // LDS) into every peer's table, then notify.
     const int RL = D.route_len;
     for (int i = tid; i < N * RL; i += kRouteThreads) {
         const int peer = i / RL, f = i - peer * RL;
         int v;
-        if (f < E) v = W.C[(size_t)s * E + f];
-        else if (f < E + N) v = W.M[(size_t)s * N + (f - E)];
-        else if (f < E + 2 * N) v = W.comb_off[(size_t)s * (N + 1) + (f - E - N)];
+        if (f < E + N) v = total_hits[f];
+        else if (f < E + 2 * N) v = start[(f - E - N) * El];
         else v = valid;
         st_word<FENCED>(&W.routes[((size_t)peer * N + s) * RL + f], v);
     }

@@ -13,7 +13,7 @@ constexpr int kWave = 64;
 struct Dims {
     int N, E, El, T, K, H;
     int dtype, align, flags;
-    int TT;               // tokens per LDS tile of route_count_kernel (multiple of 32)
+    int TT;               // tokens per LDS tile of the counting blocks (multiple of 32)
     int route_len;        // ints one rank pushes to every peer: C[E] | M[N] | comb_off[N] | valid
     int scales_per_row;   // 0 or H/128
     long long recv_cap, expert_cap, send_cap;   // rows per rank

@@ -16,12 +16,12 @@ using namespace flmoe;
 namespace {
 
 enum KernelId {
-    KID_ROUTE_COUNT = 0, KID_ROUTE_PLAN, KID_DISPATCH_PACK, KID_DISPATCH_FABRIC,
+    KID_ROUTE_LAYOUT = 0, KID_DISPATCH_PACK, KID_DISPATCH_FABRIC,
     KID_DISPATCH_UNPACK, KID_COMBINE_PACK, KID_COMBINE_FABRIC, KID_COMBINE_REDUCE,
     KID_DISPATCH_PACK_E4M3, KID_DISPATCH_FABRIC_PRIVATE, KID_TRANSFER_DONE, KID_COMBINE_PARTIAL_PACK
 };
 const char *kKernelNames[FL_KERNEL_COUNT] = {
-    "route_count_kernel", "route_plan_kernel", "dispatch_pack_kernel", "fabric_copy_kernel(dispatch)",
+    "route_layout_kernel", "dispatch_pack_kernel", "fabric_copy_kernel(dispatch)",
     "dispatch_unpack_kernel", "combine_pack_kernel", "fabric_copy_kernel(combine)",
     "combine_reduce_kernel", "dispatch_pack_e4m3_kernel", "fabric_copy_kernel(dispatch, private slots)",
     "transfer_done_kernel", "combine_partial_pack_kernel"};
@@ -334,20 +334,12 @@ int fl_moe_layout(fl_moe_ctx *ctx, int rb, int rc, const int32_t *indices,
     const Dims &D = ctx->D;
     ctx->indices = indices;
     ctx->num_tokens = num_tokens;
-    const bool fenced = D.flags & FL_FLAG_UNORDERED_FABRIC;
     {
-        LaunchTimer t(ctx, KID_ROUTE_COUNT, st);
-        const size_t lds = route_count_lds_bytes(D.E, D.N, D.TT);
-        if (fenced) route_count_kernel<true><<<dim3(rc), dim3(kRouteThreads), lds, st>>>(
-            D, ctx->W, rb, indices, num_tokens);
-        else route_count_kernel<false><<<dim3(rc), dim3(kRouteThreads), lds, st>>>(
-            D, ctx->W, rb, indices, num_tokens);
-    }
-    {
-        LaunchTimer t(ctx, KID_ROUTE_PLAN, st);
-        const size_t lds = route_plan_lds_bytes(D.E, D.N, D.El);
-        if (fenced) route_plan_kernel<true><<<dim3(rc), dim3(kPlanThreads), lds, st>>>(D, ctx->W, rb);
-        else route_plan_kernel<false><<<dim3(rc), dim3(kPlanThreads), lds, st>>>(D, ctx->W, rb);
+        LaunchTimer t(ctx, KID_ROUTE_LAYOUT, st);
+        const size_t lds_count = route_count_lds_bytes(D.E, D.N, D.TT);
+        const size_t lds_plan = route_plan_lds_bytes(D.E, D.N, D.El);
+        route_layout_kernel<<<dim3(2 * rc), dim3(kRouteThreads), lds_count > lds_plan ? lds_count : lds_plan, st>>>(
+            D, ctx->W, rb, rc, indices, num_tokens);
     }
     if (view) {
         const Tables &W = ctx->W;

@@ -42,12 +42,9 @@ __host__ __device__ inline size_t route_count_lds_bytes(int E, int N, int TT) {
 // Outputs for rank s: C[s][.], M[s][.], send_off[s][.], comb_off[s][.], per pair
 // send_row / pair_meta / comb_pos; the route record (C | M | comb_off | valid) is
 // pushed into every peer's routes[peer][s] and arrive_route[peer][s] is bumped.
-template <bool FENCED>
-__global__ __launch_bounds__(kRouteThreads) void route_count_kernel(
-    Dims D, Tables W, int rank_begin, const int *__restrict__ indices,
-    const int *__restrict__ num_tokens) {
-    extern __shared__ unsigned lds[];
-    const int s = rank_begin + blockIdx.x;
+__device__ __forceinline__ void route_count_block(const Dims &D, const Tables &W, int s,
+                                                  const int *__restrict__ indices,
+                                                  const int *__restrict__ num_tokens, unsigned *lds) {
     const int tid = threadIdx.x;
     const int E = D.E, N = D.N, El = D.El, K = D.K;
     const int rows = E + N;
@@ -170,12 +167,11 @@ __global__ __launch_bounds__(kRouteThreads) void route_count_kernel(
         if (f < E + N) v = total_hits[f];
         else if (f < E + 2 * N) v = start[(f - E - N) * El];
         else v = valid;
-        st_word<FENCED>(&W.routes[((size_t)peer * N + s) * RL + f], v);
+        st_word<true>(&W.routes[((size_t)peer * N + s) * RL + f], v);
     }
-    stores_done<FENCED>();
+    stores_done<true>();
     __syncthreads();
     if (tid < N) add_counter(W.arrive_route + (size_t)tid * N + s, 1u);
-    if (tid == 0) W.epoch_route[s] += 1u;
 }
 
 __host__ __device__ inline size_t route_plan_lds_bytes(int E, int N, int El) {
@@ -188,11 +184,7 @@ __host__ __device__ inline size_t route_plan_lds_bytes(int E, int N, int El) {
 // table rank r needs for the step.  All ranks see the same records, so all reach
 // the same verdict on validity and capacity: a bad step is skipped by everyone
 // without further communication.
-template <bool FENCED>
-__global__ __launch_bounds__(kPlanThreads) void route_plan_kernel(Dims D, Tables W,
-                                                                  int rank_begin) {
-    extern __shared__ unsigned lds[];
-    const int r = rank_begin + blockIdx.x;
+__device__ __forceinline__ void route_plan_block(const Dims &D, const Tables &W, int r, unsigned *lds) {
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wid = tid / kWave;
     const int E = D.E, N = D.N, El = D.El, RL = D.route_len;
     int *G_all = (int *)lds;              // [E]      tokens per expert over all sources
@@ -207,11 +199,14 @@ __global__ __launch_bounds__(kPlanThreads) void route_plan_kernel(Dims D, Tables
     for (int e = tid; e < E; e += kPlanThreads) G_all[e] = 0;
     __syncthreads();
     if (wid == 0) {
-        const unsigned expect = W.epoch_route[r];
+        // Rank r has planned epoch_route[r] steps so far (only this block touches the
+        // word); this step is complete when every source's message count has caught up.
+        const unsigned expect = W.epoch_route[r] + 1u;
+        if (lane == 0) W.epoch_route[r] = expect;
         if (!wave_wait_counters(W.arrive_route + (size_t)r * N, nullptr, expect, N, D.spin_limit)) {
             if (lane == 0) { flag = 1; latch_status(W.status, FL_STATUS_TIMEOUT); }
         }
-        acquire_payload<FENCED>();
+        acquire_payload<true>();
     }
     __syncthreads();
     if (flag) {
@@ -313,6 +308,25 @@ __global__ __launch_bounds__(kPlanThreads) void route_plan_kernel(Dims D, Tables
     if (wid == 0 && lane < N) W.expect_disp[(size_t)r * N + lane] += exp_units;
     if (wid == 1 && lane < N) W.expect_comb[(size_t)r * N + lane] += exp_units;
     if (tid == 0) W.plan_ok[r] = 1;
+}
+
+// One launch for both halves of the layout step: blocks [0, rank_count) count for
+// their source rank and push its route record, blocks [rank_count, 2 * rank_count)
+// plan for their rank as soon as the records of all sources have arrived.  The
+// planning blocks poll the message counters (bounded) while the counting blocks
+// run: workgroups are dispatched in index order and all of them fit on the
+// machine at once (two 1024-thread blocks per compute unit, at most 128 blocks),
+// so a poller never keeps a counter from starting.  Records cross compute dies
+// inside one kernel, hence device-scope stores and one cache invalidation per
+// planning block in every mode.
+__global__ __launch_bounds__(kRouteThreads) void route_layout_kernel(
+    Dims D, Tables W, int rank_begin, int rank_count, const int *__restrict__ indices,
+    const int *__restrict__ num_tokens) {
+    extern __shared__ unsigned lds[];
+    if ((int)blockIdx.x < rank_count)
+        route_count_block(D, W, rank_begin + blockIdx.x, indices, num_tokens, lds);
+    else
+        route_plan_block(D, W, rank_begin + blockIdx.x - rank_count, lds);
 }
 
 }  // namespace flmoe

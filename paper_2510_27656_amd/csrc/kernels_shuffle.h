@@ -25,9 +25,11 @@ constexpr int kMaxRowsPerBlock = 64;
 //
 // PUSH (every peer's receive buffer can be stored to, section Dispatch: within a
 // node payloads are pushed from the send kernel): the copies and their sidecars
-// go straight into the destinations' receive buffers, and the block adds the
-// 16-byte units it wrote to arrive[destination][source] itself; no send buffer is
-// filled and no scatter follows.  FENCED applies to PUSH only (unordered fabric).
+// go straight into the destinations' receive buffers; no send buffer is filled
+// and no scatter follows.  FENCED (unordered fabric, PUSH only): device-scope
+// stores, and the block adds the 16-byte units it wrote to
+// arrive[destination][source] itself once they are acknowledged; stream-ordered,
+// transfer_done_kernel announces the transfers after this kernel.
 template <bool PUSH, bool FENCED>
 __global__ __launch_bounds__(kPackThreads) void dispatch_pack_kernel(
     Dims D, Tables W, int rank_begin, const char *__restrict__ x,
@@ -255,8 +257,8 @@ struct FabricArgs {
 };
 
 // One wave's share of one row: slice `sub` of `G` (vectors v with (v / 64) % G ==
-// sub), the sidecar when it is slice 0, then the count of 16-byte units it
-// delivered, added to arrive[destination][source].
+// sub), the sidecar when it is slice 0, and in unordered mode the count of
+// 16-byte units it delivered, added to arrive[destination][source].
 template <bool FENCED, bool STREAMING>
 __device__ inline void fabric_send_row(const Dims &D, const FabricArgs &A, int s, int src_row,
                                        int dst_rank, int dst_row, int sub, int lane) {
@@ -490,8 +492,9 @@ __global__ __launch_bounds__(kCopyThreads) void dispatch_unpack_kernel(
 // combine-send row q of source s and local expert j comes from expert-major row
 // base_x[d][j][s] + (q - cs_base[d][s][j]).
 //
-// PUSH: the rows go straight into the sources' combine receive buffers and the
-// block adds each row's units to arrive[source][this rank]; FENCED as above.
+// PUSH: the rows go straight into the sources' combine receive buffers; FENCED as
+// in the dispatch pack kernel (the block adds each row's units to
+// arrive[source][this rank] itself).
 template <bool PUSH, bool FENCED>
 __global__ __launch_bounds__(kCopyThreads) void combine_pack_kernel(
     Dims D, Tables W, int rank_begin, const char *__restrict__ expert_y, int rows_per_block) {

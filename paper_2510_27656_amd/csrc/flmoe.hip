@@ -175,6 +175,7 @@ int waves_per_row(long long row_bytes, int tune_waves) {
 int pack_slices(long long row_bytes, int tune_slices) {
     if (tune_slices > 0) return tune_slices;
     const long long nvec = row_bytes / 16;
+    if (nvec <= 2 * kPackThreads) return 1;                   // short rows (<= 4 KB): one block, measured faster
     long long s = (nvec + kPackThreads - 1) / kPackThreads;   // one vector per thread
     return (int)(s < 1 ? 1 : s > 16 ? 16 : s);
 }

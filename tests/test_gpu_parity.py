@@ -193,6 +193,43 @@ def test_repeated_steps_are_deterministic_and_counters_monotone():
         sh.close()
 
 
+@pytest.mark.parametrize("kw", [dict(), dict(unordered_fabric=True), dict(peer_push=True, partial_sums=True)])
+def test_counters_wrap_around_32_bits(kw):
+    """The arrival and expectation counters are monotone 32-bit words compared
+    wrap-safely: set just below 2^32 (consistently, as after very many steps), the
+    next steps carry them across zero without a time-out or a wrong row."""
+    inp = wlmod.make_inputs(CASES["ragged_520"]())
+    dev = harness.to_device(inp)
+    partial = kw.get("partial_sums", False)
+    ref = oracle_step(inp, partial=partial)
+    want = ref.out_partial if partial else ref.out
+    sh = harness.make_shuffle(inp, **kw)
+    try:
+        dbg = sh.debug()
+        near = 0xFFFFFFFF - 1000                   # a step adds tens of thousands of units
+        for name in ("arrive_disp", "expect_disp", "arrive_comb", "expect_comb"):
+            dbg[name].view(torch.int32).fill_(near - (1 << 32))
+        for name in ("arrive_route", "epoch_route"):
+            dbg[name].view(torch.int32).fill_(-2)  # 0xFFFFFFFE: wraps on the second step
+        for step in range(4):
+            sh.out.view(torch.int16).fill_(POISON)
+            out = harness.run_step(sh, dev)
+            torch.cuda.synchronize()
+            assert sh.status() == 0, step
+            ob = bits(out)
+            for s in range(inp.wl.n_ranks):
+                n = inp.num_tokens[s]
+                assert (ob[s, :n] == want[s, :n]).all(), (step, s)
+        after = sh.debug()
+        assert (after["arrive_disp"] == after["expect_disp"]).all()
+        assert (after["arrive_comb"] == after["expect_comb"]).all()
+        assert int(after["epoch_route"].view(torch.int32)[0]) == 2         # -2 + 4 steps
+        unsigned = after["arrive_disp"].long().cpu().numpy() & 0xFFFFFFFF
+        assert (unsigned[ref.lay.M.T > 0] < near).all()                    # they did pass zero
+    finally:
+        sh.close()
+
+
 def test_round_trip_identity_returns_input():
     wl = wlmod.custom("rt", 8, 64, 48, 512, 8, seed=21, expert="identity")
     inp = wlmod.make_inputs(wl)

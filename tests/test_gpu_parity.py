@@ -869,16 +869,24 @@ def test_bad_expert_id_skips_the_step_everywhere():
         sh.close()
 
 
-def test_capacity_overflow_is_reported_not_written():
+@pytest.mark.parametrize("kw", [dict(), dict(peer_push=True), dict(partial_sums=True, max_private_rows=2),
+                                dict(unordered_fabric=True, peer_push=True)])
+def test_capacity_overflow_is_reported_not_written(kw):
     inp = wlmod.make_inputs(CASES["ragged_520"]())
     dev = harness.to_device(inp)
-    sh = harness.make_shuffle(inp, capacity_factor=0.25)
+    sh = harness.make_shuffle(inp, capacity_factor=0.25, **kw)
     try:
         sh.expert_x.view(torch.int16).fill_(POISON)
+        sh.out.view(torch.int16).fill_(POISON)
+        buf_b = sh.debug()["buf_b"]
+        buf_b.fill_(0x3C)
         harness.run_hot_path(sh, dev)
         torch.cuda.synchronize()
         assert sh.status() == flmoe.FL_STATUS_CAPACITY
-        assert (bits(sh.expert_x) == POISON).all()
+        assert (bits(sh.expert_x) == POISON).all() and (bits(sh.out) == POISON).all()
+        assert bool((buf_b == 0x3C).all()), "a skipped step wrote into a receive buffer"
+        dbg = sh.debug()
+        assert (dbg["arrive_disp"] == dbg["expect_disp"]).all() and (dbg["arrive_comb"] == dbg["expect_comb"]).all()
     finally:
         sh.close()
 

@@ -831,8 +831,9 @@ def small_shuffle(spin_limit=0, **kw):
     return inp, dev, sh
 
 
-def test_bad_expert_id_skips_the_step_everywhere():
-    inp, dev, sh = small_shuffle()
+@pytest.mark.parametrize("kw", [dict(), dict(peer_push=True), dict(unordered_fabric=True, max_private_rows=4)])
+def test_bad_expert_id_skips_the_step_everywhere(kw):
+    inp, dev, sh = small_shuffle(**kw)
     try:
         bad = dev["indices"].clone()
         bad[1, 3, 2] = inp.wl.n_experts + 5

@@ -138,6 +138,10 @@ __device__ inline void latch_status(int *status, int bit) {
 // its expectation (wrap-safe comparison; `expect` is either one value for all or,
 // with expect_arr, one per counter).  Returns true when all n counters arrived,
 // false when the poll budget ran out.  Every lane of the wave must call it.
+// SLEEP: pause between polls in units of 64 clocks.  Payload waits may last as long
+// as a copy kernel and must not crowd out the senders they wait for (about 2 us);
+// the route exchange inside the layout kernel is a few microseconds long (short pause).
+template <int SLEEP = 64>
 __device__ inline bool wave_wait_counters(const unsigned *ctr, const unsigned *expect_arr,
                                           unsigned expect, int n, long long spin_limit) {
     const int lane = threadIdx.x & (kWave - 1);
@@ -150,7 +154,7 @@ __device__ inline bool wave_wait_counters(const unsigned *ctr, const unsigned *e
             if (i < n) ok = (int)(ld_relaxed(ctr + i) - expect) >= 0;
             if (__all(ok)) break;
             if (++spins > spin_limit) return false;
-            __builtin_amdgcn_s_sleep(2);
+            __builtin_amdgcn_s_sleep(SLEEP);
         }
     }
     return true;

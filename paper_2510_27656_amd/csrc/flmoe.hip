@@ -29,7 +29,7 @@ const char *kKernelNames[FL_KERNEL_COUNT] = {
 constexpr int kEventPool = 64;
 constexpr long long kMaxFabricBlocks = 1 << 16;   // waves loop cheaply (no barriers)
 constexpr long long kMaxRowBlocks = 1 << 18;      // blocks with barriers: loop only when far oversized
-constexpr long long kDefaultSpin = 1 << 22;
+constexpr long long kDefaultSpin = 1 << 20;       // polls about 2 us apart: gives up after about 2 s
 
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
@@ -465,12 +465,12 @@ int fl_moe_dispatch_recv(fl_moe_ctx *ctx, int rb, int rc, void *expert_x, float 
     hipStream_t st = (hipStream_t)stream;
     const int rbk = rows_per_block(D.Bw, D.tune_rows);
     // In unordered mode the receivers may be polling while senders still need
-    // somewhere to run: they take at most half of the resident-block slots.
+    // somewhere to run: they take at most three eighths of the resident-block slots (measured best).
     const bool unordered = D.flags & FL_FLAG_UNORDERED_FABRIC;
     const long long worst_rows = (long long)D.N * D.T;       // received rows in use never exceed this
     const long long max_rows = D.recv_rows < worst_rows ? D.recv_rows : worst_rows;
     unsigned gx = capped_grid((grid_rows(D, max_rows, D.typ_recv_rows) + rbk - 1) / rbk, rc,
-                              unordered ? (long long)ctx->cu_count * 4 : kMaxRowBlocks);
+                              unordered ? (long long)ctx->cu_count * 3 : kMaxRowBlocks);
     if (gx < (unsigned)D.El) gx = D.El;      // the first El-1 blocks also clear padding rows
     {
         LaunchTimer t(ctx, KID_DISPATCH_UNPACK, st);
@@ -574,8 +574,8 @@ int fl_moe_combine_reduce(fl_moe_ctx *ctx, int rb, int rc, const float *weights,
         if (nt > kReduceMaxThreads) nt = kReduceMaxThreads;
         if (nt < 2 * kWave) nt = 2 * kWave;      // wave 0 waits, wave 1 fetches positions and weights
         const bool unordered = D.flags & FL_FLAG_UNORDERED_FABRIC, partial = D.flags & FL_FLAG_PARTIAL_SUMS;
-        // polling receivers (unordered mode) take at most half of the machine
-        const dim3 grid(unordered ? capped_grid(D.T, rc, (long long)ctx->cu_count * 1024 / nt) : (unsigned)D.T, rc);
+        // polling receivers (unordered mode) take at most three eighths of the machine's wave slots
+        const dim3 grid(unordered ? capped_grid(D.T, rc, (long long)ctx->cu_count * 768 / nt) : (unsigned)D.T, rc);
         char *o = (char *)out;
         if (unordered && partial)
             combine_reduce_kernel<true, true><<<grid, dim3(nt), 0, st>>>(D, ctx->W, rb, weights, o, ctx->num_tokens);

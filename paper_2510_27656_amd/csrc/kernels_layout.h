@@ -203,7 +203,7 @@ __device__ __forceinline__ void route_plan_block(const Dims &D, const Tables &W,
         // word); this step is complete when every source's message count has caught up.
         const unsigned expect = W.epoch_route[r] + 1u;
         if (lane == 0) W.epoch_route[r] = expect;
-        if (!wave_wait_counters(W.arrive_route + (size_t)r * N, nullptr, expect, N, D.spin_limit)) {
+        if (!wave_wait_counters<2>(W.arrive_route + (size_t)r * N, nullptr, expect, N, D.spin_limit)) {
             if (lane == 0) { flag = 1; latch_status(W.status, FL_STATUS_TIMEOUT); }
         }
         acquire_payload<true>();

@@ -31,6 +31,8 @@
  *     dispatch_recv, combine_send, combine_reduce, with every rank of the group
  *     taking part in each (in one launch or several).  A receive call whose
  *     senders never ran ends with FL_STATUS_TIMEOUT, not with a hang.
+ *   - A context is not thread-safe: its calls come from one host thread at a
+ *     time.  Several contexts (each with its own workspace) are independent.
  *   - Return value: FL_OK or a negative FL_ERR_* for errors the host can see
  *     (nothing is enqueued then).  Errors found on the device (bad expert id,
  *     capacity overflow, arrival time-out) make the affected step a no-op on every
@@ -123,7 +125,8 @@ typedef struct fl_moe_config {
     int64_t recv_capacity_rows;   /* per rank: deduplicated rows it can receive; 0 = N*T  */
     int64_t expert_capacity_rows; /* per rank: rows of its expert-major layout, padding
                                      included; 0 = N*T*min(K, E/N) + padding              */
-    int64_t spin_limit;     /* polls of an arrival counter before FL_STATUS_TIMEOUT; 0 = default */
+    int64_t spin_limit;     /* polls of an arrival counter before FL_STATUS_TIMEOUT (a waiting wave
+                               polls about every 2 us); 0 = default, about 2 s                    */
     int32_t max_private_rows; /* P: the first P rows a source sends to a destination go to fixed
                                private slots at the head of the destination's receive buffer, in a
                                scatter of their own that needs no exchanged counts; only the rows

@@ -201,6 +201,25 @@ __device__ inline int seg_of(const int *off, int n, int x) {
     return lo;
 }
 
+// seg_of for a short table in global memory: all entries are fetched at once (one
+// round trip instead of one per halving step); *start receives off[result].
+__device__ inline int seg_of_short(const int *off, int n, int x, int *start) {
+    if (n > 16) {
+        const int j = seg_of(off, n, x);
+        *start = off[j];
+        return j;
+    }
+    int c[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) c[i] = i < n ? off[i] : 0x7fffffff;
+    int j = 0, cj = c[0];
+#pragma unroll
+    for (int i = 1; i < 16; ++i)
+        if (c[i] <= x) { j = i; cj = c[i]; }
+    *start = cj;
+    return j;
+}
+
 // ---------------------------------------------------------------- row copies
 // 16-byte streaming accesses.  The payload of every copy kernel is touched once
 // per kernel, so loads and stores carry the non-temporal hint; on this part a

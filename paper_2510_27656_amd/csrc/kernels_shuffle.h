@@ -516,9 +516,9 @@ __global__ __launch_bounds__(kCopyThreads) void combine_pack_kernel(
         if (tid < q1 - q0) {
             const int q = q0 + tid;
             const int s = seg_of(off, N, q);
-            const int *csb = W.cs_base + ((size_t)d * N + s) * El;
-            const int j = seg_of(csb, El, q);
-            src_row[tid] = W.base_x[((size_t)d * El + j) * N + s] + (q - csb[j]);
+            int first;                         // first reply row of (source s, local expert j)
+            const int j = seg_of_short(W.cs_base + ((size_t)d * N + s) * El, El, q, &first);
+            src_row[tid] = W.base_x[((size_t)d * El + j) * N + s] + (q - first);
             const int2 to = make_int2(s, W.comb_dst_off[(size_t)d * N + s] + (q - off[s]));
             if (PUSH) push_to[tid] = to;
             else W.fab_dst_comb[(size_t)d * D.expert_cap + q] = to;

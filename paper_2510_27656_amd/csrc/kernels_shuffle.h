@@ -38,6 +38,17 @@ __global__ __launch_bounds__(kPackThreads) void dispatch_pack_kernel(
     const int s = rank_begin + blockIdx.y, t = blockIdx.x / slices, slice = blockIdx.x % slices;
     const int tid = threadIdx.x;
     const int K = D.K, El = D.El;
+    // The slice's payload depends on nothing but (s, t): its loads are issued first, so
+    // that the validity check and the routing tables are fetched while they are in flight
+    // (x has T rows per rank, so the loads are in bounds for absent tokens too).
+    const int nvec = (int)(D.Bx / 16);
+    const int per = (nvec + slices - 1) / slices;          // vectors of this slice: [v0, v1)
+    const int v0 = slice * per, v1 = min(v0 + per, nvec);
+    const v4u *src = (const v4u *)(x + ((size_t)s * D.T + t) * D.Bx);
+    v4u r[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+        if (v0 + tid + i * kPackThreads < v1) r[i] = ld_stream(src + v0 + tid + i * kPackThreads);
     if (!W.plan_ok[s] || t >= num_tokens[s]) return;
     __shared__ int s_row[FL_MAX_TOPK];
     __shared__ int s_dst[FL_MAX_TOPK];
@@ -69,16 +80,13 @@ __global__ __launch_bounds__(kPackThreads) void dispatch_pack_kernel(
         for (; m < D.KM; ++m) st_word<PUSH && FENCED>((int *)meta + m, (int)kNoEntry);
         if (!PUSH) W.fab_dst_disp[(size_t)s * D.send_cap + my_row] = make_int2(my_d, target);
     }
-    const int nvec = (int)(D.Bx / 16);
-    const int per = (nvec + slices - 1) / slices;          // vectors of this slice: [v0, v1)
-    const int v0 = slice * per, v1 = min(v0 + per, nvec);
-    const v4u *src = (const v4u *)(x + ((size_t)s * D.T + t) * D.Bx);
     char *sendbuf = W.bufA + (size_t)s * D.bufA_rank_bytes;
     for (int b = v0 + tid; b < v1; b += 4 * kPackThreads) {
-        v4u r[4];
+        if (b != v0 + tid) {                   // later batches (rows beyond 8 KB per slice)
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
-            if (b + i * kPackThreads < v1) r[i] = ld_stream(src + b + i * kPackThreads);
+            for (int i = 0; i < 4; ++i)
+                if (b + i * kPackThreads < v1) r[i] = ld_stream(src + b + i * kPackThreads);
+        }
         for (int k = 0; k < K; ++k) {
             const int row = s_row[k];          // uniform: one copy per distinct destination
             if (row < 0) continue;

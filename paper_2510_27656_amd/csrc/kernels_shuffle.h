@@ -142,6 +142,17 @@ __global__ __launch_bounds__(kQuantThreads) void dispatch_pack_e4m3_kernel(
     const int s = rank_begin + blockIdx.y, t = blockIdx.x / slices, slice = blockIdx.x % slices;
     const int tid = threadIdx.x;
     const int K = D.K, El = D.El;
+    // as in dispatch_pack_kernel, the payload loads go first
+    const int nblk = D.scales_per_row;                          // 128-element blocks in the row
+    const int blk = slice * (kQuantThreads / kQuantLanes) + tid / kQuantLanes;
+    const int sub = tid % kQuantLanes;
+    const bool live = blk < nblk;
+    v4u in0 = {0u, 0u, 0u, 0u}, in1 = {0u, 0u, 0u, 0u};
+    if (live) {
+        const v4u *src = (const v4u *)(x + ((size_t)s * D.T + t) * D.Bx) + (size_t)blk * 16 + sub * 2;
+        in0 = ld_stream(src);
+        in1 = ld_stream(src + 1);
+    }
     if (!W.plan_ok[s] || t >= num_tokens[s]) return;
     __shared__ int s_row[FL_MAX_TOPK];
     __shared__ int s_dst[FL_MAX_TOPK];
@@ -172,16 +183,6 @@ __global__ __launch_bounds__(kQuantThreads) void dispatch_pack_e4m3_kernel(
             }
         for (; m < D.KM; ++m) st_word<PUSH && FENCED>((int *)meta + m, (int)kNoEntry);
         if (!PUSH) W.fab_dst_disp[(size_t)s * D.send_cap + my_row] = make_int2(my_d, target);
-    }
-    const int nblk = D.scales_per_row;                          // 128-element blocks in the row
-    const int blk = slice * (kQuantThreads / kQuantLanes) + tid / kQuantLanes;
-    const int sub = tid % kQuantLanes;
-    const bool live = blk < nblk;
-    v4u in0 = {0u, 0u, 0u, 0u}, in1 = {0u, 0u, 0u, 0u};
-    if (live) {
-        const v4u *src = (const v4u *)(x + ((size_t)s * D.T + t) * D.Bx) + (size_t)blk * 16 + sub * 2;
-        in0 = ld_stream(src);
-        in1 = ld_stream(src + 1);
     }
     float f[16];
     const unsigned w[8] = {in0.x, in0.y, in0.z, in0.w, in1.x, in1.y, in1.z, in1.w};

@@ -116,7 +116,7 @@ typedef struct fl_moe_config {
     int32_t n_experts;      /* E, multiple of N, <= FL_MAX_EXPERTS                       */
     int32_t max_tokens;     /* T, upper bound of tokens per rank                         */
     int32_t top_k;          /* K, 1..min(E, FL_MAX_TOPK)                                 */
-    int32_t hidden;         /* H                                                          */
+    int32_t hidden;         /* H, 8..2^20, 2*H a multiple of 16                           */
     int32_t dispatch_dtype; /* FL_DTYPE_*: payload type of dispatch; combine is bf16      */
     int32_t expert_align;   /* every local expert but the first starts on a multiple of
                                this many rows ("optional padding between experts",

@@ -54,7 +54,7 @@ int resolve(const fl_moe_config *c, Dims *D) {
     if (El > FL_MAX_EXPERTS_PER_RANK) return FL_ERR_INVALID_ARG;
     if (c->top_k < 1 || c->top_k > FL_MAX_TOPK || c->top_k > c->n_experts) return FL_ERR_INVALID_ARG;
     if (c->max_tokens < 1 || c->max_tokens >= (1 << 24)) return FL_ERR_INVALID_ARG;
-    if (c->hidden < 8) return FL_ERR_INVALID_ARG;
+    if (c->hidden < 8 || c->hidden > (1 << 20)) return FL_ERR_INVALID_ARG;
     if ((c->hidden * 2) % 16 != 0) return FL_ERR_ALIGNMENT;
     if (c->dispatch_dtype != FL_DTYPE_BF16 && c->dispatch_dtype != FL_DTYPE_E4M3_BLOCK128)
         return FL_ERR_INVALID_ARG;
@@ -303,8 +303,16 @@ int fl_moe_create(const fl_moe_config *cfg, void *workspace, size_t workspace_by
             ctx->cu_count = cus;
     }
     for (int i = 0; i < kEventPool; ++i) {
+        ctx->ev_start[i] = nullptr;
+        ctx->ev_stop[i] = nullptr;
+    }
+    for (int i = 0; i < kEventPool; ++i) {
         if (hipEventCreate(&ctx->ev_start[i]) != hipSuccess ||
             hipEventCreate(&ctx->ev_stop[i]) != hipSuccess) {
+            for (int j = 0; j <= i; ++j) {     // give back what was created so far
+                if (ctx->ev_start[j]) (void)hipEventDestroy(ctx->ev_start[j]);
+                if (ctx->ev_stop[j]) (void)hipEventDestroy(ctx->ev_stop[j]);
+            }
             delete ctx;
             return FL_ERR_HIP;
         }

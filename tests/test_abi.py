@@ -78,6 +78,7 @@ def test_private_rows_extend_the_receive_buffer():
     (dict(top_k=17), flmoe.FL_ERR_INVALID_ARG),
     (dict(top_k=0), flmoe.FL_ERR_INVALID_ARG),
     (dict(hidden=100), flmoe.FL_ERR_ALIGNMENT),
+    (dict(hidden=(1 << 20) + 8), flmoe.FL_ERR_INVALID_ARG),
     (dict(hidden=192, dispatch_dtype=1), flmoe.FL_ERR_ALIGNMENT),
     (dict(dispatch_dtype=7), flmoe.FL_ERR_INVALID_ARG),
     (dict(expert_align=0), flmoe.FL_ERR_INVALID_ARG),

@@ -208,6 +208,15 @@ def main():
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     assert sh.status() == 0
 
+    # host cost of enqueueing one step (the five C calls through the binding, nothing
+    # waited for): the part of the paper's CPU-overhead table that exists here
+    torch.cuda.synchronize()
+    h0 = time.perf_counter()
+    for _ in range(10):
+        step()
+    host_enqueue_us = (time.perf_counter() - h0) * 1e6 / 10
+    torch.cuda.synchronize()
+
     # per-call split with events on the stream the library launches on
     calls = ["layout", "dispatch_send", "dispatch_recv", "combine_send", "combine_reduce"]
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(args.profile_steps)]
@@ -381,6 +390,7 @@ def main():
         "latency_us": latency_us,
         "call_us": {k: round(v, 1) for k, v in call_us.items()},
         "single_rank_call_us": single_rank_us,
+        "host_enqueue_us_per_step": round(host_enqueue_us, 1),
         "kernel_us": {k: round(v, 2) for k, v in kern_us.items()},
         "kernel_gbps": {k: round(per_kernel[k] / (kern_us[k] * 1e-6) / 1e9, 1)
                         for k in kern_us if k in per_kernel},

@@ -16,6 +16,7 @@ import pytest
 import torch
 
 from oracle import oracle as orc
+from oracle.reference_step import oracle_step
 from paper_2510_27656_amd import workloads as wlmod
 
 HERE = os.path.dirname(os.path.abspath(__file__))
@@ -702,3 +703,30 @@ def test_random_shapes_against_brute_force_sort():
             assert got.shape[0] == len(rows[d])
             for r, st in enumerate(rows[d]):
                 assert (got[r] == (0 if st is None else inp.x[st[0], st[1]])).all()
+
+
+# ----------------------------------------------------------------- chunked prefill (host side)
+@pytest.mark.parametrize("chunk", [7, 32, 100, 250])
+def test_token_chunks_partition_the_batch_and_keep_every_tokens_result(chunk):
+    """workloads.token_chunk cuts tokens [t0, t0 + chunk) out of every rank, pads the last
+    chunk with absent tokens, and the oracle run chunk by chunk gives every token the
+    combined row of the one-shot run (a token's sum does not depend on its neighbours)."""
+    wl = wlmod.custom("chunks", 4, 16, 100, 64, 3, seed=95, ragged=True)
+    inp = wlmod.make_inputs(wl)
+    whole = oracle_step(inp)
+    seen = np.zeros((wl.n_ranks, wl.tokens), bool)
+    for t0 in range(0, wl.tokens, chunk):
+        piece = wlmod.token_chunk(inp, t0, chunk)
+        n = min(chunk, wl.tokens - t0)
+        assert piece.x.shape == (wl.n_ranks, chunk, wl.hidden) and piece.wl.tokens == chunk
+        assert (piece.x[:, :n] == inp.x[:, t0:t0 + n]).all()
+        assert (piece.indices[:, :n] == inp.indices[:, t0:t0 + n]).all()
+        assert (piece.weights[:, :n] == inp.weights[:, t0:t0 + n]).all()
+        assert (piece.num_tokens == np.clip(inp.num_tokens - t0, 0, n)).all()
+        ref = oracle_step(piece)
+        for s in range(wl.n_ranks):
+            k = int(piece.num_tokens[s])
+            assert (ref.out[s, :k] == whole.out[s, t0:t0 + k]).all()
+            seen[s, t0:t0 + k] = True
+    for s in range(wl.n_ranks):
+        assert seen[s, :inp.num_tokens[s]].all() and not seen[s, inp.num_tokens[s]:].any()

@@ -19,13 +19,17 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBPS = 8000.0
 
 
-def algorithmic_bytes(wl, ttot, D, P, sizes, push=False, partial=False):
+def algorithmic_bytes(wl, ttot, D, P, sizes, push=False, partial=False, ready=False):
     """Bytes the method itself has to move (reads + writes), per kernel.  Staged
     (default): pack into send buffers, scatter, unpack.  Push: the send kernels
     write into the receive buffers, so the send-buffer write and the scatter's
     read and write are not part of the method."""
-    Bx, Bw, Be, Bc = (sizes.x_row_bytes, sizes.wire_row_bytes,
-                      sizes.expert_x_row_bytes + 4 * sizes.scales_per_row, sizes.combine_row_bytes)
+    Be = sizes.expert_x_row_bytes + 4 * sizes.scales_per_row
+    # a dispatched row as the method defines it; the library pads e4m3 wire rows to whole
+    # 128-byte lines, and that padding is not counted as useful traffic
+    Bx, Bw, Bc = sizes.x_row_bytes, min(sizes.wire_row_bytes, Be), sizes.combine_row_bytes
+    if ready:        # the pack kernel reads wire-format rows instead of bf16 rows
+        Bx = Bw
     k = {
         "dispatch_pack_kernel": ttot * Bx + D * Bw,
         "fabric_copy_kernel(dispatch)": 2 * D * Bw,
@@ -41,7 +45,7 @@ def algorithmic_bytes(wl, ttot, D, P, sizes, push=False, partial=False):
         k["combine_reduce_kernel"] = D * Bc + ttot * Bc
     if push:
         del k["fabric_copy_kernel(dispatch)"], k["fabric_copy_kernel(combine)"]
-    if wl.dispatch_dtype != "bf16":
+    if wl.dispatch_dtype != "bf16" and not ready:
         k["dispatch_pack_e4m3_kernel"] = k.pop("dispatch_pack_kernel")
     dispatch = sum(v for n, v in k.items() if n.startswith(("dispatch", "fabric_copy_kernel(d")))
     combine = sum(v for n, v in k.items() if n.startswith(("combine", "fabric_copy_kernel(c")))
@@ -72,6 +76,9 @@ def main():
     ap.add_argument("--chunk-tokens", type=int, default=0,
                     help="chunked prefill: step a context sized for this many tokens per rank over the "
                          "workload's batch (reports time per whole batch and the workspace size)")
+    ap.add_argument("--ready-e4m3", action="store_true",
+                    help="e4m3 workloads: dispatch tokens that are already quantised (synthetic codes and "
+                         "scales), the payload of the paper's microbenchmark, instead of quantising bf16")
     ap.add_argument("--private-rows", type=int, default=0,
                     help="first rows per (source, destination) sent to private slots in a scatter "
                          "of their own (ablation of section Ablation: Private Buffer Size)")
@@ -114,7 +121,7 @@ def main():
                               max_private_rows=args.private_rows, peer_push=args.push,
                               partial_sums=args.partial_sums)
     ttot, D, P = stats["tokens_total"], stats["dedup_rows"], stats["pairs"]
-    per_kernel, bytes_dispatch, bytes_combine = algorithmic_bytes(wl, ttot, D, P, sh.sizes, args.push, args.partial_sums)
+    per_kernel, bytes_dispatch, bytes_combine = algorithmic_bytes(wl, ttot, D, P, sh.sizes, args.push, args.partial_sums, args.ready_e4m3)
     bytes_step = bytes_dispatch + bytes_combine
 
     expert_y = None
@@ -122,8 +129,17 @@ def main():
         expert_y = torch.zeros((wl.n_ranks, sh.expert_capacity_rows, wl.hidden),
                                dtype=torch.bfloat16, device="cuda:0")
 
+    ready = None
+    if args.ready_e4m3:
+        assert wl.dispatch_dtype != "bf16", "--ready-e4m3 needs a workload with e4m3 dispatch"
+        gen = torch.Generator(device="cuda:0").manual_seed(7)
+        codes = torch.randint(0, 0x78, (wl.n_ranks, wl.tokens, wl.hidden), dtype=torch.uint8,
+                              device="cuda:0", generator=gen)           # finite, positive codes
+        scales = torch.rand((wl.n_ranks, wl.tokens, wl.hidden // 128), device="cuda:0", generator=gen) + 0.5
+        ready = (codes, scales)
+
     def step():
-        harness.run_hot_path(sh, dev, expert_y)
+        harness.run_hot_path(sh, dev, expert_y, ready)
 
     if args.chunk_tokens:
         C = args.chunk_tokens
@@ -223,7 +239,11 @@ def main():
     for i in range(args.profile_steps):
         ev[i][0].record()
         sh.layout(dev["indices"], dev["num_tokens"]); ev[i][1].record()
-        sh.dispatch_send(dev["x"], weights=harness.send_weights(sh, dev)); ev[i][2].record()
+        if ready is None:
+            sh.dispatch_send(dev["x"], weights=harness.send_weights(sh, dev))
+        else:
+            sh.dispatch_send(ready[0], scales=ready[1], weights=harness.send_weights(sh, dev))
+        ev[i][2].record()
         sh.dispatch_recv(); ev[i][3].record()
         sh.combine_send(sh.expert_x if expert_y is None else expert_y); ev[i][4].record()
         sh.combine_reduce(dev["weights"]); ev[i][5].record()
@@ -245,7 +265,7 @@ def main():
     # other ranks' launches issued around them outside the brackets.  The layout call
     # cannot be split this way (its planning kernel waits for every peer's counts).
     single_rank_us = None
-    if wl.n_ranks > 1 and not big and not args.headline_only:
+    if wl.n_ranks > 1 and not big and not args.headline_only and ready is None:
         me, rest = (0, 1), (1, wl.n_ranks - 1)
         y = sh.expert_x if expert_y is None else expert_y
         reps = min(args.profile_steps, 50)
@@ -332,7 +352,8 @@ def main():
     # The same step with FL_FLAG_PEER_PUSH, beside the headline: fewer bytes by
     # construction, so its GB/s is computed against its own byte count.
     push_line = None
-    if not args.push and not big and not args.unordered and not args.headline_only and not args.partial_sums:
+    if not args.push and not big and not args.unordered and not args.headline_only and not args.partial_sums \
+            and not args.ready_e4m3:
         shp = harness.make_shuffle(inp, capacity_factor=cf, max_private_rows=args.private_rows,
                                    peer_push=True)
         _, pd, pc = algorithmic_bytes(wl, ttot, D, P, shp.sizes, True)
@@ -377,6 +398,7 @@ def main():
                    "dedup_rows": D, "pairs": P, "capacity_factor": cf, "private_rows": int(sh.sizes.private_rows),
                    "method": "peer push (no send buffer, no scatter)" if args.push else "staged (pack, scatter, unpack)",
                    "combine": "sender-side bf16 partial sums" if args.partial_sums else "fp32 sum in k order",
+                   "dispatch_input": "ready-made e4m3 codes + scales" if args.ready_e4m3 else "bf16",
                    "fabric": "unordered (release/acquire)" if args.unordered else "stream-ordered",
                    "expert_stage": "identity (expert_y aliases expert_x)" if expert_y is None
                    else "none in the timed path (resident bf16 expert_y)"},

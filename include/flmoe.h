@@ -145,7 +145,7 @@ typedef struct fl_moe_sizes {
     int64_t send_capacity_rows;   /* T * min(K, N)                                        */
     int64_t x_row_bytes;          /* 2*H                                                  */
     int64_t wire_row_bytes;       /* bytes of one dispatched row in the send/receive
-                                     buffers: 2*H, or H + 4*H/128 rounded up to 16 for e4m3 */
+                                     buffers: 2*H, or H + 4*H/128 rounded up to 128 for e4m3 */
     int64_t expert_x_row_bytes;   /* 2*H or H                                             */
     int64_t scales_per_row;       /* 0 or H/128                                           */
     int64_t combine_row_bytes;    /* 2*H                                                  */
@@ -227,6 +227,16 @@ int fl_moe_dispatch_send(fl_moe_ctx *ctx, int rank_begin, int rank_count, const 
  * weights pointer (unused, non-NULL). */
 int fl_moe_dispatch_send_weighted(fl_moe_ctx *ctx, int rank_begin, int rank_count, const void *x,
                                   const float *weights, void *stream);
+
+/* Step 2 for tokens the caller has already quantised (section Kernel
+ * Microbenchmarks: each dispatched token is 7168 fp8 values and 56 fp32 scaling
+ * factors).  Needs dispatch_dtype FL_DTYPE_E4M3_BLOCK128.  codes [N][T][H] e4m3
+ * bytes, scales [N][T][H/128] fp32 (one per 128 values, as fl_moe_dispatch_send
+ * would have produced them); both are copied unchanged into the wire rows, so
+ * expert_x / expert_scales receive exactly these bytes.  weights: NULL, or
+ * [N][T][K] when the context has FL_FLAG_PARTIAL_SUMS. */
+int fl_moe_dispatch_send_e4m3(fl_moe_ctx *ctx, int rank_begin, int rank_count, const void *codes,
+                              const float *scales, const float *weights, void *stream);
 
 /* Step 3 (section Dispatch: wait for all transfers, then reorder tokens with
  * optional padding into a layout suitable for grouped GEMM).  expert_x

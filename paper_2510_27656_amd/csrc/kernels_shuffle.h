@@ -34,17 +34,19 @@ template <bool PUSH, bool FENCED>
 __global__ __launch_bounds__(kPackThreads) void dispatch_pack_kernel(
     Dims D, Tables W, int rank_begin, const char *__restrict__ x,
     const int *__restrict__ indices, const int *__restrict__ num_tokens, int slices,
-    const float *__restrict__ weights /* [N][T][K], only when the sidecar carries them */) {
+    const float *__restrict__ weights /* [N][T][K], only when the sidecar carries them */,
+    long long src_row_bytes /* bytes of one row of x: 2*H, or H for ready-made e4m3 codes */,
+    const float *__restrict__ src_scales /* [N][T][H/128] with ready-made codes, else null */) {
     const int s = rank_begin + blockIdx.y, t = blockIdx.x / slices, slice = blockIdx.x % slices;
     const int tid = threadIdx.x;
     const int K = D.K, El = D.El;
     // The slice's payload depends on nothing but (s, t): its loads are issued first, so
     // that the validity check and the routing tables are fetched while they are in flight
     // (x has T rows per rank, so the loads are in bounds for absent tokens too).
-    const int nvec = (int)(D.Bx / 16);
+    const int nvec = (int)(src_row_bytes / 16);
     const int per = (nvec + slices - 1) / slices;          // vectors of this slice: [v0, v1)
     const int v0 = slice * per, v1 = min(v0 + per, nvec);
-    const v4u *src = (const v4u *)(x + ((size_t)s * D.T + t) * D.Bx);
+    const v4u *src = (const v4u *)(x + ((size_t)s * D.T + t) * src_row_bytes);
     v4u r[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i)
@@ -98,11 +100,39 @@ __global__ __launch_bounds__(kPackThreads) void dispatch_pack_kernel(
                     st_payload<PUSH && FENCED, true>(dst + b + i * kPackThreads, r[i]);
         }
     }
+    // Ready-made e4m3 codes (section Kernel Microbenchmarks: the dispatched token is 7168
+    // fp8 values and 56 fp32 scaling factors): the scales follow the codes in the wire row.
+    const bool with_scales = src_scales != nullptr && slice == 0;
+    if (with_scales) {
+        const float *sc = src_scales + ((size_t)s * D.T + t) * D.scales_per_row;
+        if (D.scales_per_row % 4 == 0) {       // whole 16-byte vectors (rows of scales stay aligned)
+            for (int v = tid; v < D.scales_per_row / 4; v += kPackThreads) {
+                const v4u val = ld_stream((const v4u *)sc + v);
+                for (int k = 0; k < K; ++k) {
+                    const int row = s_row[k];
+                    if (row < 0) continue;
+                    char *base = PUSH ? W.bufB + (size_t)s_dst[k] * D.bufB_rank_bytes : sendbuf;
+                    st_payload<PUSH && FENCED, true>((v4u *)(base + (size_t)row * D.Bw + D.Be) + v, val);
+                }
+            }
+        } else {
+            for (int v = tid; v < D.scales_per_row; v += kPackThreads) {
+                const int val = __float_as_int(sc[v]);
+                for (int k = 0; k < K; ++k) {
+                    const int row = s_row[k];
+                    if (row < 0) continue;
+                    char *base = PUSH ? W.bufB + (size_t)s_dst[k] * D.bufB_rank_bytes : sendbuf;
+                    st_word<PUSH && FENCED>((int *)(base + (size_t)row * D.Bw + D.Be) + v, val);
+                }
+            }
+        }
+    }
     if (PUSH && FENCED) {                      // what this block delivered, per destination
         stores_done<FENCED>();
         __syncthreads();
-        if (tid < K && my_row >= 0 && v1 > v0)
-            add_counter(W.arrive_disp + (size_t)my_d * D.N + s, (unsigned)(v1 - v0));
+        const unsigned units = (unsigned)(v1 - v0) + (with_scales ? (unsigned)((D.Bw - D.Be) / 16) : 0u);
+        if (tid < K && my_row >= 0 && units > 0)
+            add_counter(W.arrive_disp + (size_t)my_d * D.N + s, units);
     }
 }
 
@@ -232,8 +262,12 @@ __global__ __launch_bounds__(kQuantThreads) void dispatch_pack_e4m3_kernel(
         const int n_live = min(nblk - blk0, kQuantThreads / kQuantLanes);
         stores_done<FENCED>();
         __syncthreads();
+        // the padding that brings a wire row to a whole number of 128-byte lines is nobody's
+        // to write; the first block claims it so that a row's units add up to Bw / 16
+        const int pad_units = (int)(D.Bw / 16) - (nblk * 8 + (nblk + 3) / 4);
         if (tid < K && my_row >= 0 && n_live > 0)
-            add_counter(W.arrive_disp + (size_t)my_d * D.N + s, (unsigned)(n_live * 8 + (n_live + 3) / 4));
+            add_counter(W.arrive_disp + (size_t)my_d * D.N + s,
+                        (unsigned)(n_live * 8 + (n_live + 3) / 4 + (slice == 0 ? pad_units : 0)));
     }
 }
 

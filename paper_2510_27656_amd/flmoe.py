@@ -56,7 +56,8 @@ class fl_moe_debug_view(C.Structure):
 
 
 EXPORTS = ["fl_moe_query_sizes", "fl_moe_create", "fl_moe_destroy", "fl_moe_layout",
-           "fl_moe_dispatch_send", "fl_moe_dispatch_send_weighted", "fl_moe_dispatch_recv",
+           "fl_moe_dispatch_send", "fl_moe_dispatch_send_weighted", "fl_moe_dispatch_send_e4m3",
+           "fl_moe_dispatch_recv",
            "fl_moe_combine_send",
            "fl_moe_combine_reduce", "fl_moe_status", "fl_moe_strerror", "fl_moe_debug_views",
            "fl_moe_debug_tune", "fl_moe_debug_copy", "fl_moe_profile_enable", "fl_moe_profile_collect", "fl_moe_profile_read",
@@ -80,6 +81,7 @@ def lib():
         L.fl_moe_layout.argtypes = [vp, i32, i32, vp, vp, C.POINTER(fl_moe_layout_view), vp]
         L.fl_moe_dispatch_send.argtypes = [vp, i32, i32, vp, vp]
         L.fl_moe_dispatch_send_weighted.argtypes = [vp, i32, i32, vp, vp, vp]
+        L.fl_moe_dispatch_send_e4m3.argtypes = [vp, i32, i32, vp, vp, vp, vp]
         L.fl_moe_dispatch_recv.argtypes = [vp, i32, i32, vp, vp, vp, vp]
         L.fl_moe_combine_send.argtypes = [vp, i32, i32, vp, vp]
         L.fl_moe_combine_reduce.argtypes = [vp, i32, i32, vp, vp, vp]
@@ -153,6 +155,12 @@ def fl_moe_layout(ctx, rank_begin, rank_count, indices, num_tokens, stream=None)
 def fl_moe_dispatch_send(ctx, rank_begin, rank_count, x, stream=None):
     _check(lib().fl_moe_dispatch_send(ctx, rank_begin, rank_count, _ptr(x), _stream(stream)),
            "fl_moe_dispatch_send")
+
+
+def fl_moe_dispatch_send_e4m3(ctx, rank_begin, rank_count, codes, scales, weights=None, stream=None):
+    _check(lib().fl_moe_dispatch_send_e4m3(ctx, rank_begin, rank_count, _ptr(codes), _ptr(scales),
+                                           _ptr(weights) if weights is not None else None,
+                                           _stream(stream)), "fl_moe_dispatch_send_e4m3")
 
 
 def fl_moe_dispatch_send_weighted(ctx, rank_begin, rank_count, x, weights, stream=None):
@@ -276,9 +284,11 @@ class MoEShuffle:
         self.view = fl_moe_layout(self.ctx, rb, rc, indices, num_tokens, stream)
         return self.view
 
-    def dispatch_send(self, x, ranks=None, stream=None, weights=None):
+    def dispatch_send(self, x, ranks=None, stream=None, weights=None, scales=None):
         rb, rc = self._ranks(ranks)
-        if weights is None:
+        if scales is not None:          # x holds e4m3 codes the caller quantised itself
+            fl_moe_dispatch_send_e4m3(self.ctx, rb, rc, x, scales, weights, stream)
+        elif weights is None:
             fl_moe_dispatch_send(self.ctx, rb, rc, x, stream)
         else:
             fl_moe_dispatch_send_weighted(self.ctx, rb, rc, x, weights, stream)

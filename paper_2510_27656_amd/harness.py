@@ -88,12 +88,16 @@ def run_step(sh: flmoe.MoEShuffle, dev, identity=False, ranks=None):
     return sh.combine_reduce(dev["weights"], ranks)
 
 
-def run_hot_path(sh: flmoe.MoEShuffle, dev, expert_y=None):
+def run_hot_path(sh: flmoe.MoEShuffle, dev, expert_y=None, ready=None):
     """The five calls back to back.  bf16 dispatch: identity expert, expert_y aliases
     expert_x.  e4m3 dispatch: the caller passes a resident bf16 expert_y of the layout's
-    shape (the stand-in expert is not part of the timed path)."""
+    shape (the stand-in expert is not part of the timed path).  ready: e4m3 codes and
+    scales already on the device, dispatched as they are."""
     sh.layout(dev["indices"], dev["num_tokens"])
-    sh.dispatch_send(dev["x"], weights=send_weights(sh, dev))
+    if ready is None:
+        sh.dispatch_send(dev["x"], weights=send_weights(sh, dev))
+    else:                                # (codes, scales) the caller quantised itself
+        sh.dispatch_send(ready[0], scales=ready[1], weights=send_weights(sh, dev))
     sh.dispatch_recv()
     sh.combine_send(sh.expert_x if expert_y is None else expert_y)
     return sh.combine_reduce(dev["weights"])

@@ -823,6 +823,70 @@ def test_chunked_steps_give_the_same_combined_output(chunk):
         sh.close()
 
 
+# ------------------------------------------------------------------ tokens the caller quantised itself
+@pytest.mark.parametrize("name", list(FP8_CASES))
+@pytest.mark.parametrize("kw", [dict(), dict(peer_push=True), dict(unordered_fabric=True, peer_push=True),
+                                dict(partial_sums=True, max_private_rows=5)])
+def test_dispatch_of_ready_made_e4m3_tokens(name, kw):
+    """fl_moe_dispatch_send_e4m3 (section Kernel Microbenchmarks: the dispatched token is
+    fp8 values plus fp32 scaling factors): codes and scales quantised beforehand, here by
+    the oracle, arrive in expert_x / expert_scales byte for byte, and the rest of the step
+    is the one of the quantise-on-the-fly path."""
+    inp = wlmod.make_inputs(FP8_CASES[name]())
+    wl = inp.wl
+    N = wl.n_ranks
+    partial = kw.get("partial_sums", False)
+    ref = oracle_step(inp, partial=partial)
+    want = ref.out_partial if partial else ref.out
+    q, sc = orc.quant_e4m3_block128(inp.x)
+    dev = harness.to_device(inp)
+    codes = torch.from_numpy(q).cuda()
+    scales = torch.from_numpy(sc).cuda()
+    sh = harness.make_shuffle(inp, **kw)
+    try:
+        sh.out.view(torch.int16).fill_(POISON)
+        sh.layout(dev["indices"], dev["num_tokens"])
+        sh.dispatch_send(codes, scales=scales, weights=harness.send_weights(sh, dev))
+        sh.dispatch_recv()
+        y = harness.expert_stage(sh, dev["gain"], wl.expert == "identity")
+        sh.combine_send(y)
+        out = sh.combine_reduce(dev["weights"])
+        torch.cuda.synchronize()
+        assert sh.status() == 0
+        check_tables(sh, ref, N)
+        ex = sh.expert_x[:, :ref.stride].cpu().numpy()
+        exs = sh.expert_scales[:, :ref.stride].cpu().numpy().view(np.uint32)
+        for d in range(N):
+            n = ref.expert_rows[d].shape[0]
+            assert (ex[d, :n] == ref.expert_rows[d]).all(), f"e4m3 bytes, rank {d}"
+            assert (exs[d, :n] == ref.expert_scales[d].view(np.uint32)).all(), f"scales, rank {d}"
+        ob = bits(out)
+        for s in range(N):
+            k = inp.num_tokens[s]
+            assert (ob[s, :k] == want[s, :k]).all()
+            assert (ob[s, k:] == POISON).all()
+        dbg = sh.debug()
+        assert (dbg["arrive_disp"] == dbg["expect_disp"]).all()
+    finally:
+        sh.close()
+
+
+def test_ready_made_e4m3_needs_an_e4m3_context():
+    inp = wlmod.make_inputs(CASES["tiny"]())
+    dev = harness.to_device(inp)
+    sh = harness.make_shuffle(inp)
+    try:
+        harness.run_step(sh, dev, identity=True)
+        fake = torch.zeros((2, 16, 256), dtype=torch.uint8, device="cuda")
+        fsc = torch.ones((2, 16, 2), dtype=torch.float32, device="cuda")
+        with pytest.raises(flmoe.FlMoeError) as ei:
+            sh.dispatch_send(fake, scales=fsc)
+        assert ei.value.code == flmoe.FL_ERR_INVALID_ARG
+        torch.cuda.synchronize()
+    finally:
+        sh.close()
+
+
 # ------------------------------------------------------------------ failure handling
 def small_shuffle(spin_limit=0, **kw):
     inp = wlmod.make_inputs(CASES["ragged_520"]())

@@ -211,11 +211,12 @@ int fl_moe_layout(fl_moe_ctx *ctx, int rank_begin, int rank_count, const int32_t
                   const int32_t *num_tokens, fl_moe_layout_view *view /*host*/, void *stream);
 
 /* Step 2 (section Dispatch: tokens are copied into send buffers, a contiguous
- * source per peer, then scattered).  x [N][T][H] bf16.  Packs one copy of each
- * token per distinct destination rank (quantising to e4m3 when configured),
- * copies every (source, destination) segment into the destination's receive
- * buffer and adds what was delivered (in 16-byte units) to
- * arrive_disp[destination][source]. */
+ * source per peer, then scattered).  x [N][T][H] bf16; all T rows of a rank
+ * must be addressable (rows of absent tokens may be read, they are never used).
+ * Packs one copy of each token per distinct destination rank (quantising to
+ * e4m3 when configured), copies every (source, destination) segment into the
+ * destination's receive buffer and adds what was delivered (in 16-byte units)
+ * to arrive_disp[destination][source]. */
 int fl_moe_dispatch_send(fl_moe_ctx *ctx, int rank_begin, int rank_count, const void *x,
                          void *stream);
 

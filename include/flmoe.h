@@ -193,7 +193,10 @@ int fl_moe_query_sizes(const fl_moe_config *cfg /*host*/, fl_moe_sizes *out /*ho
 
 /* Binds a context to a caller-owned device workspace of at least
  * sizes.workspace_bytes bytes and clears its counters (this call synchronises;
- * it is set-up, not part of the hot path). */
+ * it is set-up, not part of the hot path).  The workspace must be 256-byte
+ * aligned; when it is 2 MB aligned (large device allocations are) the big payload
+ * buffers inside it start on 2 MB pages too, which the copy kernels measurably
+ * like. */
 int fl_moe_create(const fl_moe_config *cfg /*host*/, void *workspace, size_t workspace_bytes,
                   fl_moe_ctx **out /*host*/);
 int fl_moe_destroy(fl_moe_ctx *ctx);

@@ -383,6 +383,19 @@ def main():
                "kind": "oracle", "seconds_per_step": round(per, 3), "repetitions": reps,
                "sample": f"{reps} full {wl.name} steps (all {wl.n_ranks} ranks, {ttot} tokens each), "
                          "same algorithmic byte count per step, single thread"}
+        # The same untouched oracle on all the host cores this job may use: one whole
+        # step per thread, side by side (its C routines run outside the interpreter lock).
+        workers = max(1, min(16, len(os.sched_getaffinity(0))))
+        if workers > 1 and not big:
+            from concurrent.futures import ThreadPoolExecutor
+            rounds = max(1, min(4, int(10.0 / max(per, 1e-3) / workers + 0.5)))
+            a0 = time.perf_counter()
+            with ThreadPoolExecutor(workers) as pool:
+                list(pool.map(lambda _: [oracle_step(inp) for _ in range(rounds)], range(workers)))
+            aper = (time.perf_counter() - a0) / (rounds * workers)
+            cpu["all_cores"] = {"value": round(bytes_step / aper / 1e9, 3), "unit": "GB/s", "cores": workers,
+                                "sample": f"{rounds * workers} full steps, {workers} threads with "
+                                          f"{rounds} step(s) each"}
 
     value = bytes_step / (ms_per_step * 1e-3) / 1e9
     line = {

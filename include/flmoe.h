@@ -29,8 +29,11 @@
  *     allocate, and can be captured in a HIP graph.
  *   - One step = the five calls once each, in the order layout, dispatch_send,
  *     dispatch_recv, combine_send, combine_reduce, with every rank of the group
- *     taking part in each (in one launch or several).  A receive call whose
- *     senders never ran ends with FL_STATUS_TIMEOUT, not with a hang.
+ *     taking part in each.  The payload calls may be split over several launches
+ *     by rank range.  fl_moe_layout waits inside the call for every peer's counts,
+ *     as ranks on separate GPUs wait for each other: all ranks go into one launch,
+ *     or into launches the device can run at the same time (different streams).
+ *     A call whose peers never ran ends with FL_STATUS_TIMEOUT, not with a hang.
  *   - A context is not thread-safe: its calls come from one host thread at a
  *     time.  Several contexts (each with its own workspace) are independent.
  *   - Return value: FL_OK or a negative FL_ERR_* for errors the host can see
@@ -86,9 +89,11 @@ extern "C" {
  * simulated ranks live on one GPU).  The send calls then write each row and its
  * sidecar straight into the destination's receive buffer: no send buffer is
  * filled and no scatter kernel runs; the arrival counters advance as in the
- * staged path (after the kernel, or per workgroup with FL_FLAG_UNORDERED_FABRIC).  Receivers, counters, capacities and every result are
- * unchanged; only the bytes moved per step shrink (one write per sent row instead
- * of write + read + write).  Combines with the other flags and max_private_rows. */
+ * staged path (after the kernel, or per workgroup with
+ * FL_FLAG_UNORDERED_FABRIC).  Receivers, counters, capacities and every result
+ * are unchanged; only the bytes moved per step shrink (one write per sent row
+ * instead of write + read + write).  Combines with the other flags and
+ * max_private_rows. */
 #define FL_FLAG_PEER_PUSH 4
 /* Combine with sender-side partial sums (section Comparison with DeepEP and the
  * prefill results of section Performance: pre-accumulating on the sending side

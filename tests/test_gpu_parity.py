@@ -969,6 +969,32 @@ def test_missing_peers_time_out_instead_of_hanging():
         sh.close()
 
 
+def test_layout_split_over_two_streams_meets_in_the_exchange():
+    """Half of the ranks plan on one stream, half on another: each half waits inside
+    the call for the other's counts, as ranks on separate GPUs do (bounded wait)."""
+    inp, dev, sh = small_shuffle()
+    try:
+        ref = oracle_step(inp)
+        a, b = torch.cuda.Stream(), torch.cuda.Stream()
+        torch.cuda.synchronize()
+        sh.layout(dev["indices"], dev["num_tokens"], ranks=(0, 2), stream=a)
+        sh.layout(dev["indices"], dev["num_tokens"], ranks=(2, 2), stream=b)
+        torch.cuda.synchronize()
+        sh.dispatch_send(dev["x"])
+        sh.dispatch_recv()
+        y = harness.expert_stage(sh, dev["gain"])
+        sh.combine_send(y)
+        out = sh.combine_reduce(dev["weights"])
+        torch.cuda.synchronize()
+        assert sh.status() == 0
+        check_tables(sh, ref, inp.wl.n_ranks)
+        for r in range(inp.wl.n_ranks):
+            n = inp.num_tokens[r]
+            assert (bits(out)[r, :n] == ref.out[r, :n]).all()
+    finally:
+        sh.close()
+
+
 def test_withheld_arrival_counter_times_out_then_recovers():
     inp, dev, sh = small_shuffle(spin_limit=200)
     try:

@@ -288,7 +288,7 @@ int fl_moe_debug_views(fl_moe_ctx *ctx, fl_moe_debug_view *out /*host*/);
  * the fabric kernel (0 = chosen from the row size, else 1..16), knob 3 =
  * workgroups per token in the pack kernel (0 = chosen from the row size, at
  * most 16), knob 4 = size in MiB of the receive buffers a fabric launch may
- * write above which it uses streaming instead of cached stores (default 1024),
+ * write above which it uses streaming instead of cached stores (default 2560),
  * knob 5 = percentage of the rows uniform routing would bring to a rank that the
  * grids of the receive-side and reply kernels are sized for (default 200; 0 = the
  * whole capacity; a rank that holds more is served by the kernels' row loops). */

@@ -114,7 +114,7 @@ int resolve(const fl_moe_config *c, Dims *D) {
     D->tune_reduce = 0;
     D->tune_waves = 0;
     D->tune_slices = 0;
-    D->tune_stream_mb = 1024;
+    D->tune_stream_mb = 2560;
     D->tune_grid_pct = 200;
     {   // a token reaches a given rank with probability 1 - (1 - 1/N)^K when experts are drawn uniformly
         double miss = 1.0;

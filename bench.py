@@ -295,17 +295,23 @@ def main():
         flmoe.fl_moe_profile_collect(sh.ctx)
     flmoe.fl_moe_profile_enable(sh.ctx, 0)
     prof = flmoe.fl_moe_profile_read(sh.ctx)
-    kern_us = {n: ms / cnt * 1e3 for n, (ms, cnt) in prof.items() if cnt}
-    dominant = max((n for n in kern_us if n in per_kernel), key=lambda n: kern_us[n])
-    achieved = per_kernel[dominant] / (kern_us[dominant] * 1e-6) / 1e9
+    kern_us = {n: ms / cnt * 1e3 for n, (ms, cnt) in prof.items() if cnt}          # per launch
+    # launches per step: 1, except transfer_done (once per send call) and calls that move
+    # several GB, which the library issues as one launch per group of ranks
+    kern_launches = {n: cnt / args.profile_steps for n, (ms, cnt) in prof.items() if cnt}
+    step_us_of = {n: kern_us[n] * kern_launches[n] for n in kern_us}
+    dominant = max((n for n in kern_us if n in per_kernel), key=lambda n: step_us_of[n])
+    launch_bytes = per_kernel[dominant] / kern_launches[dominant]
+    achieved = launch_bytes / (kern_us[dominant] * 1e-6) / 1e9
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     if os.path.exists(tpath):
         traffic = json.load(open(tpath)).get(args.workload, {}).get(dominant)
     roofline = {"bound": "hbm", "kernel": dominant, "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                "traffic": traffic, "algorithmic_bytes": per_kernel[dominant],
-                "avg_us": round(kern_us[dominant], 2)}
+                "traffic": traffic, "algorithmic_bytes": round(launch_bytes),
+                "avg_us": round(kern_us[dominant], 2),
+                "launches_per_step": round(kern_launches[dominant], 2)}
 
     # cold protocol (the paper clears caches between iterations): a 2 GiB copy between
     # steps evicts the 256 MB last-level cache; per-call medians with HIP events
@@ -427,7 +433,8 @@ def main():
         "single_rank_call_us": single_rank_us,
         "host_enqueue_us_per_step": round(host_enqueue_us, 1),
         "kernel_us": {k: round(v, 2) for k, v in kern_us.items()},
-        "kernel_gbps": {k: round(per_kernel[k] / (kern_us[k] * 1e-6) / 1e9, 1)
+        "kernel_launches_per_step": {k: round(v, 2) for k, v in kern_launches.items()},
+        "kernel_gbps": {k: round(per_kernel[k] / (step_us_of[k] * 1e-6) / 1e9, 1)
                         for k in kern_us if k in per_kernel},
         "hip_graph_replay": graph_line,
         "peer_push_variant": push_line,

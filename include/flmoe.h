@@ -26,7 +26,9 @@
  *     copy and its counters.  A real deployment would pass rank_count = 1.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  The
  *     five shuffle calls only enqueue kernels: they never synchronise, never
- *     allocate, and can be captured in a HIP graph.
+ *     allocate, and can be captured in a HIP graph.  A call that moves several GB
+ *     enqueues its kernels once per group of ranks (very large launches run
+ *     measurably slower than the same work in launches of about a GB).
  *   - One step = the five calls once each, in the order layout, dispatch_send,
  *     dispatch_recv, combine_send, combine_reduce, with every rank of the group
  *     taking part in each.  The payload calls may be split over several launches
@@ -291,7 +293,10 @@ int fl_moe_debug_views(fl_moe_ctx *ctx, fl_moe_debug_view *out /*host*/);
  * write above which it uses streaming instead of cached stores (default 2560),
  * knob 5 = percentage of the rows uniform routing would bring to a rank that the
  * grids of the receive-side and reply kernels are sized for (default 200; 0 = the
- * whole capacity; a rank that holds more is served by the kernels' row loops). */
+ * whole capacity; a rank that holds more is served by the kernels' row loops),
+ * knob 6 = payload in MiB one launch should move per direction: a call whose ranks
+ * move more than three times as much is issued as several launches over rank
+ * groups of about this size (default 860; 0 = always one launch per kernel). */
 int fl_moe_debug_tune(fl_moe_ctx *ctx, int knob, int value);
 
 /* Diagnostic: plain linear device copy of `bytes` bytes with 16-byte accesses

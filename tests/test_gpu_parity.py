@@ -44,7 +44,7 @@ def check_tables(sh, ref, N):
 
 
 def run_and_compare(inp, align=1, zero_pad=False, capacity_factor=None, ranks_split=False,
-                    unordered=False, private_rows=0, push=False, partial=False):
+                    unordered=False, private_rows=0, push=False, partial=False, launch_mb=None):
     wl = inp.wl
     N, T = wl.n_ranks, wl.tokens
     ref = oracle_step(inp, align, zero_pad=True, partial=partial)
@@ -55,6 +55,8 @@ def run_and_compare(inp, align=1, zero_pad=False, capacity_factor=None, ranks_sp
                               capacity_factor=capacity_factor, unordered_fabric=unordered,
                               max_private_rows=private_rows, peer_push=push)
     try:
+        if launch_mb is not None:        # payload per launch above which a call is cut into rank groups
+            flmoe.fl_moe_debug_tune(sh.ctx, 6, launch_mb)
         if wl.dispatch_dtype == "bf16":
             sh.expert_x.view(torch.int16).fill_(POISON)
         sh.out.view(torch.int16).fill_(POISON)
@@ -401,6 +403,44 @@ def test_parity_random_shapes_and_mode_combinations():
         inp = wlmod.make_inputs(wl)
         print(f"trial {trial}: N={N} El={El} K={K} T={T} H={H} fp8={fp8} {modes}", flush=True)
         sh, _, _ = run_and_compare(inp, align=int(rng.choice([1, 4])), zero_pad=True, **modes)
+        sh.close()
+
+
+@pytest.mark.parametrize("kw", [dict(), dict(unordered=True), dict(push=True), dict(ranks_split=True),
+                                dict(partial=True, private_rows=20), dict(fp8=True, align=4),
+                                dict(unordered=True, push=True, partial=True, fp8=True)])
+def test_large_calls_are_issued_as_several_launches_over_rank_groups(kw):
+    """A call that moves several times the per-launch target enqueues its kernels once
+    per group of ranks; here the target is set to 1 MiB so that a small step is cut into
+    one launch per rank.  Same results, and the launch counts show the cut happened."""
+    kw = dict(kw)
+    fp8 = kw.pop("fp8", False)
+    wl = wlmod.custom("groups", 8, 32, 128, 1024, 4, seed=77, ragged=True,
+                      dispatch_dtype="e4m3" if fp8 else "bf16")
+    inp = wlmod.make_inputs(wl)
+    sh, _, _ = run_and_compare(inp, zero_pad=True, launch_mb=1, **kw)
+    try:
+        dev = harness.to_device(inp)
+        before = flmoe.fl_moe_profile_read(sh.ctx)
+        flmoe.fl_moe_profile_enable(sh.ctx, 1)
+        harness.run_step(sh, dev)
+        flmoe.fl_moe_profile_collect(sh.ctx)
+        flmoe.fl_moe_profile_enable(sh.ctx, 0)
+        after = flmoe.fl_moe_profile_read(sh.ctx)
+        assert sh.status() == 0
+        launches = {k: after[k][1] - before[k][1] for k in after}
+        assert launches["route_layout_kernel"] == 1
+        assert launches["dispatch_unpack_kernel"] == wl.n_ranks
+        assert launches["combine_reduce_kernel"] == wl.n_ranks
+        flmoe.fl_moe_debug_tune(sh.ctx, 6, 0)          # never cut
+        before = after
+        flmoe.fl_moe_profile_enable(sh.ctx, 1)
+        harness.run_step(sh, dev)
+        flmoe.fl_moe_profile_collect(sh.ctx)
+        flmoe.fl_moe_profile_enable(sh.ctx, 0)
+        after = flmoe.fl_moe_profile_read(sh.ctx)
+        assert after["dispatch_unpack_kernel"][1] - before["dispatch_unpack_kernel"][1] == 1
+    finally:
         sh.close()
 
 

@@ -207,7 +207,7 @@ def main():
         flmoe.fl_moe_debug_copy(a, b, 1 << 30)
         torch.cuda.synchronize()
         assert sh.status() == 0
-        print(json.dumps({"counters_run": True, "workload": wl.name, "copy_bytes": 1 << 30,
+        print(json.dumps({"counters_run": True, "workload": wl.name, "copy_bytes": 1 << 30, "steps": 3,
                           "algorithmic_bytes": per_kernel}))
         sh.close()
         return

@@ -308,7 +308,8 @@ int fl_moe_debug_copy(void *dst, const void *src, size_t bytes, void *stream);
  * every kernel launch of the shuffle calls is bracketed by an event pair;
  * fl_moe_profile_collect synchronises, adds the elapsed times of the launches
  * since the last collect to per-kernel totals, and fl_moe_profile_read returns
- * totals (ms) and launch counts for kernel ids 0..FL_KERNEL_COUNT-1. */
+ * totals (ms) and launch counts for kernel ids 0..FL_KERNEL_COUNT-1.  At most
+ * 512 launches between two collects are timed; further ones run untimed. */
 #define FL_KERNEL_COUNT 11
 int fl_moe_profile_enable(fl_moe_ctx *ctx, int on);
 int fl_moe_profile_collect(fl_moe_ctx *ctx, void *stream);

@@ -1,4 +1,5 @@
-"""The bench.py contract: one JSON line with the agreed keys; more than one GPU is refused."""
+"""The driver-facing entry points: bench.py prints one JSON line with the agreed keys and
+refuses more than one GPU; smoke() runs."""
 import json
 import os
 import subprocess
@@ -42,3 +43,10 @@ def test_bench_prints_one_json_line_with_the_agreed_keys():
         assert key in cpu, key
     assert cpu["kind"] == "oracle" and cpu["cores"] >= 1 and cpu["value"] > 0
     assert line["value"] > 0 and line["ms_per_step"] > 0
+
+
+@pytest.mark.gpu
+def test_smoke_entry_point_runs():
+    sys.path.insert(0, ROOT)
+    import __graft_entry__ as entry
+    entry.smoke()

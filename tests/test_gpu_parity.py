@@ -281,6 +281,42 @@ def test_parity_e4m3_dispatch_edge_values():
     sh.close()
 
 
+def test_parity_e4m3_dispatch_every_finite_bf16_value():
+    """All 65 280 finite bf16 bit patterns, each quantised against several block maxima
+    (from its own magnitude up to 2^20 times larger: top codes, low codes, subnormal
+    codes, zero) and once in random company: same codes and scales as the oracle."""
+    wl = wlmod.custom("fp8_all_values", 2, 8, 64, 3200, 2, seed=35, dispatch_dtype="e4m3")
+    inp = wlmod.make_inputs(wl)
+    x = inp.x.reshape(-1, 128)
+    assert x.shape[0] == 3200
+    pats = np.arange(65536, dtype=np.uint32)
+    pats = pats[(pats & 0x7f80) != 0x7f80].astype(np.uint16)          # finite values only
+    mag = (pats & 0x7fff).astype(np.int32)
+    pats = pats[np.argsort(mag, kind="stable")]                        # by magnitude, signs alternate
+    chunks = [pats[i:i + 127] for i in range(0, len(pats), 127)]
+    as_f32 = lambda b: (b.astype(np.uint32) << 16).view(np.float32)
+    to_bf16 = lambda v: torch.tensor(v, dtype=torch.float32).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    row = 0
+    for mult in (1.0, 3.0, 37.0, 1000.0, 2.0 ** 20):
+        for c in chunks:
+            top = float(np.abs(as_f32(c)).max())
+            setter = to_bf16([min(top * mult, 3.0e38)])[0]
+            x[row, :len(c)] = c
+            x[row, len(c):] = setter
+            row += 1
+    rng = np.random.default_rng(35)
+    mixed = rng.permutation(pats)
+    for i in range(0, len(mixed), 127):
+        c = mixed[i:i + 127]
+        x[row, :len(c)] = c
+        x[row, len(c):] = 0
+        row += 1
+    assert row <= 3200
+    x[row:] = 0
+    sh, _, _ = run_and_compare(inp, zero_pad=True)
+    sh.close()
+
+
 def test_parity_named_workload_dsv3_fp8():
     inp = wlmod.make_inputs(wlmod.WORKLOADS["dsv3_fp8"])
     sh, _, _ = run_and_compare(inp)

@@ -144,18 +144,19 @@ __global__ __launch_bounds__(kPackThreads) void dispatch_pack_kernel(
 //
 // OCP E4M3, finite-only: 1 sign, 4 exponent bits (bias 7), 3 mantissa bits,
 // subnormals m * 2^-9, largest finite 448, no infinities.
-__device__ inline unsigned e4m3_encode(float v) {
-    unsigned u = __float_as_uint(v);
-    const unsigned sign = (u >> 24) & 0x80u;
-    u &= 0x7fffffffu;
-    if (u > 0x7f800000u) return sign | 0x7fu;          // NaN
-    if (u >= 0x43e00000u) return sign | 0x7eu;         // |v| >= 448 saturates
-    if (u >= 0x3c800000u) {                            // |v| >= 2^-6: a normal e4m3 number
-        u += 0x7ffffu + ((u >> 20) & 1u);              // drop 20 mantissa bits, ties to even
-        return sign | ((u >> 20) - (120u << 3));       // re-bias the exponent: 127 -> 7
-    }
-    // subnormal range: m = rne(|v| * 2^9), m = 8 is the smallest normal number
-    return sign | (unsigned)__float2int_rn(__uint_as_float(u) * 512.0f);
+//
+// Four quotients to four e4m3 bytes with the part's own converter (OCP E4M3 on
+// gfx950, round to nearest even, subnormals included; checked against the oracle's
+// arithmetic encoder on every finite bf16 input under several block maxima).  A quotient can exceed 448
+// by one fp32 step (both divisions round), so magnitudes are held at 448 first;
+// NaN passes through the comparison and converts to a NaN code.
+__device__ inline float e4m3_hold(float v) {
+    return fabsf(v) >= 448.0f ? copysignf(448.0f, v) : v;
+}
+__device__ inline unsigned e4m3_pack4(float a, float b, float c, float d) {
+    int w = __builtin_amdgcn_cvt_pk_fp8_f32(e4m3_hold(a), e4m3_hold(b), 0, false);
+    w = __builtin_amdgcn_cvt_pk_fp8_f32(e4m3_hold(c), e4m3_hold(d), w, true);
+    return (unsigned)w;
 }
 
 constexpr int kQuantLanes = 8;     // lanes per 128-element block: 16 bf16 values each
@@ -227,9 +228,8 @@ __global__ __launch_bounds__(kQuantThreads) void dispatch_pack_e4m3_kernel(
     unsigned q[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i)
-        q[i] = e4m3_encode(__fdiv_rn(f[4 * i], scale)) | (e4m3_encode(__fdiv_rn(f[4 * i + 1], scale)) << 8) |
-               (e4m3_encode(__fdiv_rn(f[4 * i + 2], scale)) << 16) |
-               (e4m3_encode(__fdiv_rn(f[4 * i + 3], scale)) << 24);
+        q[i] = e4m3_pack4(__fdiv_rn(f[4 * i], scale), __fdiv_rn(f[4 * i + 1], scale),
+                          __fdiv_rn(f[4 * i + 2], scale), __fdiv_rn(f[4 * i + 3], scale));
     const v4u out = {q[0], q[1], q[2], q[3]};
     // the block's scales are gathered in LDS and stored as 16-byte vectors when the
     // row's scale count allows it (scattered 4-byte stores are partial-line writes)

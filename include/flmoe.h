@@ -299,6 +299,13 @@ int fl_moe_debug_views(fl_moe_ctx *ctx, fl_moe_debug_view *out /*host*/);
  * groups of about this size (default 860; 0 = always one launch per kernel). */
 int fl_moe_debug_tune(fl_moe_ctx *ctx, int knob, int value);
 
+/* Diagnostic, host only (no GPU needed): how a payload call over `rank_count` ranks of
+ * this configuration is cut into launches.  launch_mb as knob 6 above (-1 = the
+ * default).  *ranks_per_group receives the ranks one launch serves (rank_count
+ * when the call is not cut; the last group may be smaller). */
+int fl_moe_debug_launch_groups(const fl_moe_config *cfg /*host*/, int rank_count, int launch_mb,
+                               int *ranks_per_group /*host*/);
+
 /* Diagnostic: plain linear device copy of `bytes` bytes with 16-byte accesses
  * (multiple of 16, both pointers 16-byte aligned).  Used to measure the copy ceiling of the
  * machine and to calibrate hardware byte counters against a known size. */

@@ -32,6 +32,7 @@ constexpr long long kMaxRowBlocks = 1 << 18;      // blocks with barriers: loop 
 constexpr long long kDefaultSpin = 1 << 20;       // polls about 2 us apart: gives up after about 2 s
 
 constexpr size_t kBigPage = 2u << 20;
+constexpr int kLaunchMiB = 860;
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 // Walks the workspace; with base == nullptr it only measures.
@@ -227,7 +228,7 @@ struct fl_moe_ctx {
     const int32_t *indices = nullptr;
     const int32_t *num_tokens = nullptr;
     int cu_count = 256;
-    int launch_mb = 860;          // payload a launch should move per direction, see ranks_per_launch
+    int launch_mb = kLaunchMiB;   // payload a launch should move per direction, see ranks_per_launch
     // profiling
     int profile = 0;
     hipEvent_t ev_start[kEventPool], ev_stop[kEventPool];
@@ -265,12 +266,11 @@ int launch_status() { return hipGetLastError() == hipSuccess ? FL_OK : FL_ERR_HI
 // 4096-token step: 8 % faster in 2-rank launches), while cutting a launch that is
 // small already only adds launch tails.  So a call whose ranks move more than three
 // times the target is cut into rank groups of about the target size.
-int ranks_per_launch(const fl_moe_ctx *ctx, int rc) {
-    if (ctx->launch_mb <= 0) return rc;
-    const Dims &D = ctx->D;
+int ranks_per_launch(const Dims &D, int launch_mb, int rc) {
+    if (launch_mb <= 0) return rc;
     const long long row = D.Bw > D.Bc ? D.Bw : D.Bc;
     const long long per_rank = (long long)D.T * D.K * row;
-    const long long target = (long long)ctx->launch_mb << 20;
+    const long long target = (long long)launch_mb << 20;
     if (per_rank * rc <= 3 * target) return rc;
     long long launches = (per_rank * rc + target - 1) / target;
     if (launches > rc) launches = rc;
@@ -282,7 +282,7 @@ template <class F>
 int for_rank_groups(const fl_moe_ctx *ctx, int rb, int rc, F f) {
     int e = check_ranks(ctx, rb, rc);
     if (e != FL_OK) return e;
-    const int g = ranks_per_launch(ctx, rc);
+    const int g = ranks_per_launch(ctx->D, ctx->launch_mb, rc);
     for (int r = rb; r < rb + rc; r += g) {
         const int n = rb + rc - r < g ? rb + rc - r : g;
         e = f(r, n);
@@ -726,6 +726,16 @@ int fl_moe_debug_tune(fl_moe_ctx *ctx, int knob, int value) {
         case 6: ctx->launch_mb = value; break;
         default: return FL_ERR_INVALID_ARG;
     }
+    return FL_OK;
+}
+
+int fl_moe_debug_launch_groups(const fl_moe_config *cfg, int rank_count, int launch_mb, int *ranks_per_group) {
+    if (!ranks_per_group || launch_mb < -1) return FL_ERR_INVALID_ARG;
+    Dims D;
+    int e = resolve(cfg, &D);
+    if (e != FL_OK) return e;
+    if (rank_count < 1 || rank_count > D.N) return FL_ERR_INVALID_ARG;
+    *ranks_per_group = ranks_per_launch(D, launch_mb < 0 ? kLaunchMiB : launch_mb, rank_count);
     return FL_OK;
 }
 

@@ -60,7 +60,7 @@ EXPORTS = ["fl_moe_query_sizes", "fl_moe_create", "fl_moe_destroy", "fl_moe_layo
            "fl_moe_dispatch_recv",
            "fl_moe_combine_send",
            "fl_moe_combine_reduce", "fl_moe_status", "fl_moe_strerror", "fl_moe_debug_views",
-           "fl_moe_debug_tune", "fl_moe_debug_copy", "fl_moe_profile_enable", "fl_moe_profile_collect", "fl_moe_profile_read",
+           "fl_moe_debug_tune", "fl_moe_debug_launch_groups", "fl_moe_debug_copy", "fl_moe_profile_enable", "fl_moe_profile_collect", "fl_moe_profile_read",
            "fl_moe_kernel_name"]
 
 _lib = None
@@ -90,6 +90,7 @@ def lib():
         L.fl_moe_strerror.restype = C.c_char_p
         L.fl_moe_debug_views.argtypes = [vp, C.POINTER(fl_moe_debug_view)]
         L.fl_moe_debug_tune.argtypes = [vp, i32, i32]
+        L.fl_moe_debug_launch_groups.argtypes = [C.POINTER(fl_moe_config), i32, i32, C.POINTER(C.c_int)]
         L.fl_moe_debug_copy.argtypes = [vp, vp, C.c_size_t, vp]
         L.fl_moe_profile_enable.argtypes = [vp, i32]
         L.fl_moe_profile_collect.argtypes = [vp, vp]
@@ -199,6 +200,13 @@ def fl_moe_debug_views(ctx) -> fl_moe_debug_view:
 
 def fl_moe_debug_tune(ctx, knob, value):
     _check(lib().fl_moe_debug_tune(ctx, knob, value), "fl_moe_debug_tune")
+
+
+def fl_moe_debug_launch_groups(cfg: fl_moe_config, rank_count: int, launch_mb: int = -1) -> int:
+    out = C.c_int(0)
+    _check(lib().fl_moe_debug_launch_groups(C.byref(cfg), rank_count, launch_mb, C.byref(out)),
+           "fl_moe_debug_launch_groups")
+    return out.value
 
 
 def fl_moe_debug_copy(dst, src, nbytes, stream=None):

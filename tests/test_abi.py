@@ -103,3 +103,30 @@ def test_null_arguments_are_errors_not_crashes():
     assert L.fl_moe_strerror(flmoe.FL_ERR_WORKSPACE) == b"workspace too small"
     names = [L.fl_moe_kernel_name(i).decode() for i in range(flmoe.FL_KERNEL_COUNT)]
     assert all(names) and len(set(names)) == flmoe.FL_KERNEL_COUNT
+
+
+def test_large_calls_are_cut_into_rank_groups_small_ones_are_not():
+    """Host rule behind the launches of a payload call: one launch while the ranks of the
+    call move at most three times the per-launch target (860 MiB by default), otherwise
+    groups of ranks of about the target size; row = the larger of wire and combine row."""
+    groups = flmoe.fl_moe_debug_launch_groups
+    dsv3 = dict(n_ranks=32, n_experts=256, top_k=8, hidden=7168)
+    per_rank_128 = 128 * 8 * 14336
+    assert per_rank_128 * 32 <= 3 * (860 << 20)
+    assert groups(cfg(max_tokens=128, **dsv3), 32) == 32          # decode: 470 MB, one launch
+    assert groups(cfg(max_tokens=512, **dsv3), 32) == 32          # 1.9 GB: still one launch
+    assert groups(cfg(max_tokens=1024, **dsv3), 32) == 7          # 3.8 GB -> 5 launches
+    assert groups(cfg(max_tokens=2048, **dsv3), 32) == 4
+    assert groups(cfg(max_tokens=4096, **dsv3), 32) == 2          # prefill: 16 launches of 2 ranks
+    assert groups(cfg(max_tokens=4096, **dsv3), 1) == 1           # one real rank's call is never cut
+    assert groups(cfg(max_tokens=4096, **dsv3), 32, 0) == 32      # knob 0: never cut
+    assert groups(cfg(max_tokens=128, **dsv3), 32, 1) == 1        # tiny target: one rank per launch
+    assert groups(cfg(max_tokens=1 << 20, **dsv3), 32) == 1       # never below one rank
+    # e4m3 dispatch: the combine row (bf16) is the larger one and decides
+    assert groups(cfg(max_tokens=4096, dispatch_dtype=flmoe.FL_DTYPE_E4M3_BLOCK128, **dsv3), 32) == 2
+    lib = flmoe.lib()
+    out = C.c_int(0)
+    c = cfg(max_tokens=128, **dsv3)
+    assert lib.fl_moe_debug_launch_groups(C.byref(c), 0, -1, C.byref(out)) == flmoe.FL_ERR_INVALID_ARG
+    assert lib.fl_moe_debug_launch_groups(C.byref(c), 33, -1, C.byref(out)) == flmoe.FL_ERR_INVALID_ARG
+    assert lib.fl_moe_debug_launch_groups(C.byref(c), 32, -1, None) == flmoe.FL_ERR_INVALID_ARG

@@ -28,7 +28,8 @@
  *     five shuffle calls only enqueue kernels: they never synchronise, never
  *     allocate, and can be captured in a HIP graph.  A call that moves several GB
  *     enqueues its kernels once per group of ranks (very large launches run
- *     measurably slower than the same work in launches of about a GB).
+ *     measurably slower than the same work in launches of about a GB), except
+ *     with FL_FLAG_UNORDERED_FABRIC.
  *   - One step = the five calls once each, in the order layout, dispatch_send,
  *     dispatch_recv, combine_send, combine_reduce, with every rank of the group
  *     taking part in each.  The payload calls may be split over several launches
@@ -296,7 +297,8 @@ int fl_moe_debug_views(fl_moe_ctx *ctx, fl_moe_debug_view *out /*host*/);
  * whole capacity; a rank that holds more is served by the kernels' row loops),
  * knob 6 = payload in MiB one launch should move per direction: a call whose ranks
  * move more than three times as much is issued as several launches over rank
- * groups of about this size (default 860; 0 = always one launch per kernel). */
+ * groups of about this size (default 860; 0 = always one launch per kernel;
+ * contexts with FL_FLAG_UNORDERED_FABRIC are never cut). */
 int fl_moe_debug_tune(fl_moe_ctx *ctx, int knob, int value);
 
 /* Diagnostic, host only (no GPU needed): how a payload call over `rank_count` ranks of

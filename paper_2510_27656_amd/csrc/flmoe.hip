@@ -265,9 +265,12 @@ int launch_status() { return hipGetLastError() == hipSuccess ? FL_OK : FL_ERR_HI
 // (a plain copy: 6.1 TB/s in 1 GiB launches, 5.7 TB/s as one 12 GiB launch; the
 // 4096-token step: 8 % faster in 2-rank launches), while cutting a launch that is
 // small already only adds launch tails.  So a call whose ranks move more than three
-// times the target is cut into rank groups of about the target size.
+// times the target is cut into rank groups of about the target size.  Not in
+// unordered mode: its receive kernels run on capped grids and its copies write
+// through, and there the cut measured 3 % slower (and the caller who overlaps
+// senders and receivers chooses the granularity of the send calls itself).
 int ranks_per_launch(const Dims &D, int launch_mb, int rc) {
-    if (launch_mb <= 0) return rc;
+    if (launch_mb <= 0 || (D.flags & FL_FLAG_UNORDERED_FABRIC)) return rc;
     const long long row = D.Bw > D.Bc ? D.Bw : D.Bc;
     const long long per_rank = (long long)D.T * D.K * row;
     const long long target = (long long)launch_mb << 20;

@@ -122,6 +122,7 @@ def test_large_calls_are_cut_into_rank_groups_small_ones_are_not():
     assert groups(cfg(max_tokens=4096, **dsv3), 32, 0) == 32      # knob 0: never cut
     assert groups(cfg(max_tokens=128, **dsv3), 32, 1) == 1        # tiny target: one rank per launch
     assert groups(cfg(max_tokens=1 << 20, **dsv3), 32) == 1       # never below one rank
+    assert groups(cfg(max_tokens=4096, flags=flmoe.FL_FLAG_UNORDERED_FABRIC, **dsv3), 32) == 32   # not in that mode
     # e4m3 dispatch: the combine row (bf16) is the larger one and decides
     assert groups(cfg(max_tokens=4096, dispatch_dtype=flmoe.FL_DTYPE_E4M3_BLOCK128, **dsv3), 32) == 2
     lib = flmoe.lib()

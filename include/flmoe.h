@@ -76,9 +76,9 @@ extern "C" {
 /* Without this flag the caller keeps each send call before the matching receive
  * call in stream order (one stream, or events between streams); the arrival
  * counters are then checked with relaxed atomics and no cache maintenance, and
- * advanced once per (sender, receiver) transfer by a small kernel that follows
- * the copy kernel in stream order, as a NIC delivers one immediate after a whole
- * WRITE.  With it, send and receive kernels may overlap in time (other
+ * advanced once per (sender, receiver) transfer by the kernel that copies the
+ * payload (its end, in stream order, is what makes payload and counters visible
+ * to the receivers), as a NIC delivers one immediate after a whole WRITE.  With it, send and receive kernels may overlap in time (other
  * streams, other orders): a sender writes its payload through to memory
  * (device-scope stores) and waits for the acknowledgement before it reports
  * progress (every wave adds what it delivered, so a receiver sees a source's

@@ -466,6 +466,7 @@ static int dispatch_send_range(fl_moe_ctx *ctx, int rb, int rc, const void *x, c
     A.src_meta = W.send_meta; A.src_meta_rank_stride = D.send_cap * D.MW;
     A.dst_meta = W.recv_meta; A.dst_meta_rank_stride = D.recv_rows * D.MW;
     A.dst_row_lo = 0;
+    A.announce = 0;
     A.arrive = W.arrive_disp;
     A.row_bytes = D.Bw; A.waves_per_row = waves_per_row(D.Bw, D.tune_waves);
     const int wpb = kCopyThreads / kWave;
@@ -475,6 +476,7 @@ static int dispatch_send_range(fl_moe_ctx *ctx, int rb, int rc, const void *x, c
     if (D.P > 0) {
         // First scatter: the rows bound for private slots.  Their targets follow from the
         // sender's own counts alone, so this launch reads nothing a peer produced.
+        A.announce = !fenced && D.P >= D.T;   // the call's last copy kernel announces the transfers
         LaunchTimer t(ctx, KID_DISPATCH_FABRIC_PRIVATE, st);
         const unsigned g1 = capped_grid(((long long)D.N * D.P * A.waves_per_row + wpb - 1) / wpb, rc,
                                         kMaxFabricBlocks, A.waves_per_row);
@@ -487,6 +489,7 @@ static int dispatch_send_range(fl_moe_ctx *ctx, int rb, int rc, const void *x, c
         A.dst_row_lo = D.N * D.P;             // second scatter: the rest, into the shared range
     }
     if (D.P < D.T) {                          // with P = T every row has a private slot
+        A.announce = !fenced;
         LaunchTimer t(ctx, KID_DISPATCH_FABRIC, st);
         if (D.flags & FL_FLAG_UNORDERED_FABRIC)
             fabric_copy_kernel<true, 0, true><<<dim3(gx, rc), dim3(kCopyThreads), 0, st>>>(D, W, A, rb);
@@ -495,7 +498,6 @@ static int dispatch_send_range(fl_moe_ctx *ctx, int rb, int rc, const void *x, c
         else
             fabric_copy_kernel<false, 0, false><<<dim3(gx, rc), dim3(kCopyThreads), 0, st>>>(D, W, A, rb);
     }
-    announce(0);
     return launch_status();
 }
 
@@ -619,6 +621,7 @@ static int combine_send_range(fl_moe_ctx *ctx, int rb, int rc, const void *exper
     A.src_meta = nullptr; A.src_meta_rank_stride = 0;
     A.dst_meta = nullptr; A.dst_meta_rank_stride = 0;
     A.dst_row_lo = 0;
+    A.announce = !fenced;
     A.arrive = W.arrive_comb;
     A.row_bytes = D.Bc; A.waves_per_row = waves_per_row(D.Bc, D.tune_waves);
     const int wpb = kCopyThreads / kWave;
@@ -635,7 +638,6 @@ static int combine_send_range(fl_moe_ctx *ctx, int rb, int rc, const void *exper
         else
             fabric_copy_kernel<false, 1, false><<<dim3(gxf, rc), dim3(kCopyThreads), 0, st>>>(D, W, A, rb);
     }
-    announce();
     return launch_status();
 }
 

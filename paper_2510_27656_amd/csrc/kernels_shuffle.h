@@ -28,8 +28,8 @@ constexpr int kMaxRowsPerBlock = 64;
 // go straight into the destinations' receive buffers; no send buffer is filled
 // and no scatter follows.  FENCED (unordered fabric, PUSH only): device-scope
 // stores, and the block adds the 16-byte units it wrote to
-// arrive[destination][source] itself once they are acknowledged; stream-ordered,
-// transfer_done_kernel announces the transfers after this kernel.
+// arrive[destination][source] itself once they are acknowledged; stream-ordered
+// with PUSH, transfer_done_kernel announces the transfers after this kernel.
 template <bool PUSH, bool FENCED>
 __global__ __launch_bounds__(kPackThreads) void dispatch_pack_kernel(
     Dims D, Tables W, int rank_begin, const char *__restrict__ x,
@@ -283,8 +283,8 @@ __global__ __launch_bounds__(kQuantThreads) void dispatch_pack_e4m3_kernel(
 // delivered to arrive[destination][source] with an atomic whose result nobody
 // waits for: the counters only ever say "this much of source s's payload has
 // landed", in whatever order waves finish.  In stream-ordered mode nobody may
-// look before the kernel has ended, and transfer_done_kernel announces each
-// whole transfer afterwards.
+// look before the kernel has ended, and one wave per sender announces each whole
+// transfer (fabric_announce).
 struct FabricArgs {
     const char *src_base; long long src_rank_stride;
     char *dst_base;       long long dst_rank_stride;
@@ -297,7 +297,24 @@ struct FabricArgs {
     long long row_bytes;
     int waves_per_row;    // 1..16
     int dst_row_lo;       // rows whose target row is below this belong to the private-slot scatter
+    int announce;         // stream-ordered mode: this launch also advances arrive[.][s] (see fabric_announce)
 };
+
+// Stream-ordered mode: one add per (sender, receiver) announces the whole
+// transfer, like the single immediate a NIC delivers after a WRITE (section
+// TransferEngine, ImmCounter).  It is issued by one wave per sender inside the
+// last copy kernel of the call: receivers are ordered after that kernel by the
+// stream, so they find counters and payload complete together, and no extra
+// launch is spent.  (Per-wave announcements, as in unordered mode, cost more than
+// they give here: adds to one counter from many compute dies serialise at about
+// 0.2 us each, which made skewed routing several times slower.)
+__device__ inline void fabric_announce(const FabricArgs &A, int s, int N, int lane) {
+    const unsigned units = (unsigned)(A.row_bytes / 16);
+    for (int p = lane; p < N; p += kWave) {
+        const int rows = A.seg_off[(size_t)s * (N + 1) + p + 1] - A.seg_off[(size_t)s * (N + 1) + p];
+        if (rows) add_counter(A.arrive + (size_t)p * N + s, (unsigned)rows * units);
+    }
+}
 
 // One wave's share of one row: slice `sub` of `G` (vectors v with (v / 64) % G ==
 // sub), the sidecar when it is slice 0, and in unordered mode the count of
@@ -327,7 +344,7 @@ __device__ inline void fabric_send_row(const Dims &D, const FabricArgs &A, int s
         v4u *md = (v4u *)(A.dst_meta + (size_t)dst_rank * A.dst_meta_rank_stride) + (size_t)dst_row * mv;
         if (lane < mv) st_payload<FENCED, STREAMING>(md + lane, ms[lane]);
     }
-    if (FENCED) {          // stream-ordered launches are followed by transfer_done_kernel instead
+    if (FENCED) {          // stream-ordered launches announce whole transfers instead (fabric_announce)
         const int full = nvec / step, rem = nvec - full * step;
         const int mine = full * kWave + min(max(rem - sub * kWave, 0), kWave);
         stores_done<FENCED>();
@@ -357,6 +374,7 @@ __global__ __launch_bounds__(kCopyThreads) void fabric_copy_kernel(Dims D, Table
         i += row_stride;
         if (i < total) t = A.row_dst[(size_t)s * A.row_cap + i];
     }
+    if (!FENCED && A.announce && wave == 0 && ok) fabric_announce(A, s, N, lane);
 }
 
 // First scatter of a dispatch with private slots (section Dispatch: tokens up to
@@ -379,16 +397,13 @@ __global__ __launch_bounds__(kCopyThreads) void fabric_private_kernel(Dims D, Ta
         const int lo = A.seg_off[(size_t)s * (N + 1) + d], hi = A.seg_off[(size_t)s * (N + 1) + d + 1];
         if (i < hi - lo) fabric_send_row<FENCED, STREAMING>(D, A, s, lo + i, d, s * P + i, sub, lane);
     }
+    if (!FENCED && A.announce && wave == 0) fabric_announce(A, s, N, lane);
 }
 
 // ------------------------------------------------------------------ completion of whole transfers
-// Stream-ordered mode: launched right after the kernel(s) that moved the payload
-// of ranks [rank_begin, ...), so every byte is in place when it runs.  One add
-// per (sender, receiver) announces the whole transfer, like the single immediate
-// a NIC delivers after a WRITE (section TransferEngine, ImmCounter): lane = peer.
-// Per-wave announcements from inside the copy kernels cost more than they give
-// in this mode: adds to one counter from many compute dies serialise (about
-// 0.2 us each), which made skewed routing several times slower.
+// Stream-ordered peer push: no copy kernel runs, so the announcement of
+// fabric_announce gets a launch of its own, right after the pack kernel that
+// stored the payload of ranks [rank_begin, ...) into the peers' buffers: lane = peer.
 __global__ __launch_bounds__(kWave) void transfer_done_kernel(Dims D, Tables W, int rank_begin,
                                                               int combine) {
     const int r = rank_begin + blockIdx.x, N = D.N;

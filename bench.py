@@ -296,7 +296,7 @@ def main():
     flmoe.fl_moe_profile_enable(sh.ctx, 0)
     prof = flmoe.fl_moe_profile_read(sh.ctx)
     kern_us = {n: ms / cnt * 1e3 for n, (ms, cnt) in prof.items() if cnt}          # per launch
-    # launches per step: 1, except transfer_done (peer push: once per send call) and calls that move
+    # launches per step: 1, except for calls that move
     # several GB, which the library issues as one launch per group of ranks
     kern_launches = {n: cnt / args.profile_steps for n, (ms, cnt) in prof.items() if cnt}
     step_us_of = {n: kern_us[n] * kern_launches[n] for n in kern_us}

@@ -319,7 +319,7 @@ int fl_moe_debug_copy(void *dst, const void *src, size_t bytes, void *stream);
  * since the last collect to per-kernel totals, and fl_moe_profile_read returns
  * totals (ms) and launch counts for kernel ids 0..FL_KERNEL_COUNT-1.  At most
  * 512 launches between two collects are timed; further ones run untimed. */
-#define FL_KERNEL_COUNT 11
+#define FL_KERNEL_COUNT 10
 int fl_moe_profile_enable(fl_moe_ctx *ctx, int on);
 int fl_moe_profile_collect(fl_moe_ctx *ctx, void *stream);
 int fl_moe_profile_read(fl_moe_ctx *ctx, double *total_ms /*host [FL_KERNEL_COUNT]*/,

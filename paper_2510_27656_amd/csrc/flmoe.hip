@@ -18,13 +18,13 @@ namespace {
 enum KernelId {
     KID_ROUTE_LAYOUT = 0, KID_DISPATCH_PACK, KID_DISPATCH_FABRIC,
     KID_DISPATCH_UNPACK, KID_COMBINE_PACK, KID_COMBINE_FABRIC, KID_COMBINE_REDUCE,
-    KID_DISPATCH_PACK_E4M3, KID_DISPATCH_FABRIC_PRIVATE, KID_TRANSFER_DONE, KID_COMBINE_PARTIAL_PACK
+    KID_DISPATCH_PACK_E4M3, KID_DISPATCH_FABRIC_PRIVATE, KID_COMBINE_PARTIAL_PACK
 };
 const char *kKernelNames[FL_KERNEL_COUNT] = {
     "route_layout_kernel", "dispatch_pack_kernel", "fabric_copy_kernel(dispatch)",
     "dispatch_unpack_kernel", "combine_pack_kernel", "fabric_copy_kernel(combine)",
     "combine_reduce_kernel", "dispatch_pack_e4m3_kernel", "fabric_copy_kernel(dispatch, private slots)",
-    "transfer_done_kernel", "combine_partial_pack_kernel"};
+    "combine_partial_pack_kernel"};
 
 constexpr int kEventPool = 512;
 constexpr long long kMaxFabricBlocks = 1 << 16;   // waves loop cheaply (no barriers)
@@ -450,15 +450,7 @@ static int dispatch_send_range(fl_moe_ctx *ctx, int rb, int rc, const void *x, c
             dispatch_pack_kernel<false, false><<<grid, block, 0, st>>>(D, W, rb, xp, ctx->indices,
                                                                        ctx->num_tokens, slices, weights, src_row, ready_scales);
     }
-    auto announce = [&](int combine) {         // stream-ordered: one add per finished transfer
-        if (fenced) return;                    // unordered: the copy kernels announce as they go
-        LaunchTimer t(ctx, KID_TRANSFER_DONE, st);
-        transfer_done_kernel<<<dim3(rc), dim3(kWave), 0, st>>>(D, W, rb, combine);
-    };
-    if (push) {                                // the rows are already in the peers' receive buffers
-        announce(0);
-        return launch_status();
-    }
+    if (push) return launch_status();         // the rows are already in the peers' receive buffers
     FabricArgs A;
     A.src_base = W.bufA; A.src_rank_stride = D.bufA_rank_bytes;
     A.dst_base = W.bufB; A.dst_rank_stride = D.bufB_rank_bytes;
@@ -605,15 +597,7 @@ static int combine_send_range(fl_moe_ctx *ctx, int rb, int rc, const void *exper
             else combine_pack_kernel<false, false><<<grid, block, 0, st>>>(D, W, rb, yp, rbk);
         }
     }
-    auto announce = [&]() {
-        if (fenced) return;
-        LaunchTimer t(ctx, KID_TRANSFER_DONE, st);
-        transfer_done_kernel<<<dim3(rc), dim3(kWave), 0, st>>>(D, W, rb, partial ? 2 : 1);
-    };
-    if (push) {                                // the rows are already in the sources' receive buffers
-        announce();
-        return launch_status();
-    }
+    if (push) return launch_status();         // the rows are already in the sources' receive buffers
     FabricArgs A;
     A.src_base = W.bufB; A.src_rank_stride = D.bufB_rank_bytes;
     A.dst_base = W.bufA; A.dst_rank_stride = D.bufA_rank_bytes;

@@ -15,6 +15,25 @@ constexpr int kCopyThreads = 256;
 constexpr int kPackThreads = 128;
 constexpr int kMaxRowsPerBlock = 64;
 
+// Stream-ordered mode: one add per (sender, receiver) announces the whole
+// transfer, like the single immediate a NIC delivers after a WRITE (section
+// TransferEngine, ImmCounter).  It is issued once per sender inside the kernel of
+// the send call that writes into the receivers' buffers (the scatter kernel, or
+// with PUSH the pack kernel): receivers are ordered after that kernel by the
+// stream, so they find counters and payload complete together, and no extra
+// launch is spent.  (Per-wave announcements, as in unordered mode, cost more than
+// they give here: adds to one counter from many compute dies serialise at about
+// 0.2 us each, which made skewed routing several times slower.)
+// off = the sender's row of the segment table ([N + 1] row offsets by receiver);
+// threads first, first + step, ... each take one receiver.
+__device__ inline void announce_transfers(const int *off, unsigned *arrive, unsigned units_per_row,
+                                          int sender, int N, int first, int step) {
+    for (int p = first; p < N; p += step) {
+        const int rows = off[p + 1] - off[p];
+        if (rows) add_counter(arrive + (size_t)p * N + sender, (unsigned)rows * units_per_row);
+    }
+}
+
 // ------------------------------------------------------------------ dispatch: pack
 // `slices` blocks per token (s, t), each taking a slice of the row (so a thread
 // usually has a single vector): the slice is read once and written once per
@@ -29,7 +48,7 @@ constexpr int kMaxRowsPerBlock = 64;
 // and no scatter follows.  FENCED (unordered fabric, PUSH only): device-scope
 // stores, and the block adds the 16-byte units it wrote to
 // arrive[destination][source] itself once they are acknowledged; stream-ordered
-// with PUSH, transfer_done_kernel announces the transfers after this kernel.
+// with PUSH, the sender's first block announces the whole transfers.
 template <bool PUSH, bool FENCED>
 __global__ __launch_bounds__(kPackThreads) void dispatch_pack_kernel(
     Dims D, Tables W, int rank_begin, const char *__restrict__ x,
@@ -134,6 +153,9 @@ __global__ __launch_bounds__(kPackThreads) void dispatch_pack_kernel(
         if (tid < K && my_row >= 0 && units > 0)
             add_counter(W.arrive_disp + (size_t)my_d * D.N + s, units);
     }
+    if (PUSH && !FENCED && blockIdx.x == 0)    // stream-ordered: the sender's first block announces
+        announce_transfers(W.send_off + (size_t)s * (D.N + 1), W.arrive_disp, (unsigned)(D.Bw / 16), s, D.N,
+                           tid, kPackThreads);
 }
 
 // ------------------------------------------------------------------ dispatch: pack with e4m3 quantisation
@@ -269,6 +291,9 @@ __global__ __launch_bounds__(kQuantThreads) void dispatch_pack_e4m3_kernel(
             add_counter(W.arrive_disp + (size_t)my_d * D.N + s,
                         (unsigned)(n_live * 8 + (n_live + 3) / 4 + (slice == 0 ? pad_units : 0)));
     }
+    if (PUSH && !FENCED && blockIdx.x == 0)
+        announce_transfers(W.send_off + (size_t)s * (D.N + 1), W.arrive_disp, (unsigned)(D.Bw / 16), s, D.N,
+                           tid, kQuantThreads);
 }
 
 // ------------------------------------------------------------------ fabric copy
@@ -284,7 +309,7 @@ __global__ __launch_bounds__(kQuantThreads) void dispatch_pack_e4m3_kernel(
 // waits for: the counters only ever say "this much of source s's payload has
 // landed", in whatever order waves finish.  In stream-ordered mode nobody may
 // look before the kernel has ended, and one wave per sender announces each whole
-// transfer (fabric_announce).
+// transfer (announce_transfers).
 struct FabricArgs {
     const char *src_base; long long src_rank_stride;
     char *dst_base;       long long dst_rank_stride;
@@ -297,24 +322,8 @@ struct FabricArgs {
     long long row_bytes;
     int waves_per_row;    // 1..16
     int dst_row_lo;       // rows whose target row is below this belong to the private-slot scatter
-    int announce;         // stream-ordered mode: this launch also advances arrive[.][s] (see fabric_announce)
+    int announce;         // stream-ordered mode: this launch also advances arrive[.][s] (announce_transfers)
 };
-
-// Stream-ordered mode: one add per (sender, receiver) announces the whole
-// transfer, like the single immediate a NIC delivers after a WRITE (section
-// TransferEngine, ImmCounter).  It is issued by one wave per sender inside the
-// last copy kernel of the call: receivers are ordered after that kernel by the
-// stream, so they find counters and payload complete together, and no extra
-// launch is spent.  (Per-wave announcements, as in unordered mode, cost more than
-// they give here: adds to one counter from many compute dies serialise at about
-// 0.2 us each, which made skewed routing several times slower.)
-__device__ inline void fabric_announce(const FabricArgs &A, int s, int N, int lane) {
-    const unsigned units = (unsigned)(A.row_bytes / 16);
-    for (int p = lane; p < N; p += kWave) {
-        const int rows = A.seg_off[(size_t)s * (N + 1) + p + 1] - A.seg_off[(size_t)s * (N + 1) + p];
-        if (rows) add_counter(A.arrive + (size_t)p * N + s, (unsigned)rows * units);
-    }
-}
 
 // One wave's share of one row: slice `sub` of `G` (vectors v with (v / 64) % G ==
 // sub), the sidecar when it is slice 0, and in unordered mode the count of
@@ -344,7 +353,7 @@ __device__ inline void fabric_send_row(const Dims &D, const FabricArgs &A, int s
         v4u *md = (v4u *)(A.dst_meta + (size_t)dst_rank * A.dst_meta_rank_stride) + (size_t)dst_row * mv;
         if (lane < mv) st_payload<FENCED, STREAMING>(md + lane, ms[lane]);
     }
-    if (FENCED) {          // stream-ordered launches announce whole transfers instead (fabric_announce)
+    if (FENCED) {          // stream-ordered launches announce whole transfers instead (announce_transfers)
         const int full = nvec / step, rem = nvec - full * step;
         const int mine = full * kWave + min(max(rem - sub * kWave, 0), kWave);
         stores_done<FENCED>();
@@ -374,7 +383,8 @@ __global__ __launch_bounds__(kCopyThreads) void fabric_copy_kernel(Dims D, Table
         i += row_stride;
         if (i < total) t = A.row_dst[(size_t)s * A.row_cap + i];
     }
-    if (!FENCED && A.announce && wave == 0 && ok) fabric_announce(A, s, N, lane);
+    if (!FENCED && A.announce && wave == 0 && ok)
+        announce_transfers(A.seg_off + (size_t)s * (N + 1), A.arrive, (unsigned)(A.row_bytes / 16), s, N, lane, kWave);
 }
 
 // First scatter of a dispatch with private slots (section Dispatch: tokens up to
@@ -397,26 +407,8 @@ __global__ __launch_bounds__(kCopyThreads) void fabric_private_kernel(Dims D, Ta
         const int lo = A.seg_off[(size_t)s * (N + 1) + d], hi = A.seg_off[(size_t)s * (N + 1) + d + 1];
         if (i < hi - lo) fabric_send_row<FENCED, STREAMING>(D, A, s, lo + i, d, s * P + i, sub, lane);
     }
-    if (!FENCED && A.announce && wave == 0) fabric_announce(A, s, N, lane);
-}
-
-// ------------------------------------------------------------------ completion of whole transfers
-// Stream-ordered peer push: no copy kernel runs, so the announcement of
-// fabric_announce gets a launch of its own, right after the pack kernel that
-// stored the payload of ranks [rank_begin, ...) into the peers' buffers: lane = peer.
-__global__ __launch_bounds__(kWave) void transfer_done_kernel(Dims D, Tables W, int rank_begin,
-                                                              int combine) {
-    const int r = rank_begin + blockIdx.x, N = D.N;
-    const int *off = (combine == 2 ? W.recv_off : combine ? W.cs_off : W.send_off) + (size_t)r * (N + 1);
-    unsigned *arrive = combine ? W.arrive_comb : W.arrive_disp;
-    const unsigned units = (unsigned)((combine ? D.Bc : D.Bw) / 16);
-    const int ok = W.plan_ok[r];               // all three loads are issued together
-    for (int p = threadIdx.x; p < N; p += kWave) {
-        // dispatch: r sent M[r][p] rows to p; combine: r replied to p with every row of
-        // r's experts that came from p, or (2, partial sums) one share per row p sent to r
-        const int rows = off[p + 1] - off[p];
-        if (ok && rows) add_counter(arrive + (size_t)p * N + r, (unsigned)rows * units);
-    }
+    if (!FENCED && A.announce && wave == 0)
+        announce_transfers(A.seg_off + (size_t)s * (N + 1), A.arrive, (unsigned)(A.row_bytes / 16), s, N, lane, kWave);
 }
 
 // ------------------------------------------------------------------ dispatch: unpack
@@ -567,6 +559,8 @@ __global__ __launch_bounds__(kCopyThreads) void combine_pack_kernel(
     if (tid <= N) off[tid] = W.cs_off[(size_t)d * (N + 1) + tid];
     __syncthreads();
     const int nvec = (int)(D.Bc / 16);
+    if (PUSH && !FENCED && blockIdx.x == 0)
+        announce_transfers(off, W.arrive_comb, (unsigned)nvec, d, N, tid, kCopyThreads);
     const char *yd = expert_y + (size_t)d * D.expert_cap * D.Bc;
     // capacities are upper bounds, so the grid may be smaller than the rows in use
     for (int q0 = blockIdx.x * rows_per_block; q0 < total; q0 += gridDim.x * rows_per_block) {
@@ -638,6 +632,8 @@ __global__ __launch_bounds__(kCopyThreads) void combine_partial_pack_kernel(
     if (tid <= N) off[tid] = W.recv_off[(size_t)d * (N + 1) + tid];
     __syncthreads();
     const int nvec = (int)(D.Bc / 16);
+    if (PUSH && !FENCED && blockIdx.x == 0)
+        announce_transfers(off, W.arrive_comb, (unsigned)nvec, d, N, tid, kCopyThreads);
     const char *yd = expert_y + (size_t)d * D.expert_cap * D.Bc;
     for (int r0 = blockIdx.x * rows_per_block; r0 < total; r0 += gridDim.x * rows_per_block) {
         const int r1 = min(r0 + rows_per_block, total);

@@ -20,7 +20,7 @@ FL_FLAG_ZERO_PAD = 1
 FL_FLAG_UNORDERED_FABRIC = 2
 FL_FLAG_PEER_PUSH = 4
 FL_FLAG_PARTIAL_SUMS = 8
-FL_KERNEL_COUNT = 11
+FL_KERNEL_COUNT = 10
 
 
 class fl_moe_config(C.Structure):

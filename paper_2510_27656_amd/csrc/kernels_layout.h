@@ -121,6 +121,27 @@ __device__ __forceinline__ void route_count_block(const Dims &D, const Tables &W
         W.comb_off[(size_t)s * (N + 1) + N] = pairs_total;
     }
 
+    // Everything a peer needs is known now (pass 1 saw every index, so `bad` is final):
+    // the record goes out before pass 2, whose per-pair tables only this rank's later
+    // kernels read, so the peers' planning overlaps with it.
+    const int valid = bad ? 0 : 1;
+    if (bad && tid == 0) latch_status(W.status, FL_STATUS_BAD_INDEX);
+
+    // Route exchange: push this rank's record (C | M | comb_off | valid, all still in
+    // LDS) into every peer's table, then notify.
+    const int RL = D.route_len;
+    for (int i = tid; i < N * RL; i += kRouteThreads) {
+        const int peer = i / RL, f = i - peer * RL;
+        int v;
+        if (f < E + N) v = total_hits[f];
+        else if (f < E + 2 * N) v = start[(f - E - N) * El];
+        else v = valid;
+        st_word<true>(&W.routes[((size_t)peer * N + s) * RL + f], v);
+    }
+    stores_done<true>();
+    __syncthreads();
+    if (tid < N) add_counter(W.arrive_route + (size_t)tid * N + s, 1u);
+
     // pass 2: final position of every pair
     for (int tile = 0; tile < ntiles; ++tile) {
         const int t0 = tile * D.TT, nt = min(D.TT, Ts - t0);
@@ -154,24 +175,6 @@ __device__ __forceinline__ void route_count_block(const Dims &D, const Tables &W
             __syncthreads();
         }
     }
-    __syncthreads();
-    const int valid = bad ? 0 : 1;
-    if (bad && tid == 0) latch_status(W.status, FL_STATUS_BAD_INDEX);
-
-    // Route exchange: push this rank's record (C | M | comb_off | valid, all still in
-    // LDS) into every peer's table, then notify.
-    const int RL = D.route_len;
-    for (int i = tid; i < N * RL; i += kRouteThreads) {
-        const int peer = i / RL, f = i - peer * RL;
-        int v;
-        if (f < E + N) v = total_hits[f];
-        else if (f < E + 2 * N) v = start[(f - E - N) * El];
-        else v = valid;
-        st_word<true>(&W.routes[((size_t)peer * N + s) * RL + f], v);
-    }
-    stores_done<true>();
-    __syncthreads();
-    if (tid < N) add_counter(W.arrive_route + (size_t)tid * N + s, 1u);
 }
 
 __host__ __device__ inline size_t route_plan_lds_bytes(int E, int N, int El) {

@@ -159,11 +159,15 @@ __device__ __forceinline__ void route_count_block(const Dims &D, const Tables &W
                 base[re] + pre[(size_t)re * Wd + w] + __popc(bits[(size_t)re * Wd + w] & below);
             const int rank_d =
                 base[rd] + pre[(size_t)rd * Wd + w] + __popc(bits[(size_t)rd * Wd + w] & below);
-            bool first = true;                             // first slot of this token bound for rank d?
-            for (int k2 = 0; k2 < k; ++k2) {
-                const int e2 = idx_s[g - k + k2];
-                if (e2 >= 0 && e2 < E && e2 / El == d) first = false;
-            }
+            // first slot of this token bound for rank d?  The token's earlier ids are fetched
+            // together (predicated, independent loads) rather than one per loop turn.
+            int before[FL_MAX_TOPK];
+#pragma unroll
+            for (int k2 = 0; k2 < FL_MAX_TOPK; ++k2) before[k2] = k2 < k ? idx_s[g - k + k2] : -1;
+            bool first = true;
+#pragma unroll
+            for (int k2 = 0; k2 < FL_MAX_TOPK; ++k2)
+                if (before[k2] >= 0 && before[k2] < E && before[k2] / El == d) first = false;
             const size_t o = (size_t)s * D.T * K + g;
             W.comb_pos[o] = start[re] + rank_e;
             W.pair_meta[o] = ((unsigned)(e - d * El) << 24) | (unsigned)rank_e;

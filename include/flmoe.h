@@ -78,8 +78,9 @@ extern "C" {
  * counters are then checked with relaxed atomics and no cache maintenance, and
  * advanced once per (sender, receiver) transfer by the kernel that copies the
  * payload (its end, in stream order, is what makes payload and counters visible
- * to the receivers), as a NIC delivers one immediate after a whole WRITE.  With it, send and receive kernels may overlap in time (other
- * streams, other orders): a sender writes its payload through to memory
+ * to the receivers), as a NIC delivers one immediate after a whole WRITE.
+ * With it, send and receive kernels may overlap in time (other streams, other
+ * orders): a sender writes its payload through to memory
  * (device-scope stores) and waits for the acknowledgement before it reports
  * progress (every wave adds what it delivered, so a receiver sees a source's
  * range complete as early as possible), and a receiver invalidates its caches
@@ -92,8 +93,8 @@ extern "C" {
  * simulated ranks live on one GPU).  The send calls then write each row and its
  * sidecar straight into the destination's receive buffer: no send buffer is
  * filled and no scatter kernel runs; the arrival counters advance as in the
- * staged path (after the kernel, or per workgroup with
- * FL_FLAG_UNORDERED_FABRIC).  Receivers, counters, capacities and every result
+ * staged path (once per transfer inside the kernel that stores the payload, or
+ * per workgroup with FL_FLAG_UNORDERED_FABRIC).  Receivers, counters, capacities and every result
  * are unchanged; only the bytes moved per step shrink (one write per sent row
  * instead of write + read + write).  Combines with the other flags and
  * max_private_rows. */

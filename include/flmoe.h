@@ -60,6 +60,8 @@ extern "C" {
 #define FL_ERR_ALIGNMENT (-2)
 #define FL_ERR_WORKSPACE (-3)
 #define FL_ERR_HIP (-4)
+#define FL_ERR_STATIC_LIMIT (-5) /* fl_moe_layout_static: the configuration needs more scratch
+                                    than FL_STATIC_SCRATCH_BYTES                             */
 
 /* bits of the device status word */
 #define FL_STATUS_BAD_INDEX 1 /* expert id outside [0,E) or repeated inside a token */
@@ -221,6 +223,40 @@ int fl_moe_destroy(fl_moe_ctx *ctx);
  * `view` (host, may be NULL) receives pointers to the resulting tables. */
 int fl_moe_layout(fl_moe_ctx *ctx, int rank_begin, int rank_count, const int32_t *indices,
                   const int32_t *num_tokens, fl_moe_layout_view *view /*host*/, void *stream);
+
+/* fl_moe_layout for callers that cannot allocate device memory or hold a context:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  It needs no fl_moe_ctx and no workspace: the route records, message
+ * counters and per-pair tables that fl_moe_layout keeps in the caller's workspace
+ * live in an array of FL_STATIC_SCRATCH_BYTES bytes inside the library's device
+ * image (every GPU the library runs on holds one copy until the process ends),
+ * and the call itself allocates nothing (no hipMalloc / hipFree, no events, no host
+ * allocation).  It acts for all cfg->n_ranks ranks in one launch and writes the
+ * same tables, with the same contents, that fl_moe_layout's view points to, into
+ * the caller's buffers:
+ *   counts [N][E], dedup_counts [N][N], tokens_per_expert [N][E/N],
+ *   send_off [N][N+1], recv_off [N][N+1], expert_off [N][E/N+1], comb_off [N][N+1],
+ *   comb_pos [N][T][K], plan_ok [N], status [1] (the FL_STATUS_* bits of THIS call;
+ *   0 when the step is valid) - all int32 device pointers, 4-byte aligned, non-NULL.
+ * Capacities, expert_align, max_private_rows and the flags of cfg are honoured
+ * as in fl_moe_layout (capacity overflow and bad expert ids clear plan_ok on every
+ * rank and set the status bits).  Returns FL_ERR_STATIC_LIMIT, and enqueues
+ * nothing, when the configuration's tables do not fit the array (it holds the
+ * 32-rank, 256-expert, top-8 shape up to about 3000 tokens per rank).  The call
+ * only enqueues kernels on `stream`; the scratch is cleared by a kernel of the
+ * call, not by a memset.  The first call on each device looks up the array's
+ * address (hipGetSymbolAddress); make that call outside graph capture.
+ * Every call on one GPU uses that GPU's one array: calls that overlap in time on
+ * the same GPU (different streams, or a graph replay racing an eager call) race
+ * and give undefined tables; calls on one stream, or ordered by events, are fine. */
+#define FL_STATIC_SCRATCH_BYTES (8u << 20)
+typedef struct fl_moe_layout_out {
+    int32_t *counts, *dedup_counts, *tokens_per_expert, *send_off, *recv_off, *expert_off,
+        *comb_off, *comb_pos, *plan_ok, *status;
+} fl_moe_layout_out;
+int fl_moe_layout_static(const fl_moe_config *cfg /*host*/, const int32_t *indices,
+                         const int32_t *num_tokens, const fl_moe_layout_out *out /*host*/,
+                         void *stream);
 
 /* Step 2 (section Dispatch: tokens are copied into send buffers, a contiguous
  * source per peer, then scattered).  x [N][T][H] bf16; all T rows of a rank

@@ -4,6 +4,7 @@
 
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 
 #include "../../include/flmoe.h"
@@ -12,6 +13,11 @@
 #include "kernels_shuffle.h"
 
 using namespace flmoe;
+
+// Scratch of fl_moe_layout_static, part of the device image: every GPU the library
+// is loaded on holds its own copy at its own address.  In host code this name is
+// only a handle for hipGetSymbolAddress, never a device address.
+static __device__ __align__(256) unsigned char scratch[FL_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -294,6 +300,57 @@ int for_rank_groups(const fl_moe_ctx *ctx, int rb, int rc, F f) {
     return FL_OK;
 }
 
+// ---------------------------------------------------------------- static scratch
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void *g_scratch_ptr[kMaxDevices];          // device address of `scratch` on each GPU, looked up once
+
+// Address of the current device's copy of `scratch`.
+int static_scratch(void **ptr) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return FL_ERR_HIP;
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return FL_ERR_HIP;
+        g_scratch_ptr[dev] = p;
+    }
+    *ptr = g_scratch_ptr[dev];
+    return FL_OK;
+}
+
+// What route_layout_kernel keeps outside the caller-visible tables, carved from
+// `base` (nullptr: measure only).  The counters come first, in one run of
+// *clear_words 32-bit words at `base` that every call clears.  Returns the bytes needed.
+size_t carve_static(const Dims &D, void *base, Tables *W, size_t *clear_words) {
+    Carver c(base);
+    const size_t N = D.N, El = D.El, T = D.T, K = D.K;
+    W->epoch_route = c.take<unsigned>(N);
+    W->arrive_route = c.take<unsigned>(N * N);
+    W->expect_disp = c.take<unsigned>(N * N);
+    W->expect_comb = c.take<unsigned>(N * N);
+    *clear_words = align_up(c.cur, 256) / sizeof(unsigned);
+    W->routes = c.take<int>(N * N * D.route_len);
+    W->recv_shared_off = c.take<int>(N * N);
+    W->dst_off = c.take<int>(N * N);
+    W->comb_dst_off = c.take<int>(N * N);
+    W->ret_off = c.take<int>(N * N);
+    W->base_x = c.take<int>(N * El * N);
+    W->cs_base = c.take<int>(N * N * El);
+    W->cs_off = c.take<int>(N * (N + 1));
+    W->send_row = c.take<int>(N * T * K);
+    W->pair_meta = c.take<unsigned>(N * T * K);
+    return align_up(c.cur, 256);
+}
+
+// Zeroes the counters of the static scratch and the caller's status word (a kernel,
+// not a memset node: the call may be captured in a HIP graph).
+__global__ void clear_words_kernel(unsigned *words, size_t n, int *status) {
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) words[i] = 0u;
+    if (i == 0) *status = 0;
+}
+
 }  // namespace
 
 extern "C" {
@@ -402,6 +459,44 @@ int fl_moe_layout(fl_moe_ctx *ctx, int rb, int rc, const int32_t *indices,
         view->send_off = W.send_off; view->recv_off = W.recv_off; view->expert_off = W.expert_off;
         view->comb_off = W.comb_off; view->comb_pos = W.comb_pos; view->plan_ok = W.plan_ok;
     }
+    return launch_status();
+}
+
+int fl_moe_layout_static(const fl_moe_config *cfg, const int32_t *indices, const int32_t *num_tokens,
+                         const fl_moe_layout_out *out, void *stream) {
+    if (!cfg || !indices || !num_tokens || !out) return FL_ERR_INVALID_ARG;
+    int32_t *const outs[] = {out->counts, out->dedup_counts, out->tokens_per_expert, out->send_off,
+                             out->recv_off, out->expert_off, out->comb_off, out->comb_pos,
+                             out->plan_ok, out->status};
+    for (int32_t *p : outs) {
+        if (!p) return FL_ERR_INVALID_ARG;
+        if ((uintptr_t)p & 3) return FL_ERR_ALIGNMENT;
+    }
+    if (((uintptr_t)indices & 3) || ((uintptr_t)num_tokens & 3)) return FL_ERR_ALIGNMENT;
+    Dims D;
+    int e = resolve(cfg, &D);
+    if (e != FL_OK) return e;
+    Tables W;
+    memset(&W, 0, sizeof(W));
+    size_t clear_words = 0;
+    if (carve_static(D, nullptr, &W, &clear_words) > FL_STATIC_SCRATCH_BYTES) return FL_ERR_STATIC_LIMIT;
+    void *ptr = nullptr;
+    e = static_scratch(&ptr);
+    if (e != FL_OK) return e;
+    carve_static(D, ptr, &W, &clear_words);
+    W.C = out->counts; W.M = out->dedup_counts; W.G = out->tokens_per_expert;
+    W.send_off = out->send_off; W.recv_off = out->recv_off; W.expert_off = out->expert_off;
+    W.comb_off = out->comb_off; W.comb_pos = out->comb_pos; W.plan_ok = out->plan_ok;
+    W.status = out->status;
+    hipStream_t st = (hipStream_t)stream;
+    // The array keeps what the last call left (possibly of another shape): the message
+    // counters and epochs must start at zero, everything else is written before it is read.
+    clear_words_kernel<<<dim3((unsigned)((clear_words + 255) / 256)), dim3(256), 0, st>>>(
+        (unsigned *)ptr, clear_words, W.status);
+    const size_t lds_count = route_count_lds_bytes(D.E, D.N, D.TT);
+    const size_t lds_plan = route_plan_lds_bytes(D.E, D.N, D.El);
+    route_layout_kernel<<<dim3(2 * D.N), dim3(kRouteThreads), lds_count > lds_plan ? lds_count : lds_plan, st>>>(
+        D, W, 0, D.N, indices, num_tokens);
     return launch_status();
 }
 
@@ -687,6 +782,8 @@ const char *fl_moe_strerror(int code) {
         case FL_ERR_ALIGNMENT: return "pointer or size not aligned as required";
         case FL_ERR_WORKSPACE: return "workspace too small";
         case FL_ERR_HIP: return "HIP runtime error";
+        case FL_ERR_STATIC_LIMIT:
+            return "configuration needs more scratch than the library's static array (FL_STATIC_SCRATCH_BYTES)";
         default: return "unknown error";
     }
 }

@@ -14,6 +14,8 @@ from . import build as _build
 
 FL_OK = 0
 FL_ERR_INVALID_ARG, FL_ERR_ALIGNMENT, FL_ERR_WORKSPACE, FL_ERR_HIP = -1, -2, -3, -4
+FL_ERR_STATIC_LIMIT = -5
+FL_STATIC_SCRATCH_BYTES = 8 << 20
 FL_STATUS_BAD_INDEX, FL_STATUS_CAPACITY, FL_STATUS_TIMEOUT = 1, 2, 4
 FL_DTYPE_BF16, FL_DTYPE_E4M3_BLOCK128 = 0, 1
 FL_FLAG_ZERO_PAD = 1
@@ -47,6 +49,14 @@ class fl_moe_layout_view(C.Structure):
                  "expert_off", "comb_off", "comb_pos", "plan_ok")]
 
 
+LAYOUT_OUT_FIELDS = ("counts", "dedup_counts", "tokens_per_expert", "send_off", "recv_off",
+                     "expert_off", "comb_off", "comb_pos", "plan_ok", "status")
+
+
+class fl_moe_layout_out(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in LAYOUT_OUT_FIELDS]
+
+
 class fl_moe_debug_view(C.Structure):
     _fields_ = [("buf_a", C.c_void_p), ("buf_b", C.c_void_p),
                 ("buf_a_rank_bytes", C.c_int64), ("buf_b_rank_bytes", C.c_int64),
@@ -56,6 +66,7 @@ class fl_moe_debug_view(C.Structure):
 
 
 EXPORTS = ["fl_moe_query_sizes", "fl_moe_create", "fl_moe_destroy", "fl_moe_layout",
+           "fl_moe_layout_static",
            "fl_moe_dispatch_send", "fl_moe_dispatch_send_weighted", "fl_moe_dispatch_send_e4m3",
            "fl_moe_dispatch_recv",
            "fl_moe_combine_send",
@@ -79,6 +90,8 @@ def lib():
         L.fl_moe_create.argtypes = [C.POINTER(fl_moe_config), vp, C.c_size_t, C.POINTER(vp)]
         L.fl_moe_destroy.argtypes = [vp]
         L.fl_moe_layout.argtypes = [vp, i32, i32, vp, vp, C.POINTER(fl_moe_layout_view), vp]
+        L.fl_moe_layout_static.argtypes = [C.POINTER(fl_moe_config), vp, vp,
+                                           C.POINTER(fl_moe_layout_out), vp]
         L.fl_moe_dispatch_send.argtypes = [vp, i32, i32, vp, vp]
         L.fl_moe_dispatch_send_weighted.argtypes = [vp, i32, i32, vp, vp, vp]
         L.fl_moe_dispatch_send_e4m3.argtypes = [vp, i32, i32, vp, vp, vp, vp]
@@ -151,6 +164,13 @@ def fl_moe_layout(ctx, rank_begin, rank_count, indices, num_tokens, stream=None)
     _check(lib().fl_moe_layout(ctx, rank_begin, rank_count, _ptr(indices), _ptr(num_tokens),
                                C.byref(view), _stream(stream)), "fl_moe_layout")
     return view
+
+
+def fl_moe_layout_static(cfg: fl_moe_config, indices, num_tokens, out: dict, stream=None):
+    """out: int32 device tensors by the field names of fl_moe_layout_out (caller-owned)."""
+    o = fl_moe_layout_out(*[_ptr(out[n]) for n in LAYOUT_OUT_FIELDS])
+    _check(lib().fl_moe_layout_static(C.byref(cfg), _ptr(indices), _ptr(num_tokens), C.byref(o),
+                                      _stream(stream)), "fl_moe_layout_static")
 
 
 def fl_moe_dispatch_send(ctx, rank_begin, rank_count, x, stream=None):

@@ -341,7 +341,13 @@ void orc_comb_pos(int N, int E, int Tmax, int K, const int32_t *num_tokens,
  * with bias 7, 3 mantissa bits, largest finite 448, no infinities, subnormals
  * down to 2^-9.  Rule per 128-element block: amax = max |x|; scale = amax/448
  * (fp32 division; scale = 1 when amax = 0); q = e4m3(x / scale) rounded to
- * nearest, ties to even, saturating at +-448. ---------- */
+ * nearest, ties to even, saturating at +-448.
+ * Non-finite inputs, a reading (the paper dispatches ready-made fp8 and says
+ * nothing): a NaN element is skipped by the maximum (a > amax is false) and
+ * becomes the NaN code with its own sign, the rest of its block is quantised
+ * as if it were absent; an infinite element makes amax and the scale +Inf, so
+ * every finite element of that block becomes a signed zero (x / Inf) and every
+ * infinite one the NaN code with its sign; a block of NaNs only has scale 1. ---------- */
 
 float orc_e4m3_decode(uint8_t c) {
     int sign = c >> 7, ex = (c >> 3) & 0xf, man = c & 7;
@@ -399,9 +405,19 @@ void orc_quant_e4m3_block128(int64_t rows, int H, const uint16_t *x, uint8_t *q,
             }
             float scale = (amax == 0.0f) ? 1.0f : amax / 448.0f;
             scales[(size_t)r * nb + b] = scale;
-            for (int i = 0; i < 128; ++i)
-                q[(size_t)r * H + (size_t)b * 128 + i] =
-                    orc_e4m3_encode(bf16_to_f32(xb[i]) / scale);
+            for (int i = 0; i < 128; ++i) {
+                float v = bf16_to_f32(xb[i]);
+                uint8_t code;
+                if (isnan(v) || isinf(v))
+                    /* Non-finite input (the paper is silent): the rule above applied in
+                     * IEEE arithmetic gives NaN here (NaN / scale, or Inf / Inf since an
+                     * Inf makes amax and the scale infinite); the NaN code takes the
+                     * sign of the INPUT element, which IEEE leaves open for Inf / Inf. */
+                    code = (uint8_t)((xb[i] >> 8) & 0x80) | 0x7f;
+                else
+                    code = orc_e4m3_encode(v / scale);
+                q[(size_t)r * H + (size_t)b * 128 + i] = code;
+            }
         }
 }
 

@@ -117,6 +117,56 @@ def test_count_invariants(case):
     assert (lay.expert_off[:, -1] <= N * T * min(K, El)).all()
 
 
+def dedup_counts_by_sets(N, E, num_tokens, indices):
+    """M[s][d] as the definition reads: the number of tokens of s with any expert on d."""
+    El = E // N
+    M = np.zeros((N, N), np.int64)
+    for s in range(N):
+        for d in range(N):
+            M[s, d] = len({t for t in range(int(num_tokens[s]))
+                           if any(int(e) // El == d for e in indices[s, t])})
+    return M
+
+
+@pytest.mark.parametrize("case", CASES + [dict(N=4, E=32, T=300, K=8, H=8, seed=6, ragged=True),
+                                          dict(N=16, E=16, T=40, K=16, H=8, seed=7)])
+def test_dedup_counts_equal_the_set_definition(case):
+    """Every entry of M against a Python set per (source, destination rank); the routed
+    tokens include ones with several experts on one rank (the case de-duplication is for)."""
+    inp = small_case(**case)
+    N, E, K = case["N"], case["E"], case["K"]
+    lay = orc.layout(N, E, K, inp.num_tokens, inp.indices)
+    want = dedup_counts_by_sets(N, E, inp.num_tokens, inp.indices)
+    assert (lay.M == want).all()
+    if K > 1 and E // N > 1:
+        pairs_per_rank = lay.C.reshape(N, N, E // N).sum(2)
+        assert (lay.M < pairs_per_rank).any(), "no token had two experts on one rank: weak case"
+    # rows of absent tokens never count: the same indices with fewer tokens
+    fewer = np.maximum(inp.num_tokens - 3, 0).astype(np.int32)
+    lay2 = orc.layout(N, E, K, fewer, inp.indices)
+    assert (lay2.M == dedup_counts_by_sets(N, E, fewer, inp.indices)).all()
+
+
+@pytest.mark.parametrize("name", ["tiny", "dsv3_decode", "dsv3_prefill", "qwen3_skew", "dsv3_fp8"])
+def test_workload_description_counts_the_oracles_dedup_rows(name):
+    """workloads.describe() feeds the bench's byte counts; its D (counted by sorting owner
+    ranks per token) must be the oracle's sum of M, and its pair count the sum of C."""
+    inp = wlmod.make_inputs(wlmod.WORKLOADS[name], with_x=False)
+    wl = inp.wl
+    L = orc.lib()
+    M = np.empty((wl.n_ranks, wl.n_ranks), np.int32)
+    Cc = np.empty((wl.n_ranks, wl.n_experts), np.int32)
+    L.orc_dedup_counts(wl.n_ranks, wl.n_experts, wl.tokens, wl.top_k, orc._p(inp.num_tokens),
+                       orc._p(inp.indices), orc._p(M))
+    L.orc_counts(wl.n_ranks, wl.n_experts, wl.tokens, wl.top_k, orc._p(inp.num_tokens),
+                 orc._p(inp.indices), orc._p(Cc))
+    d = wlmod.describe(inp)
+    assert d["dedup_rows"] == int(M.astype(np.int64).sum())
+    assert d["pairs"] == int(Cc.astype(np.int64).sum())
+    assert d["tokens_total"] == int(inp.num_tokens.sum())
+    assert d["max_rank_rows"] == int(Cc.astype(np.int64).reshape(wl.n_ranks, wl.n_ranks, -1).sum((0, 2)).max())
+
+
 @pytest.mark.parametrize("align", [1, 4, 16])
 @pytest.mark.parametrize("case", CASES)
 def test_layout_matches_brute_force_sort(case, align):
@@ -162,6 +212,10 @@ def test_exhaustive_two_ranks_two_tokens():
     for combo in itertools.product(choices, repeat=N * T):
         idx = np.array(combo, np.int32).reshape(N, T, K)
         lay = orc.layout(N, E, K, nt, idx)
+        # de-duplicated counts: a token counts once per rank that hosts any of its experts
+        for s in range(N):
+            for d in range(N):
+                assert lay.M[s, d] == len({t for t in range(T) if d in (idx[s, t, 0] // 2, idx[s, t, 1] // 2)})
         # brute force, written inline: position = number of pairs with a smaller key
         for s in range(N):
             for t in range(T):
@@ -637,6 +691,45 @@ def test_block_quantisation_invariants():
     # dequantise: bf16(float(q) * scale) against a library rounding
     y = orc.dequant_e4m3_block128(q, sc)
     assert (y == f32_to_bf16_torch((qv * sc[..., None]).astype(np.float32)).reshape(6, H)).all()
+
+
+def test_block_quantisation_of_inf_and_nan_follows_the_stated_reading():
+    """Expected bytes and scales written out by hand from the reading: NaN is skipped by
+    the maximum and becomes 0x7f | its sign; Inf makes the scale +Inf, finite neighbours
+    +-0 and itself 0x7f | its sign; the other blocks of the row are untouched."""
+    to_bits = f32_to_bf16_torch
+    x = np.zeros((1, 128 * 6), np.uint16)
+    base = to_bits(np.linspace(-3.0, 4.0, 128).astype(np.float32))     # amax = 4 exactly, at [127]
+    for b in range(6):
+        x[0, b * 128:(b + 1) * 128] = base
+    blk = lambda b: x[0, b * 128:(b + 1) * 128]
+    blk(1)[3] = 0x7fc0; blk(1)[100] = 0xffc0; blk(1)[50] = 0x7f81      # +qNaN, -qNaN, +sNaN
+    blk(2)[10] = 0x7f80                                                # +Inf
+    blk(3)[20] = 0xff80; blk(3)[21] = 0x7fc0                           # -Inf and a NaN
+    blk(4)[:] = 0xffc0                                                 # NaNs only
+    blk(5)[:] = 0; blk(5)[7] = 0x7fc0                                  # zeros and one NaN
+    q, sc = orc.quant_e4m3_block128(x)
+    clean_q, clean_sc = orc.quant_e4m3_block128(np.ascontiguousarray(base.reshape(1, 128)))
+    assert clean_sc[0, 0] == np.float32(4.0) / np.float32(448.0)
+    qb = lambda b: q[0, b * 128:(b + 1) * 128]
+    # block 0: no special value
+    assert (qb(0) == clean_q[0]).all() and sc[0, 0] == clean_sc[0, 0]
+    # block 1: NaNs skipped by the maximum, NaN codes with the element's sign, rest unchanged
+    want = clean_q[0].copy(); want[3] = 0x7f; want[100] = 0xff; want[50] = 0x7f
+    assert sc[0, 1] == clean_sc[0, 0] and (qb(1) == want).all()
+    # block 2: scale +Inf, finite values become zeros with their sign
+    signs = (base >> 8) & 0x80
+    want = signs.astype(np.uint8); want[10] = 0x7f
+    assert np.isposinf(sc[0, 2]) and (qb(2) == want).all()
+    want = signs.astype(np.uint8); want[20] = 0xff; want[21] = 0x7f
+    assert np.isposinf(sc[0, 3]) and (qb(3) == want).all()
+    assert sc[0, 4] == 1.0 and (qb(4) == 0xff).all()
+    want = np.zeros(128, np.uint8); want[7] = 0x7f
+    assert sc[0, 5] == 1.0 and (qb(5) == want).all()
+    # the library's own conversion agrees on what a NaN becomes (code 0x7f with the sign)
+    if hasattr(torch, "float8_e4m3fn"):
+        t = torch.tensor([float("nan"), -float("nan")]).to(torch.float8_e4m3fn).view(torch.uint8)
+        assert (t & 0x7f).tolist() == [0x7f, 0x7f]
 
 
 def test_named_workloads_match_their_description():

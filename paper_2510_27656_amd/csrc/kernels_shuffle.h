@@ -170,8 +170,8 @@ __global__ __launch_bounds__(kPackThreads) void dispatch_pack_kernel(
 // Four quotients to four e4m3 bytes with the part's own converter (OCP E4M3 on
 // gfx950, round to nearest even, subnormals included; checked against the oracle's
 // arithmetic encoder on every finite bf16 input under several block maxima).  A quotient can exceed 448
-// by one fp32 step (both divisions round), so magnitudes are held at 448 first;
-// NaN passes through the comparison and converts to a NaN code.
+// by one fp32 step (both divisions round), so magnitudes are held at 448 first.
+// The block maximum skips NaN elements (an ordered comparison, as in the rule's plain reading).
 __device__ inline float e4m3_hold(float v) {
     return fabsf(v) >= 448.0f ? copysignf(448.0f, v) : v;
 }
@@ -179,6 +179,22 @@ __device__ inline unsigned e4m3_pack4(float a, float b, float c, float d) {
     int w = __builtin_amdgcn_cvt_pk_fp8_f32(e4m3_hold(a), e4m3_hold(b), 0, false);
     w = __builtin_amdgcn_cvt_pk_fp8_f32(e4m3_hold(c), e4m3_hold(d), w, true);
     return (unsigned)w;
+}
+// Non-finite inputs (Inf or NaN, exponent bits all ones): the quotient is NaN either
+// way (NaN / scale; Inf / Inf, because an Inf makes the block's scale infinite) and the
+// code is the NaN code 0x7f with the sign of the INPUT element, which IEEE leaves
+// open for Inf / Inf and the converter for NaN.  lo16 / hi16: the two bf16 inputs of
+// a packed word; byte positions 2 * i and 2 * i + 1 of the four-code word.
+__device__ inline bool bf16x2_nonfinite(unsigned w) {
+    return ((w & 0x7f80u) == 0x7f80u) || ((w & 0x7f800000u) == 0x7f800000u);
+}
+__device__ inline unsigned e4m3_fix_nonfinite(unsigned codes, unsigned w0, unsigned w1) {
+    const unsigned in[4] = {w0 & 0xffffu, w0 >> 16, w1 & 0xffffu, w1 >> 16};
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+        if ((in[i] & 0x7f80u) == 0x7f80u)
+            codes = (codes & ~(0xffu << (8 * i))) | ((((in[i] >> 8) & 0x80u) | 0x7fu) << (8 * i));
+    return codes;
 }
 
 constexpr int kQuantLanes = 8;     // lanes per 128-element block: 16 bf16 values each
@@ -241,9 +257,9 @@ __global__ __launch_bounds__(kQuantThreads) void dispatch_pack_e4m3_kernel(
     const unsigned w[8] = {in0.x, in0.y, in0.z, in0.w, in1.x, in1.y, in1.z, in1.w};
 #pragma unroll
     for (int i = 0; i < 8; ++i) { f[2 * i] = bf16_lo(w[i]); f[2 * i + 1] = bf16_hi(w[i]); }
-    float amax = 0.f;
+    float amax = 0.f;              // a NaN element (quiet or signalling) fails the comparison and is skipped
 #pragma unroll
-    for (int i = 0; i < 16; ++i) amax = fmaxf(amax, fabsf(f[i]));
+    for (int i = 0; i < 16; ++i) { const float a = fabsf(f[i]); amax = a > amax ? a : amax; }
 #pragma unroll
     for (int o = 1; o < kQuantLanes; o <<= 1) amax = fmaxf(amax, __shfl_xor(amax, o));
     const float scale = amax == 0.f ? 1.0f : __fdiv_rn(amax, 448.0f);
@@ -252,6 +268,13 @@ __global__ __launch_bounds__(kQuantThreads) void dispatch_pack_e4m3_kernel(
     for (int i = 0; i < 4; ++i)
         q[i] = e4m3_pack4(__fdiv_rn(f[4 * i], scale), __fdiv_rn(f[4 * i + 1], scale),
                           __fdiv_rn(f[4 * i + 2], scale), __fdiv_rn(f[4 * i + 3], scale));
+    bool odd_values = false;       // rare: keep the common path free of the per-byte fix-up
+#pragma unroll
+    for (int i = 0; i < 8; ++i) odd_values |= bf16x2_nonfinite(w[i]);
+    if (odd_values) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) q[i] = e4m3_fix_nonfinite(q[i], w[2 * i], w[2 * i + 1]);
+    }
     const v4u out = {q[0], q[1], q[2], q[3]};
     // the block's scales are gathered in LDS and stored as 16-byte vectors when the
     // row's scale count allows it (scattered 4-byte stores are partial-line writes)

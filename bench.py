@@ -52,6 +52,46 @@ def algorithmic_bytes(wl, ttot, D, P, sizes, push=False, partial=False, ready=Fa
     return k, dispatch, combine
 
 
+def step_time(workloads, harness, torch, name, steps, warmup, two_streams=False, **mode):
+    """ms per step of one named workload in one mode (a context of its own, inputs resident,
+    identity expert stage or a resident expert_y), with the rate against THAT workload's and
+    mode's own algorithmic bytes.  Used for the side measurements beside the headline."""
+    wl = workloads.WORKLOADS[name]
+    inp = workloads.make_inputs(wl)
+    st = workloads.describe(inp)
+    dev = harness.to_device(inp, "cuda:0")
+    cf = None if wl.zipf_alpha > 0 else (1.1 if wl.tokens >= 2048 else 1.5)
+    sh = harness.make_shuffle(inp, capacity_factor=cf, **mode)
+    _, bd, bc = algorithmic_bytes(wl, st["tokens_total"], st["dedup_rows"], st["pairs"], sh.sizes,
+                                  mode.get("peer_push", False), mode.get("partial_sums", False))
+    y = sh.expert_x
+    if wl.dispatch_dtype != "bf16":
+        y = torch.zeros((wl.n_ranks, sh.expert_capacity_rows, wl.hidden), dtype=torch.bfloat16,
+                        device="cuda:0")
+    if two_streams:
+        streams = (torch.cuda.Stream(), torch.cuda.Stream())
+        run = lambda: harness.run_step_two_streams(sh, dev, expert_y=y, streams=streams)
+    else:
+        run = lambda: harness.run_hot_path(sh, dev, None if y is sh.expert_x else y)
+    for _ in range(warmup):
+        run()
+    torch.cuda.synchronize()
+    assert sh.status() == 0, f"device status not clean: {name} {mode}"
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        run()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    assert sh.status() == 0
+    sh.close()
+    del sh, dev, y
+    torch.cuda.empty_cache()
+    gbps = (bd + bc) / (ms * 1e-3) / 1e9
+    return {"ms_per_step": round(ms, 4), "step_us": round(ms * 1e3, 1), "steps": steps,
+            "algorithmic_bytes": bd + bc, "value": round(gbps, 1), "unit": "GB/s",
+            "frac_of_hbm_peak": round(gbps / HBM_PEAK_GBPS, 4)}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -207,7 +247,7 @@ def main():
         torch.cuda.synchronize()
         assert sh.status() == 0
         print(json.dumps({"counters_run": True, "workload": wl.name, "copy_bytes": 1 << 30, "steps": 3,
-                          "algorithmic_bytes": per_kernel}))
+                          "library_build_id": flmoe.fl_moe_build_id(), "algorithmic_bytes": per_kernel}))
         sh.close()
         return
 
@@ -302,15 +342,21 @@ def main():
     dominant = max((n for n in kern_us if n in per_kernel), key=lambda n: step_us_of[n])
     launch_bytes = per_kernel[dominant] / kern_launches[dominant]
     achieved = launch_bytes / (kern_us[dominant] * 1e-6) / 1e9
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
-    if os.path.exists(tpath):
-        traffic = json.load(open(tpath)).get(args.workload, {}).get(dominant)
+    # HBM bytes of that kernel from the stored rocprofv3 --pmc passes; only figures measured
+    # with the very library build that is being timed count (else null, with the reason)
+    from paper_2510_27656_amd import profiling
+    build_id = flmoe.fl_moe_build_id()
+    mode_tag = "unordered" if args.unordered else ""
+    plain_mode = not (args.push or args.partial_sums or args.private_rows or args.ready_e4m3)
+    traffic, traffic_note = (profiling.stored_traffic(args.workload, dominant, build_id, mode_tag)
+                             if plain_mode else (None, "no counter run stored for this mode"))
     roofline = {"bound": "hbm", "kernel": dominant, "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
                 "traffic": traffic, "algorithmic_bytes": round(launch_bytes),
                 "avg_us": round(kern_us[dominant], 2),
                 "launches_per_step": round(kern_launches[dominant], 2)}
+    if traffic is None:
+        roofline["traffic_stale"] = traffic_note
 
     # cold protocol (the paper clears caches between iterations): a 2 GiB copy between
     # steps evicts the 256 MB last-level cache; per-call medians with HIP events
@@ -372,9 +418,31 @@ def main():
         pms = (time.perf_counter() - p0) * 1e3 / args.steps
         assert shp.status() == 0
         shp.close()
-        push_line = {"ms_per_step": round(pms, 4), "algorithmic_bytes": pd + pc,
+        push_line = {"ms_per_step": round(pms, 4), "step_us": round(pms * 1e3, 1), "algorithmic_bytes": pd + pc,
                      "value": round((pd + pc) / (pms * 1e-3) / 1e9, 1), "unit": "GB/s",
                      "frac_of_hbm_peak": round((pd + pc) / (pms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)}
+
+    # The modes and workloads that are not the headline, measured in the same run: the
+    # fabric that keeps the arrival-counter contract with no ordering assumed (one stream,
+    # and with senders and receivers on two streams), and the other four named workloads.
+    side = args.workload == "dsv3_decode" and not args.headline_only and not (
+        args.push or args.unordered or args.partial_sums or args.private_rows or args.ready_e4m3)
+    unordered_line = two_stream_line = others = None
+    if side:
+        sh.close()
+        n = max(20, min(args.steps, 300))
+        w = max(5, min(args.warmup, 50))
+        unordered_line = step_time(workloads, harness, torch, "dsv3_decode", n, w, unordered_fabric=True)
+        two_stream_line = step_time(workloads, harness, torch, "dsv3_decode", n, w, two_streams=True,
+                                    unordered_fabric=True)
+        others = {}
+        for name, note in [("tiny", "launch-bound: seven kernels on a few KB"),
+                           ("qwen3_skew", "cache-assisted: the working set partly fits the 256 MB last-level cache"),
+                           ("dsv3_fp8", "e4m3 dispatch quantised on the fly, bf16 combine"),
+                           ("dsv3_prefill", "4096 tokens per rank, payload calls cut into launches of 2 ranks")]:
+            big_w = workloads.WORKLOADS[name].tokens >= 2048
+            others[name] = step_time(workloads, harness, torch, name, 5 if big_w else n, 2 if big_w else w)
+            others[name]["note"] = note
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -417,7 +485,7 @@ def main():
         "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if wl.dispatch_dtype == "bf16" else "e4m3+bf16",
-        "data": "synthetic",
+        "data": "synthetic", "library_build_id": build_id,
         "config": {"workload": wl.name, "ranks_simulated": wl.n_ranks, "experts": wl.n_experts,
                    "tokens_per_rank": wl.tokens, "hidden": wl.hidden, "top_k": wl.top_k,
                    "dedup_rows": D, "pairs": P, "capacity_factor": cf, "private_rows": int(sh.sizes.private_rows),
@@ -443,10 +511,17 @@ def main():
         "kernel_gbps": {k: round(per_kernel[k] / (step_us_of[k] * 1e-6) / 1e9, 1)
                         for k in kern_us if k in per_kernel},
         "hip_graph_replay": graph_line,
+        "step_us": round(ms_per_step * 1e3, 1),
+        "gbps_note": "GB/s divides each method's OWN algorithmic bytes by its step time: compare methods "
+                     "by step_us, not by GB/s (peer push moves fewer bytes and is the faster method)",
         "peer_push_variant": push_line,
+        "unordered_fabric_variant": unordered_line,
+        "two_stream_variant": two_stream_line,
+        "other_workloads": others,
         "roofline": roofline, "cpu_baseline": cpu,
     }
-    sh.close()
+    if sh.ctx is not None:
+        sh.close()
     print(json.dumps(line))
 
 

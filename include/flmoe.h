@@ -317,6 +317,15 @@ int fl_moe_combine_reduce(fl_moe_ctx *ctx, int rank_begin, int rank_count, const
 /* Reads and clears the device status word (synchronises the stream). */
 int fl_moe_status(fl_moe_ctx *ctx, int32_t *host_out /*host*/, void *stream);
 
+/* After FL_STATUS_TIMEOUT the counters of a context can be out of step for good: a
+ * layout call whose peers never ran has advanced its own ranks' epochs and message
+ * counters but not theirs, and a payload wait that gave up leaves its expectation ahead
+ * of what was delivered.  Once every stream that carries calls of this context has
+ * drained, fl_moe_reset zeroes the status word, the route epochs and message counters
+ * and the payload counters (set-up work: a memset and a synchronisation of `stream`),
+ * after which the next step starts as on a new context.  Not to be recorded in a graph. */
+int fl_moe_reset(fl_moe_ctx *ctx, void *stream);
+
 const char *fl_moe_strerror(int code);
 
 int fl_moe_debug_views(fl_moe_ctx *ctx, fl_moe_debug_view *out /*host*/);
@@ -362,6 +371,11 @@ int fl_moe_profile_collect(fl_moe_ctx *ctx, void *stream);
 int fl_moe_profile_read(fl_moe_ctx *ctx, double *total_ms /*host [FL_KERNEL_COUNT]*/,
                         int64_t *launches /*host [FL_KERNEL_COUNT]*/);
 const char *fl_moe_kernel_name(int kernel_id);
+
+/* Identifies the sources this binary was built from (a hash the build passes in; "unknown"
+ * for a build that did not).  The Python binding refuses a library whose id differs from
+ * the sources beside it, and stored profiler figures name the id they were measured with. */
+const char *fl_moe_build_id(void);
 
 #ifdef __cplusplus
 }

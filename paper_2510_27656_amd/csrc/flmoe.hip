@@ -405,20 +405,9 @@ int fl_moe_create(const fl_moe_config *cfg, void *workspace, size_t workspace_by
             cus > 0)
             ctx->cu_count = cus;
     }
-    for (int i = 0; i < kEventPool; ++i) {
+    for (int i = 0; i < kEventPool; ++i) {      // created when profiling is first enabled
         ctx->ev_start[i] = nullptr;
         ctx->ev_stop[i] = nullptr;
-    }
-    for (int i = 0; i < kEventPool; ++i) {
-        if (hipEventCreate(&ctx->ev_start[i]) != hipSuccess ||
-            hipEventCreate(&ctx->ev_stop[i]) != hipSuccess) {
-            for (int j = 0; j <= i; ++j) {     // give back what was created so far
-                if (ctx->ev_start[j]) (void)hipEventDestroy(ctx->ev_start[j]);
-                if (ctx->ev_stop[j]) (void)hipEventDestroy(ctx->ev_stop[j]);
-            }
-            delete ctx;
-            return FL_ERR_HIP;
-        }
     }
     memset(ctx->total_ms, 0, sizeof(ctx->total_ms));
     memset(ctx->launches, 0, sizeof(ctx->launches));
@@ -429,8 +418,8 @@ int fl_moe_create(const fl_moe_config *cfg, void *workspace, size_t workspace_by
 int fl_moe_destroy(fl_moe_ctx *ctx) {
     if (!ctx) return FL_ERR_INVALID_ARG;
     for (int i = 0; i < kEventPool; ++i) {
-        (void)hipEventDestroy(ctx->ev_start[i]);
-        (void)hipEventDestroy(ctx->ev_stop[i]);
+        if (ctx->ev_start[i]) (void)hipEventDestroy(ctx->ev_start[i]);
+        if (ctx->ev_stop[i]) (void)hipEventDestroy(ctx->ev_stop[i]);
     }
     delete ctx;
     return FL_OK;
@@ -775,6 +764,16 @@ int fl_moe_status(fl_moe_ctx *ctx, int32_t *host_out, void *stream) {
     return FL_OK;
 }
 
+int fl_moe_reset(fl_moe_ctx *ctx, void *stream) {
+    if (!ctx) return FL_ERR_INVALID_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    // status word and every counter: the contiguous head of the workspace up to plan_ok
+    const size_t bytes = (size_t)((char *)ctx->W.plan_ok - (char *)ctx->W.status);
+    if (hipMemsetAsync(ctx->W.status, 0, bytes, st) != hipSuccess) return FL_ERR_HIP;
+    if (hipStreamSynchronize(st) != hipSuccess) return FL_ERR_HIP;
+    return FL_OK;
+}
+
 const char *fl_moe_strerror(int code) {
     switch (code) {
         case FL_OK: return "ok";
@@ -838,6 +837,12 @@ int fl_moe_debug_copy(void *dst, const void *src, size_t bytes, void *stream) {
 
 int fl_moe_profile_enable(fl_moe_ctx *ctx, int on) {
     if (!ctx) return FL_ERR_INVALID_ARG;
+    if (on && !ctx->ev_start[kEventPool - 1]) {     // first use: the event pool
+        for (int i = 0; i < kEventPool; ++i) {
+            if (!ctx->ev_start[i] && hipEventCreate(&ctx->ev_start[i]) != hipSuccess) return FL_ERR_HIP;
+            if (!ctx->ev_stop[i] && hipEventCreate(&ctx->ev_stop[i]) != hipSuccess) return FL_ERR_HIP;
+        }
+    }
     ctx->profile = on ? 1 : 0;
     ctx->ev_used = 0;
     return FL_OK;
@@ -865,6 +870,11 @@ int fl_moe_profile_read(fl_moe_ctx *ctx, double *total_ms, int64_t *launches) {
     }
     return FL_OK;
 }
+
+#ifndef FLMOE_BUILD_ID
+#define FLMOE_BUILD_ID "unknown"
+#endif
+const char *fl_moe_build_id(void) { return FLMOE_BUILD_ID; }
 
 const char *fl_moe_kernel_name(int kernel_id) {
     if (kernel_id < 0 || kernel_id >= FL_KERNEL_COUNT) return "";

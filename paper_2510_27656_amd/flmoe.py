@@ -70,21 +70,28 @@ EXPORTS = ["fl_moe_query_sizes", "fl_moe_create", "fl_moe_destroy", "fl_moe_layo
            "fl_moe_dispatch_send", "fl_moe_dispatch_send_weighted", "fl_moe_dispatch_send_e4m3",
            "fl_moe_dispatch_recv",
            "fl_moe_combine_send",
-           "fl_moe_combine_reduce", "fl_moe_status", "fl_moe_strerror", "fl_moe_debug_views",
+           "fl_moe_combine_reduce", "fl_moe_status", "fl_moe_reset", "fl_moe_strerror", "fl_moe_debug_views",
            "fl_moe_debug_tune", "fl_moe_debug_launch_groups", "fl_moe_debug_copy", "fl_moe_profile_enable", "fl_moe_profile_collect", "fl_moe_profile_read",
-           "fl_moe_kernel_name"]
+           "fl_moe_kernel_name", "fl_moe_build_id"]
 
 _lib = None
 
 
 def lib():
-    """The loaded shared library.  Loads what is built; builds only if nothing is."""
+    """The loaded shared library.  Loads what is built; builds only if nothing is.  A
+    library built from other sources than the ones beside it is refused: tests and
+    benchmarks must never run an older binary than the code they claim to measure."""
     global _lib
     if _lib is None:
         path = _build.lib_path()
         if not os.path.exists(path):
             _build.build()
         L = C.CDLL(path)
+        L.fl_moe_build_id.restype = C.c_char_p
+        built_from, tree = L.fl_moe_build_id().decode(), _build.source_hash()
+        if built_from != tree:
+            raise RuntimeError(f"{path} was built from other sources (build id {built_from}, the tree has "
+                               f"{tree}): rebuild it with `python -m paper_2510_27656_amd.build`")
         vp, i32, i64 = C.c_void_p, C.c_int, C.c_int64
         L.fl_moe_query_sizes.argtypes = [C.POINTER(fl_moe_config), C.POINTER(fl_moe_sizes)]
         L.fl_moe_create.argtypes = [C.POINTER(fl_moe_config), vp, C.c_size_t, C.POINTER(vp)]
@@ -99,6 +106,7 @@ def lib():
         L.fl_moe_combine_send.argtypes = [vp, i32, i32, vp, vp]
         L.fl_moe_combine_reduce.argtypes = [vp, i32, i32, vp, vp, vp]
         L.fl_moe_status.argtypes = [vp, C.POINTER(C.c_int32), vp]
+        L.fl_moe_reset.argtypes = [vp, vp]
         L.fl_moe_strerror.argtypes = [i32]
         L.fl_moe_strerror.restype = C.c_char_p
         L.fl_moe_debug_views.argtypes = [vp, C.POINTER(fl_moe_debug_view)]
@@ -110,6 +118,7 @@ def lib():
         L.fl_moe_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i64)]
         L.fl_moe_kernel_name.argtypes = [i32]
         L.fl_moe_kernel_name.restype = C.c_char_p
+        L.fl_moe_build_id.argtypes = []
         for name in EXPORTS:
             getattr(L, name)                    # every declared symbol must be exported
         _lib = L
@@ -212,6 +221,10 @@ def fl_moe_status(ctx, stream=None) -> int:
     return v.value
 
 
+def fl_moe_reset(ctx, stream=None):
+    _check(lib().fl_moe_reset(ctx, _stream(stream)), "fl_moe_reset")
+
+
 def fl_moe_debug_views(ctx) -> fl_moe_debug_view:
     out = fl_moe_debug_view()
     _check(lib().fl_moe_debug_views(ctx, C.byref(out)), "fl_moe_debug_views")
@@ -232,6 +245,10 @@ def fl_moe_debug_launch_groups(cfg: fl_moe_config, rank_count: int, launch_mb: i
 def fl_moe_debug_copy(dst, src, nbytes, stream=None):
     _check(lib().fl_moe_debug_copy(_ptr(dst), _ptr(src), nbytes, _stream(stream)),
            "fl_moe_debug_copy")
+
+
+def fl_moe_build_id() -> str:
+    return lib().fl_moe_build_id().decode()
 
 
 def fl_moe_profile_enable(ctx, on):
@@ -338,6 +355,9 @@ class MoEShuffle:
 
     def status(self):
         return fl_moe_status(self.ctx)
+
+    def reset(self):
+        fl_moe_reset(self.ctx)
 
     def table(self, ptr, shape, dtype=torch.int32):
         """A tensor view of a table inside the workspace (for parity checks)."""

@@ -1107,6 +1107,37 @@ def test_missing_peers_time_out_instead_of_hanging():
         sh.close()
 
 
+def test_reset_brings_a_context_back_in_step_after_a_layout_time_out():
+    """A layout call without its peers leaves the ranks' epochs apart (those that ran are
+    one step ahead): the next complete step times out as well.  fl_moe_reset zeroes the
+    counters; the step after it is correct on every rank."""
+    inp, dev, sh = small_shuffle(spin_limit=200)
+    try:
+        ref = oracle_step(inp)
+        sh.layout(dev["indices"], dev["num_tokens"], ranks=(0, 2))
+        torch.cuda.synchronize()
+        assert sh.status() == flmoe.FL_STATUS_TIMEOUT
+        dbg = sh.debug()
+        assert dbg["epoch_route"].cpu().tolist() == [1, 1, 0, 0]
+        harness.run_step(sh, dev)                     # all ranks, but 0 and 1 now expect a second message
+        torch.cuda.synchronize()
+        assert sh.status() & flmoe.FL_STATUS_TIMEOUT
+        sh.reset()
+        dbg = sh.debug()
+        for name in ("epoch_route", "arrive_route", "arrive_disp", "expect_disp", "arrive_comb", "expect_comb"):
+            assert not bool(dbg[name].any()), name
+        sh.out.view(torch.int16).fill_(POISON)
+        out = harness.run_step(sh, dev)
+        torch.cuda.synchronize()
+        assert sh.status() == 0
+        check_tables(sh, ref, inp.wl.n_ranks)
+        for r in range(inp.wl.n_ranks):
+            n = inp.num_tokens[r]
+            assert (bits(out)[r, :n] == ref.out[r, :n]).all()
+    finally:
+        sh.close()
+
+
 def test_layout_split_over_two_streams_meets_in_the_exchange():
     """Half of the ranks plan on one stream, half on another: each half waits inside
     the call for the other's counts, as ranks on separate GPUs do (bounded wait)."""

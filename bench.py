@@ -92,6 +92,14 @@ def step_time(workloads, harness, torch, name, steps, warmup, two_streams=False,
             "frac_of_hbm_peak": round(gbps / HBM_PEAK_GBPS, 4)}
 
 
+def ordering_name(args):
+    if args.stream_ordered:
+        return "stream order supplied by the caller (no announce, no gate kernels)"
+    if args.progressive:
+        return "arrival counters only, per-wave progress, polling receive kernels"
+    return "arrival counters only (announce kernel after each send, gate kernel before each receive)"
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -101,11 +109,16 @@ def main():
     ap.add_argument("--capacity-factor", type=float, default=1.5,
                     help="per-rank buffer capacity as a multiple of the mean load (0 = worst case)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--unordered", action="store_true",
-                    help="run the fabric with release/acquire counters (FL_FLAG_UNORDERED_FABRIC)")
+    ap.add_argument("--stream-ordered", action="store_true",
+                    help="FL_FLAG_STREAM_ORDERED: the caller keeps sends before receives in stream order, "
+                         "the library launches no announce and no gate kernels (the counters are then "
+                         "bookkeeping, not a completion signal)")
+    ap.add_argument("--progressive", action="store_true",
+                    help="FL_FLAG_PROGRESSIVE_RECV: write-through senders, every wave reports, receive "
+                         "kernels poll per source on capped grids")
     ap.add_argument("--overlap", action="store_true",
-                    help="unordered fabric with send calls on a second stream: receivers poll the "
-                         "arrival counters while the fabric copy runs (reports the step time only)")
+                    help="send calls on a second stream: the receivers wait on the arrival counters "
+                         "while the fabric copy runs (reports the step time only)")
     ap.add_argument("--push", action="store_true",
                     help="FL_FLAG_PEER_PUSH: send kernels store into the peers' receive buffers, no "
                          "send buffer and no scatter; GB/s is then computed against the smaller byte "
@@ -156,7 +169,7 @@ def main():
     elif big:
         cf = min(cf or 1.1, 1.1)        # 16 GB buffers at 1.1x the mean; the worst case would not fit
     sh = harness.make_shuffle(inp, capacity_factor=cf,
-                              unordered_fabric=args.unordered or args.overlap,
+                              stream_ordered=args.stream_ordered, progressive_recv=args.progressive,
                               max_private_rows=args.private_rows, peer_push=args.push,
                               partial_sums=args.partial_sums)
     ttot, D, P = stats["tokens_total"], stats["dedup_rows"], stats["pairs"]
@@ -230,11 +243,11 @@ def main():
         ms = (time.perf_counter() - t0) * 1e3 / args.steps
         assert sh.status() == 0
         print(json.dumps({"metric": "dispatch+combine achieved HBM GB/s, senders and receivers on "
-                                    "two streams (unordered fabric)",
+                                    "two streams",
                           "value": round(bytes_step / (ms * 1e-3) / 1e9, 1), "unit": "GB/s",
                           "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
                           "ms_per_step": round(ms, 4), "higher_is_better": True,
-                          "config": {"workload": wl.name, "fabric": "unordered, two streams"}}))
+                          "config": {"workload": wl.name, "ordering": ordering_name(args), "streams": 2}}))
         sh.close()
         return
 
@@ -346,7 +359,7 @@ def main():
     # with the very library build that is being timed count (else null, with the reason)
     from paper_2510_27656_amd import profiling
     build_id = flmoe.fl_moe_build_id()
-    mode_tag = "unordered" if args.unordered else ""
+    mode_tag = "stream_ordered" if args.stream_ordered else ("progressive" if args.progressive else "")
     plain_mode = not (args.push or args.partial_sums or args.private_rows or args.ready_e4m3)
     traffic, traffic_note = (profiling.stored_traffic(args.workload, dominant, build_id, mode_tag)
                              if plain_mode else (None, "no counter run stored for this mode"))
@@ -403,10 +416,10 @@ def main():
     # The same step with FL_FLAG_PEER_PUSH, beside the headline: fewer bytes by
     # construction, so its GB/s is computed against its own byte count.
     push_line = None
-    if not args.push and not big and not args.unordered and not args.headline_only and not args.partial_sums \
+    if not args.push and not big and not args.progressive and not args.headline_only and not args.partial_sums \
             and not args.ready_e4m3:
         shp = harness.make_shuffle(inp, capacity_factor=cf, max_private_rows=args.private_rows,
-                                   peer_push=True)
+                                   peer_push=True, stream_ordered=args.stream_ordered)
         _, pd, pc = algorithmic_bytes(wl, ttot, D, P, shp.sizes, True)
         for _ in range(args.warmup):
             harness.run_hot_path(shp, dev, expert_y)
@@ -426,15 +439,18 @@ def main():
     # fabric that keeps the arrival-counter contract with no ordering assumed (one stream,
     # and with senders and receivers on two streams), and the other four named workloads.
     side = args.workload == "dsv3_decode" and not args.headline_only and not (
-        args.push or args.unordered or args.partial_sums or args.private_rows or args.ready_e4m3)
-    unordered_line = two_stream_line = others = None
+        args.push or args.stream_ordered or args.progressive or args.partial_sums or args.private_rows
+        or args.ready_e4m3)
+    stream_line = two_stream_line = prog_line = prog_two_line = others = None
     if side:
         sh.close()
         n = max(20, min(args.steps, 300))
         w = max(5, min(args.warmup, 50))
-        unordered_line = step_time(workloads, harness, torch, "dsv3_decode", n, w, unordered_fabric=True)
-        two_stream_line = step_time(workloads, harness, torch, "dsv3_decode", n, w, two_streams=True,
-                                    unordered_fabric=True)
+        two_stream_line = step_time(workloads, harness, torch, "dsv3_decode", n, w, two_streams=True)
+        stream_line = step_time(workloads, harness, torch, "dsv3_decode", n, w, stream_ordered=True)
+        prog_line = step_time(workloads, harness, torch, "dsv3_decode", n, w, progressive_recv=True)
+        prog_two_line = step_time(workloads, harness, torch, "dsv3_decode", n, w, two_streams=True,
+                                  progressive_recv=True)
         others = {}
         for name, note in [("tiny", "launch-bound: seven kernels on a few KB"),
                            ("qwen3_skew", "cache-assisted: the working set partly fits the 256 MB last-level cache"),
@@ -492,7 +508,7 @@ def main():
                    "method": "peer push (no send buffer, no scatter)" if args.push else "staged (pack, scatter, unpack)",
                    "combine": "sender-side bf16 partial sums" if args.partial_sums else "fp32 sum in k order",
                    "dispatch_input": "ready-made e4m3 codes + scales" if args.ready_e4m3 else "bf16",
-                   "fabric": "unordered (release/acquire)" if args.unordered else "stream-ordered",
+                   "ordering": ordering_name(args),
                    "expert_stage": "identity (expert_y aliases expert_x)" if expert_y is None
                    else "none in the timed path (resident bf16 expert_y)"},
         "frac_of_hbm_peak": round(value / HBM_PEAK_GBPS, 4),
@@ -515,8 +531,10 @@ def main():
         "gbps_note": "GB/s divides each method's OWN algorithmic bytes by its step time: compare methods "
                      "by step_us, not by GB/s (peer push moves fewer bytes and is the faster method)",
         "peer_push_variant": push_line,
-        "unordered_fabric_variant": unordered_line,
         "two_stream_variant": two_stream_line,
+        "stream_ordered_variant": stream_line,
+        "progressive_recv_variant": prog_line,
+        "progressive_recv_two_stream_variant": prog_two_line,
         "other_workloads": others,
         "roofline": roofline, "cpu_baseline": cpu,
     }

@@ -23,20 +23,24 @@
  *     simulated rank r.  Each call acts for ranks [rank_begin, rank_begin +
  *     rank_count); code acting for rank r reads only rank r's tensors and
  *     receive buffers, and writes other ranks' memory only through the fabric
- *     copy and its counters.  A real deployment would pass rank_count = 1.
+ *     copy and its counters.  Ranks on separate GPUs would each pass rank_count = 1
+ *     (their calls then run at the same time, each on its own device).
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  The
  *     five shuffle calls only enqueue kernels: they never synchronise, never
  *     allocate, and can be captured in a HIP graph.  A call that moves several GB
  *     enqueues its kernels once per group of ranks (very large launches run
  *     measurably slower than the same work in launches of about a GB), except
- *     with FL_FLAG_UNORDERED_FABRIC.
+ *     with FL_FLAG_PROGRESSIVE_RECV.
  *   - One step = the five calls once each, in the order layout, dispatch_send,
  *     dispatch_recv, combine_send, combine_reduce, with every rank of the group
  *     taking part in each.  The payload calls may be split over several launches
- *     by rank range.  fl_moe_layout waits inside the call for every peer's counts,
- *     as ranks on separate GPUs wait for each other: all ranks go into one launch,
- *     or into launches the device can run at the same time (different streams).
- *     A call whose peers never ran ends with FL_STATUS_TIMEOUT, not with a hang.
+ *     by rank range.  fl_moe_layout is different: it waits INSIDE the call for every
+ *     peer's counts, as ranks on separate GPUs wait for each other.  On one GPU the
+ *     peers' layout calls must therefore be able to run at the same time: all ranks
+ *     in one call (rank_count = N), or in calls on different streams; calls for
+ *     part of the ranks one after another on ONE stream cannot complete (the first
+ *     waits for counts that only the later ones would send).  A call whose peers
+ *     never ran ends with FL_STATUS_TIMEOUT after the bounded wait, not with a hang.
  *   - A context is not thread-safe: its calls come from one host thread at a
  *     time.  Several contexts (each with its own workspace) are independent.
  *   - Return value: FL_OK or a negative FL_ERR_* for errors the host can see
@@ -71,32 +75,56 @@ extern "C" {
 #define FL_DTYPE_BF16 0
 /* OCP E4M3 (finite-only) bytes plus one fp32 scale per 128 elements, quantised
  * by dispatch_send (workload of section Kernel Microbenchmarks: 7168 fp8 values
- * and 56 fp32 scaling factors per token) */
+ * and 56 fp32 scaling factors per token).  Per block of 128: scale = max|x| / 448
+ * (1 when the maximum is 0), code = e4m3(x / scale), round to nearest even,
+ * saturating; both divisions IEEE fp32.  Non-finite inputs (the paper is silent; the
+ * rule is applied as written): a NaN is skipped by the maximum and becomes the NaN
+ * code 0x7f with its own sign, its neighbours are quantised as if it were absent; an
+ * Inf makes the block's scale +Inf, every finite value of that block a signed zero and
+ * every Inf the NaN code with its sign; a block of NaNs only has scale 1. */
 #define FL_DTYPE_E4M3_BLOCK128 1
 
 #define FL_FLAG_ZERO_PAD 1 /* dispatch_recv writes zeros into the padding rows between experts */
-/* Without this flag the caller keeps each send call before the matching receive
- * call in stream order (one stream, or events between streams); the arrival
- * counters are then checked with relaxed atomics and no cache maintenance, and
- * advanced once per (sender, receiver) transfer by the kernel that copies the
- * payload (its end, in stream order, is what makes payload and counters visible
- * to the receivers), as a NIC delivers one immediate after a whole WRITE.
- * With it, send and receive kernels may overlap in time (other streams, other
- * orders): a sender writes its payload through to memory
- * (device-scope stores) and waits for the acknowledgement before it reports
- * progress (every wave adds what it delivered, so a receiver sees a source's
- * range complete as early as possible), and a receiver invalidates its caches
- * once after its counters arrived, which is the ImmCounter contract with no
- * ordering assumed. */
-#define FL_FLAG_UNORDERED_FABRIC 2
+/* How senders and receivers are ordered.
+ *
+ * Default (neither flag below): the arrival counters are the only thing that orders a
+ * sender and a receiver, the ImmCounter contract with no ordering assumed (section
+ * TransferEngine, Completion Notification).  Send and receive calls of different ranks
+ * may be issued on any streams, in any order, and may overlap in time.
+ *   - A send call enqueues its payload kernels and, behind them in the same stream, a
+ *     small kernel that adds each whole (sender, receiver) transfer to the receiver's
+ *     counter with release semantics: it starts once the payload kernels have ended
+ *     (the sender's own stream order, as a NIC posts the immediate after its WRITE),
+ *     so the counter never runs ahead of the payload.
+ *   - A receive call first enqueues a gate kernel of one wave per rank that polls the
+ *     rank's counters with acquire semantics until every source has delivered what
+ *     the exchanged counts promised (bounded: FL_STATUS_TIMEOUT), and behind it the
+ *     receive kernel proper, on a full grid.  Waiting occupies one wave per rank.
+ * What the caller still orders itself is the RE-USE of the two staging buffers of a
+ * context: every dispatch_send and dispatch_recv of a step before any combine_send of
+ * that step (combine replies land in the senders' dispatch send buffers, and the
+ * dispatch receive buffers become the combine send buffers), and every combine_reduce
+ * of a step before the next step's dispatch_send (one stream does that by itself;
+ * across streams, events - the paper's barrier before buffers are re-used, section
+ * Combine).
+ *
+ * FL_FLAG_STREAM_ORDERED: the caller promises that each send call precedes the matching
+ * receive call in stream order (one stream, or events between streams).  The library
+ * then launches no announce and no gate kernels (four launches fewer per step): one
+ * wave of the last payload kernel of a send call advances the counters while other
+ * waves may still be storing, so here the counters are bookkeeping that only the
+ * kernel boundary makes trustworthy - they are still checked (bounded) by the
+ * receivers, but they do not signal completion by themselves. */
+#define FL_FLAG_STREAM_ORDERED 2
 /* Every peer's receive buffer can be stored to directly, as between ranks of one
  * node (section Dispatch: within a node the send kernel pushes payloads over the
  * load/store interconnect instead of handing them to the NIC; here: always, all
  * simulated ranks live on one GPU).  The send calls then write each row and its
  * sidecar straight into the destination's receive buffer: no send buffer is
  * filled and no scatter kernel runs; the arrival counters advance as in the
- * staged path (once per transfer inside the kernel that stores the payload, or
- * per workgroup with FL_FLAG_UNORDERED_FABRIC).  Receivers, counters, capacities and every result
+ * staged path (by the announce kernel, inside the kernel that stores the payload
+ * with FL_FLAG_STREAM_ORDERED, per workgroup with FL_FLAG_PROGRESSIVE_RECV).
+ * Receivers, counters, capacities and every result
  * are unchanged; only the bytes moved per step shrink (one write per sent row
  * instead of write + read + write).  Combines with the other flags and
  * max_private_rows. */
@@ -114,6 +142,19 @@ extern "C" {
  * dispatch must be issued with fl_moe_dispatch_send_weighted, and every rank
  * answers each row it received with one row (D rows per step instead of P). */
 #define FL_FLAG_PARTIAL_SUMS 8
+/* Receivers that start on each source's rows as soon as that source has landed,
+ * whatever the other sources do (not with FL_FLAG_STREAM_ORDERED).  Senders write their
+ * payload through to memory with device-scope stores, wait for the acknowledgement and
+ * every wave adds what it delivered, so a receiver sees a source complete as early as
+ * possible; the receive kernels poll the counters themselves, invalidate their caches
+ * whenever they come to rely on arrivals they had not seen before, and run on grids
+ * capped to a fraction of the machine so that pollers can never keep senders from
+ * being scheduled.  The form for receivers whose sources land far apart in time; on
+ * one GPU, where all simulated senders finish together, it only costs.  Its
+ * visibility argument is about the hardware (a device-scope store that was
+ * acknowledged is in memory; a cache invalidated after the counter was observed
+ * cannot hold older bytes), not about the HIP memory model alone. */
+#define FL_FLAG_PROGRESSIVE_RECV 16
 
 #define FL_MAX_RANKS 64
 #define FL_MAX_EXPERTS 1024
@@ -344,7 +385,9 @@ int fl_moe_debug_views(fl_moe_ctx *ctx, fl_moe_debug_view *out /*host*/);
  * knob 6 = payload in MiB one launch should move per direction: a call whose ranks
  * move more than three times as much is issued as several launches over rank
  * groups of about this size (default 860; 0 = always one launch per kernel;
- * contexts with FL_FLAG_UNORDERED_FABRIC are never cut). */
+ * contexts with FL_FLAG_PROGRESSIVE_RECV are never cut), knob 7 = eighths of the
+ * machine's resident-workgroup slots the polling receive kernels of
+ * FL_FLAG_PROGRESSIVE_RECV may take (default 3).  A value of -1 restores a knob's default. */
 int fl_moe_debug_tune(fl_moe_ctx *ctx, int knob, int value);
 
 /* Diagnostic, host only (no GPU needed): how a payload call over `rank_count` ranks of
@@ -365,7 +408,7 @@ int fl_moe_debug_copy(void *dst, const void *src, size_t bytes, void *stream);
  * since the last collect to per-kernel totals, and fl_moe_profile_read returns
  * totals (ms) and launch counts for kernel ids 0..FL_KERNEL_COUNT-1.  At most
  * 512 launches between two collects are timed; further ones run untimed. */
-#define FL_KERNEL_COUNT 10
+#define FL_KERNEL_COUNT 14
 int fl_moe_profile_enable(fl_moe_ctx *ctx, int on);
 int fl_moe_profile_collect(fl_moe_ctx *ctx, void *stream);
 int fl_moe_profile_read(fl_moe_ctx *ctx, double *total_ms /*host [FL_KERNEL_COUNT]*/,

@@ -32,6 +32,7 @@ struct Dims {
     int tune_grid_pct;    // row-kernel grids cover this percentage of the rows uniform routing would
                           // bring (0 = the whole capacity); kernels loop over whatever is beyond
     long long typ_recv_rows, typ_pair_rows;   // per rank, under uniform routing: received rows, pairs
+    int tune_cap8;        // progressive receivers: eighths of the machine's block slots their grids may take
 };
 
 // Row of a dispatch receive buffer that holds the i-th row source s sent to this
@@ -79,6 +80,8 @@ struct Tables {
     int *cs_base;         // [N][N][El]       first combine-send row of (source, local expert)
     int *cs_off;          // [N][N+1]         first combine-send row of each source
     int *plan_ok;         // [N]
+    int *gate_disp;       // [N] unordered mode: 1 once every source's dispatch payload was seen complete
+    int *gate_comb;       // [N] the same for the combine replies
     unsigned *send_meta;  // [N][send_cap][MW]
     unsigned *recv_meta;  // [N][recv_rows][MW]
     int2 *fab_dst_disp;   // [N][send_cap]    (destination rank, row there) of every send row

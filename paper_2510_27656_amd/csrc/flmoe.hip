@@ -24,13 +24,15 @@ namespace {
 enum KernelId {
     KID_ROUTE_LAYOUT = 0, KID_DISPATCH_PACK, KID_DISPATCH_FABRIC,
     KID_DISPATCH_UNPACK, KID_COMBINE_PACK, KID_COMBINE_FABRIC, KID_COMBINE_REDUCE,
-    KID_DISPATCH_PACK_E4M3, KID_DISPATCH_FABRIC_PRIVATE, KID_COMBINE_PARTIAL_PACK
+    KID_DISPATCH_PACK_E4M3, KID_DISPATCH_FABRIC_PRIVATE, KID_COMBINE_PARTIAL_PACK, KID_GATE_DISPATCH,
+    KID_GATE_COMBINE, KID_ANNOUNCE_DISPATCH, KID_ANNOUNCE_COMBINE
 };
 const char *kKernelNames[FL_KERNEL_COUNT] = {
     "route_layout_kernel", "dispatch_pack_kernel", "fabric_copy_kernel(dispatch)",
     "dispatch_unpack_kernel", "combine_pack_kernel", "fabric_copy_kernel(combine)",
     "combine_reduce_kernel", "dispatch_pack_e4m3_kernel", "fabric_copy_kernel(dispatch, private slots)",
-    "combine_partial_pack_kernel"};
+    "combine_partial_pack_kernel", "arrival_gate_kernel(dispatch)", "arrival_gate_kernel(combine)",
+    "announce_kernel(dispatch)", "announce_kernel(combine)"};
 
 constexpr int kEventPool = 512;
 constexpr long long kMaxFabricBlocks = 1 << 16;   // waves loop cheaply (no barriers)
@@ -68,8 +70,10 @@ int resolve(const fl_moe_config *c, Dims *D) {
         return FL_ERR_INVALID_ARG;
     if (c->dispatch_dtype == FL_DTYPE_E4M3_BLOCK128 && c->hidden % 128 != 0) return FL_ERR_ALIGNMENT;
     if (c->expert_align < 1 || c->expert_align > (1 << 16)) return FL_ERR_INVALID_ARG;
-    if (c->flags & ~(FL_FLAG_ZERO_PAD | FL_FLAG_UNORDERED_FABRIC | FL_FLAG_PEER_PUSH | FL_FLAG_PARTIAL_SUMS))
+    if (c->flags & ~(FL_FLAG_ZERO_PAD | FL_FLAG_STREAM_ORDERED | FL_FLAG_PEER_PUSH | FL_FLAG_PARTIAL_SUMS |
+                     FL_FLAG_PROGRESSIVE_RECV))
         return FL_ERR_INVALID_ARG;
+    if ((c->flags & FL_FLAG_PROGRESSIVE_RECV) && (c->flags & FL_FLAG_STREAM_ORDERED)) return FL_ERR_INVALID_ARG;
     if (c->recv_capacity_rows < 0 || c->expert_capacity_rows < 0 || c->spin_limit < 0)
         return FL_ERR_INVALID_ARG;
     if (c->max_private_rows < 0 || c->reserved != 0) return FL_ERR_INVALID_ARG;
@@ -123,6 +127,7 @@ int resolve(const fl_moe_config *c, Dims *D) {
     D->tune_slices = 0;
     D->tune_stream_mb = 2560;
     D->tune_grid_pct = 200;
+    D->tune_cap8 = 3;
     {   // a token reaches a given rank with probability 1 - (1 - 1/N)^K when experts are drawn uniformly
         double miss = 1.0;
         for (int k = 0; k < D->K; ++k) miss *= 1.0 - 1.0 / D->N;
@@ -144,6 +149,8 @@ size_t carve(const Dims &D, void *base, Tables *W, size_t *total) {
     W->expect_disp = c.take<unsigned>(N * N);
     W->expect_comb = c.take<unsigned>(N * N);
     W->plan_ok = c.take<int>(N);
+    W->gate_disp = c.take<int>(N);
+    W->gate_comb = c.take<int>(N);
     W->routes = c.take<int>(N * N * D.route_len);
     W->C = c.take<int>(N * E);
     W->M = c.take<int>(N * N);
@@ -276,7 +283,7 @@ int launch_status() { return hipGetLastError() == hipSuccess ? FL_OK : FL_ERR_HI
 // through, and there the cut measured 3 % slower (and the caller who overlaps
 // senders and receivers chooses the granularity of the send calls itself).
 int ranks_per_launch(const Dims &D, int launch_mb, int rc) {
-    if (launch_mb <= 0 || (D.flags & FL_FLAG_UNORDERED_FABRIC)) return rc;
+    if (launch_mb <= 0 || (D.flags & FL_FLAG_PROGRESSIVE_RECV)) return rc;
     const long long row = D.Bw > D.Bc ? D.Bw : D.Bc;
     const long long per_rank = (long long)D.T * D.K * row;
     const long long target = (long long)launch_mb << 20;
@@ -501,7 +508,11 @@ static int dispatch_send_range(fl_moe_ctx *ctx, int rb, int rc, const void *x, c
     hipStream_t st = (hipStream_t)stream;
     const Dims &D = ctx->D;
     const Tables &W = ctx->W;
-    const bool push = D.flags & FL_FLAG_PEER_PUSH, fenced = D.flags & FL_FLAG_UNORDERED_FABRIC;
+    // fenced: every wave reports what it delivered (progressive receivers); in_kernel: the last
+    // payload kernel of the call also advances the counters (stream-ordered callers); otherwise
+    // a kernel of its own does, behind the payload kernels in this (the sender's) stream
+    const bool push = D.flags & FL_FLAG_PEER_PUSH, fenced = D.flags & FL_FLAG_PROGRESSIVE_RECV;
+    const bool in_kernel = D.flags & FL_FLAG_STREAM_ORDERED;
     if (D.dtype == FL_DTYPE_E4M3_BLOCK128 && !ready_scales) {
         LaunchTimer t(ctx, KID_DISPATCH_PACK_E4M3, st);
         const int per_block = kQuantThreads / kQuantLanes;       // quantisation blocks per workgroup
@@ -534,7 +545,16 @@ static int dispatch_send_range(fl_moe_ctx *ctx, int rb, int rc, const void *x, c
             dispatch_pack_kernel<false, false><<<grid, block, 0, st>>>(D, W, rb, xp, ctx->indices,
                                                                        ctx->num_tokens, slices, weights, src_row, ready_scales);
     }
-    if (push) return launch_status();         // the rows are already in the peers' receive buffers
+    auto announce = [&]() {                   // counter-ordered mode: the transfers are announced once
+        if (fenced || in_kernel) return;      // every payload kernel of the call has ended
+        LaunchTimer t(ctx, KID_ANNOUNCE_DISPATCH, st);
+        announce_kernel<<<dim3(rc), dim3(kWave), 0, st>>>(D, W, rb, W.send_off, W.arrive_disp,
+                                                           (unsigned)(D.Bw / 16));
+    };
+    if (push) {                               // the rows are already in the peers' receive buffers
+        announce();
+        return launch_status();
+    }
     FabricArgs A;
     A.src_base = W.bufA; A.src_rank_stride = D.bufA_rank_bytes;
     A.dst_base = W.bufB; A.dst_rank_stride = D.bufB_rank_bytes;
@@ -552,11 +572,11 @@ static int dispatch_send_range(fl_moe_ctx *ctx, int rb, int rc, const void *x, c
     if (D.P > 0) {
         // First scatter: the rows bound for private slots.  Their targets follow from the
         // sender's own counts alone, so this launch reads nothing a peer produced.
-        A.announce = !fenced && D.P >= D.T;   // the call's last copy kernel announces the transfers
+        A.announce = in_kernel && D.P >= D.T; // the call's last copy kernel announces the transfers
         LaunchTimer t(ctx, KID_DISPATCH_FABRIC_PRIVATE, st);
         const unsigned g1 = capped_grid(((long long)D.N * D.P * A.waves_per_row + wpb - 1) / wpb, rc,
                                         kMaxFabricBlocks, A.waves_per_row);
-        if (D.flags & FL_FLAG_UNORDERED_FABRIC)
+        if (fenced)
             fabric_private_kernel<true, true><<<dim3(g1, rc), dim3(kCopyThreads), 0, st>>>(D, W, A, rb);
         else if (streaming)
             fabric_private_kernel<false, true><<<dim3(g1, rc), dim3(kCopyThreads), 0, st>>>(D, W, A, rb);
@@ -565,15 +585,16 @@ static int dispatch_send_range(fl_moe_ctx *ctx, int rb, int rc, const void *x, c
         A.dst_row_lo = D.N * D.P;             // second scatter: the rest, into the shared range
     }
     if (D.P < D.T) {                          // with P = T every row has a private slot
-        A.announce = !fenced;
+        A.announce = in_kernel;
         LaunchTimer t(ctx, KID_DISPATCH_FABRIC, st);
-        if (D.flags & FL_FLAG_UNORDERED_FABRIC)
+        if (fenced)
             fabric_copy_kernel<true, 0, true><<<dim3(gx, rc), dim3(kCopyThreads), 0, st>>>(D, W, A, rb);
         else if (streaming)
             fabric_copy_kernel<false, 0, true><<<dim3(gx, rc), dim3(kCopyThreads), 0, st>>>(D, W, A, rb);
         else
             fabric_copy_kernel<false, 0, false><<<dim3(gx, rc), dim3(kCopyThreads), 0, st>>>(D, W, A, rb);
     }
+    announce();
     return launch_status();
 }
 
@@ -613,31 +634,47 @@ static int dispatch_recv_range(fl_moe_ctx *ctx, int rb, int rc, void *expert_x, 
     if (!aligned16(expert_x) || !aligned16(expert_scales) || ((uintptr_t)tokens_per_expert & 3))
         return FL_ERR_ALIGNMENT;
     hipStream_t st = (hipStream_t)stream;
-    const int rbk = rows_per_block(D.Bw, D.tune_rows);
-    // In unordered mode the receivers may be polling while senders still need
-    // somewhere to run: they take at most three eighths of the resident-block slots (measured best).
-    const bool unordered = D.flags & FL_FLAG_UNORDERED_FABRIC;
+    const bool gated = !(D.flags & FL_FLAG_STREAM_ORDERED);
+    const bool progressive = D.flags & FL_FLAG_PROGRESSIVE_RECV;
+    // Default: a gate kernel of one wave per rank polls the rank's arrival counters, and the
+    // unpack kernel runs behind it in the stream on a full grid.  Stream-ordered callers need
+    // no gate.  Progressive: the unpack kernel polls itself and starts on each
+    // source's rows as they land; it may be running while senders still need somewhere to
+    // run, so it takes at most three eighths of the resident-block slots (measured best), and
+    // to keep the memory system busy with that few waves a block moves 32 KB per turn.
+    int rbk = rows_per_block(D.Bw, D.tune_rows);
+    if (progressive && D.tune_rows == 0) {
+        long long r = (32768 + D.Bw - 1) / D.Bw;
+        rbk = (int)(r > kMaxRowsPerBlock ? kMaxRowsPerBlock : r);
+    }
     const long long worst_rows = (long long)D.N * D.T;       // received rows in use never exceed this
     const long long max_rows = D.recv_rows < worst_rows ? D.recv_rows : worst_rows;
     unsigned gx = capped_grid((grid_rows(D, max_rows, D.typ_recv_rows) + rbk - 1) / rbk, rc,
-                              unordered ? (long long)ctx->cu_count * 3 : kMaxRowBlocks);
+                              progressive ? (long long)ctx->cu_count * D.tune_cap8 : kMaxRowBlocks);
     if (gx < (unsigned)D.El) gx = D.El;      // the first El-1 blocks also clear padding rows
+    const int *gate = nullptr;
+    if (gated && !progressive) {
+        LaunchTimer t(ctx, KID_GATE_DISPATCH, st);
+        arrival_gate_kernel<<<dim3(rc), dim3(kWave), 0, st>>>(D, ctx->W, rb, ctx->W.arrive_disp,
+                                                               ctx->W.expect_disp, ctx->W.gate_disp);
+        gate = ctx->W.gate_disp;
+    }
     {
         LaunchTimer t(ctx, KID_DISPATCH_UNPACK, st);
         const dim3 grid(gx, rc), block(kCopyThreads);
         char *ex = (char *)expert_x;
-        if (unordered && D.P)
+        if (progressive && D.P)
             dispatch_unpack_kernel<true, true><<<grid, block, 0, st>>>(D, ctx->W, rb, ex, expert_scales,
-                                                                       tokens_per_expert, rbk);
-        else if (unordered)
+                                                                       tokens_per_expert, rbk, gate);
+        else if (progressive)
             dispatch_unpack_kernel<true, false><<<grid, block, 0, st>>>(D, ctx->W, rb, ex, expert_scales,
-                                                                        tokens_per_expert, rbk);
+                                                                        tokens_per_expert, rbk, gate);
         else if (D.P)
             dispatch_unpack_kernel<false, true><<<grid, block, 0, st>>>(D, ctx->W, rb, ex, expert_scales,
-                                                                        tokens_per_expert, rbk);
+                                                                        tokens_per_expert, rbk, gate);
         else
             dispatch_unpack_kernel<false, false><<<grid, block, 0, st>>>(D, ctx->W, rb, ex, expert_scales,
-                                                                         tokens_per_expert, rbk);
+                                                                         tokens_per_expert, rbk, gate);
     }
     return launch_status();
 }
@@ -658,7 +695,8 @@ static int combine_send_range(fl_moe_ctx *ctx, int rb, int rc, const void *exper
     const Dims &D = ctx->D;
     const Tables &W = ctx->W;
     const int rbk = rows_per_block(D.Bc, D.tune_rows);
-    const bool push = D.flags & FL_FLAG_PEER_PUSH, fenced = D.flags & FL_FLAG_UNORDERED_FABRIC;
+    const bool push = D.flags & FL_FLAG_PEER_PUSH, fenced = D.flags & FL_FLAG_PROGRESSIVE_RECV;
+    const bool in_kernel = D.flags & FL_FLAG_STREAM_ORDERED;     // as in dispatch_send_range
     const bool partial = D.flags & FL_FLAG_PARTIAL_SUMS;
     // rows a rank sends back: one per pair, or with partial sums one per received row
     const long long worst_recv = (long long)D.N * D.T;
@@ -681,7 +719,16 @@ static int combine_send_range(fl_moe_ctx *ctx, int rb, int rc, const void *exper
             else combine_pack_kernel<false, false><<<grid, block, 0, st>>>(D, W, rb, yp, rbk);
         }
     }
-    if (push) return launch_status();         // the rows are already in the sources' receive buffers
+    auto announce = [&]() {
+        if (fenced || in_kernel) return;
+        LaunchTimer t(ctx, KID_ANNOUNCE_COMBINE, st);
+        announce_kernel<<<dim3(rc), dim3(kWave), 0, st>>>(D, W, rb, partial ? W.recv_off : W.cs_off,
+                                                           W.arrive_comb, (unsigned)(D.Bc / 16));
+    };
+    if (push) {                               // the rows are already in the sources' receive buffers
+        announce();
+        return launch_status();
+    }
     FabricArgs A;
     A.src_base = W.bufB; A.src_rank_stride = D.bufB_rank_bytes;
     A.dst_base = W.bufA; A.dst_rank_stride = D.bufA_rank_bytes;
@@ -689,7 +736,7 @@ static int combine_send_range(fl_moe_ctx *ctx, int rb, int rc, const void *exper
     A.src_meta = nullptr; A.src_meta_rank_stride = 0;
     A.dst_meta = nullptr; A.dst_meta_rank_stride = 0;
     A.dst_row_lo = 0;
-    A.announce = !fenced;
+    A.announce = in_kernel;
     A.arrive = W.arrive_comb;
     A.row_bytes = D.Bc; A.waves_per_row = waves_per_row(D.Bc, D.tune_waves);
     const int wpb = kCopyThreads / kWave;
@@ -699,13 +746,14 @@ static int combine_send_range(fl_moe_ctx *ctx, int rb, int rc, const void *exper
         LaunchTimer t(ctx, KID_COMBINE_FABRIC, st);
         // what the launch can write: every rank gets back at most T*K rows
         const bool streaming = (long long)D.N * D.T * D.K * D.Bc > ((long long)D.tune_stream_mb << 20);
-        if (D.flags & FL_FLAG_UNORDERED_FABRIC)
+        if (fenced)
             fabric_copy_kernel<true, 1, true><<<dim3(gxf, rc), dim3(kCopyThreads), 0, st>>>(D, W, A, rb);
         else if (streaming)
             fabric_copy_kernel<false, 1, true><<<dim3(gxf, rc), dim3(kCopyThreads), 0, st>>>(D, W, A, rb);
         else
             fabric_copy_kernel<false, 1, false><<<dim3(gxf, rc), dim3(kCopyThreads), 0, st>>>(D, W, A, rb);
     }
+    announce();
     return launch_status();
 }
 
@@ -723,23 +771,32 @@ static int combine_reduce_range(fl_moe_ctx *ctx, int rb, int rc, const float *we
     if (!aligned16(out) || ((uintptr_t)weights & 3)) return FL_ERR_ALIGNMENT;
     hipStream_t st = (hipStream_t)stream;
     const Dims &D = ctx->D;
+    const bool gated = !(D.flags & FL_FLAG_STREAM_ORDERED), partial = D.flags & FL_FLAG_PARTIAL_SUMS;
+    const bool progressive = D.flags & FL_FLAG_PROGRESSIVE_RECV;
+    const int *gate = nullptr;
+    if (gated && !progressive) {         // as in dispatch_recv: a gate kernel, then the full grid
+        LaunchTimer t(ctx, KID_GATE_COMBINE, st);
+        arrival_gate_kernel<<<dim3(rc), dim3(kWave), 0, st>>>(D, ctx->W, rb, ctx->W.arrive_comb,
+                                                               ctx->W.expect_comb, ctx->W.gate_comb);
+        gate = ctx->W.gate_comb;
+    }
     {
         LaunchTimer t(ctx, KID_COMBINE_REDUCE, st);
         int nt = (int)((D.Bc / 16 + kWave - 1) / kWave * kWave);
         if (nt > kReduceMaxThreads) nt = kReduceMaxThreads;
         if (nt < 2 * kWave) nt = 2 * kWave;      // wave 0 waits, wave 1 fetches positions and weights
-        const bool unordered = D.flags & FL_FLAG_UNORDERED_FABRIC, partial = D.flags & FL_FLAG_PARTIAL_SUMS;
-        // polling receivers (unordered mode) take at most three eighths of the machine's wave slots
-        const dim3 grid(unordered ? capped_grid(D.T, rc, (long long)ctx->cu_count * 768 / nt) : (unsigned)D.T, rc);
+        // progressive (polling) receivers take at most three eighths of the machine's wave slots
+        const dim3 grid(progressive ? capped_grid(D.T, rc, (long long)ctx->cu_count * 256 * D.tune_cap8 / nt)
+                                    : (unsigned)D.T, rc);
         char *o = (char *)out;
-        if (unordered && partial)
-            combine_reduce_kernel<true, true><<<grid, dim3(nt), 0, st>>>(D, ctx->W, rb, weights, o, ctx->num_tokens);
-        else if (unordered)
-            combine_reduce_kernel<true, false><<<grid, dim3(nt), 0, st>>>(D, ctx->W, rb, weights, o, ctx->num_tokens);
+        if (progressive && partial)
+            combine_reduce_kernel<true, true><<<grid, dim3(nt), 0, st>>>(D, ctx->W, rb, weights, o, ctx->num_tokens, gate);
+        else if (progressive)
+            combine_reduce_kernel<true, false><<<grid, dim3(nt), 0, st>>>(D, ctx->W, rb, weights, o, ctx->num_tokens, gate);
         else if (partial)
-            combine_reduce_kernel<false, true><<<grid, dim3(nt), 0, st>>>(D, ctx->W, rb, weights, o, ctx->num_tokens);
+            combine_reduce_kernel<false, true><<<grid, dim3(nt), 0, st>>>(D, ctx->W, rb, weights, o, ctx->num_tokens, gate);
         else
-            combine_reduce_kernel<false, false><<<grid, dim3(nt), 0, st>>>(D, ctx->W, rb, weights, o, ctx->num_tokens);
+            combine_reduce_kernel<false, false><<<grid, dim3(nt), 0, st>>>(D, ctx->W, rb, weights, o, ctx->num_tokens, gate);
     }
     return launch_status();
 }
@@ -800,15 +857,17 @@ int fl_moe_debug_views(fl_moe_ctx *ctx, fl_moe_debug_view *out) {
 }
 
 int fl_moe_debug_tune(fl_moe_ctx *ctx, int knob, int value) {
-    if (!ctx || value < 0) return FL_ERR_INVALID_ARG;
+    if (!ctx || value < -1) return FL_ERR_INVALID_ARG;
+    const bool dflt = value == -1;             // -1 = back to the default
     switch (knob) {
-        case 0: if (value > kMaxRowsPerBlock) return FL_ERR_INVALID_ARG; ctx->D.tune_rows = value; break;
-        case 2: ctx->D.tune_waves = value; break;
-        case 4: ctx->D.tune_stream_mb = value; break;
-        case 5: if (value > 1000) return FL_ERR_INVALID_ARG; ctx->D.tune_grid_pct = value; break;
-        case 3: if (value > 16) return FL_ERR_INVALID_ARG; ctx->D.tune_slices = value; break;
-        case 1: if (value > 8) return FL_ERR_INVALID_ARG; ctx->D.tune_reduce = value; break;
-        case 6: ctx->launch_mb = value; break;
+        case 0: if (value > kMaxRowsPerBlock) return FL_ERR_INVALID_ARG; ctx->D.tune_rows = dflt ? 0 : value; break;
+        case 1: if (value > 8) return FL_ERR_INVALID_ARG; ctx->D.tune_reduce = dflt ? 0 : value; break;
+        case 2: ctx->D.tune_waves = dflt ? 0 : value; break;
+        case 3: if (value > 16) return FL_ERR_INVALID_ARG; ctx->D.tune_slices = dflt ? 0 : value; break;
+        case 4: ctx->D.tune_stream_mb = dflt ? 2560 : value; break;
+        case 5: if (value > 1000) return FL_ERR_INVALID_ARG; ctx->D.tune_grid_pct = dflt ? 200 : value; break;
+        case 6: ctx->launch_mb = dflt ? kLaunchMiB : value; break;
+        case 7: if (value > 8 || value == 0) return FL_ERR_INVALID_ARG; ctx->D.tune_cap8 = dflt ? 3 : value; break;
         default: return FL_ERR_INVALID_ARG;
     }
     return FL_OK;

@@ -153,7 +153,7 @@ __global__ __launch_bounds__(kPackThreads) void dispatch_pack_kernel(
         if (tid < K && my_row >= 0 && units > 0)
             add_counter(W.arrive_disp + (size_t)my_d * D.N + s, units);
     }
-    if (PUSH && !FENCED && blockIdx.x == 0)    // stream-ordered: the sender's first block announces
+    if (PUSH && !FENCED && (D.flags & FL_FLAG_STREAM_ORDERED) && blockIdx.x == 0)    // stream-ordered: the sender's first block announces
         announce_transfers(W.send_off + (size_t)s * (D.N + 1), W.arrive_disp, (unsigned)(D.Bw / 16), s, D.N,
                            tid, kPackThreads);
 }
@@ -314,7 +314,7 @@ __global__ __launch_bounds__(kQuantThreads) void dispatch_pack_e4m3_kernel(
             add_counter(W.arrive_disp + (size_t)my_d * D.N + s,
                         (unsigned)(n_live * 8 + (n_live + 3) / 4 + (slice == 0 ? pad_units : 0)));
     }
-    if (PUSH && !FENCED && blockIdx.x == 0)
+    if (PUSH && !FENCED && (D.flags & FL_FLAG_STREAM_ORDERED) && blockIdx.x == 0)
         announce_transfers(W.send_off + (size_t)s * (D.N + 1), W.arrive_disp, (unsigned)(D.Bw / 16), s, D.N,
                            tid, kQuantThreads);
 }
@@ -434,23 +434,84 @@ __global__ __launch_bounds__(kCopyThreads) void fabric_private_kernel(Dims D, Ta
         announce_transfers(A.seg_off + (size_t)s * (N + 1), A.arrive, (unsigned)(A.row_bytes / 16), s, N, lane, kWave);
 }
 
+// ------------------------------------------------------------------ announce
+// Counter-ordered mode (the default), sending side: enqueued behind the payload
+// kernels of a send call in the sender's own stream, so it starts once they have
+// ended and everything they stored has left for memory; one wave per sender then
+// adds each whole (sender, receiver) transfer to the receiver's arrival counter
+// with release semantics - the single immediate a NIC delivers after a completed
+// WRITE (section TransferEngine, ImmCounter).  off: [N][N+1] row offsets of the
+// senders' segment tables.
+__global__ __launch_bounds__(kWave) void announce_kernel(Dims D, Tables W, int rank_begin, const int *off,
+                                                         unsigned *arrive, unsigned units_per_row) {
+    const int s = rank_begin + blockIdx.x, N = D.N;
+    if (!W.plan_ok[s]) return;                      // step skipped: nothing was sent
+    const int p = threadIdx.x;
+    if (p < N) {
+        const int rows = off[(size_t)s * (N + 1) + p + 1] - off[(size_t)s * (N + 1) + p];
+        if (rows)
+            (void)__hip_atomic_fetch_add(arrive + (size_t)p * N + s, (unsigned)rows * units_per_row,
+                                         __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
+
+// ------------------------------------------------------------------ arrival gate
+// Unordered fabric, receiving side: one wave per rank polls the rank's arrival
+// counters (bounded) until every source has delivered what the exchanged counts
+// promised, which is the paper's receive half ("waits for the completion of all
+// transfers", section Dispatch: the proxy raises a flag once the ImmCounter has
+// reached its expectation).  The receive kernel proper follows in the same
+// stream: it starts after this kernel has ended, with clean caches, so everything
+// the counters vouched for (written through to memory before they advanced) is
+// what it reads.  Waiting costs one wave per rank instead of a grid of pollers,
+// so senders that run at the same time keep the machine.
+__global__ __launch_bounds__(kWave) void arrival_gate_kernel(Dims D, Tables W, int rank_begin,
+                                                             const unsigned *arrive, const unsigned *expect,
+                                                             int *gate) {
+    const int r = rank_begin + blockIdx.x, N = D.N;
+    if (!W.plan_ok[r]) return;                      // step skipped: the receive kernel leaves on plan_ok too
+    const bool ok = wave_wait_counters(arrive + (size_t)r * N, expect + (size_t)r * N, 0u, N, D.spin_limit);
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");     // pairs with the senders' release adds
+    if (threadIdx.x == 0) {
+        gate[r] = ok ? 1 : 0;
+        if (!ok) latch_status(W.status, FL_STATUS_TIMEOUT);
+    }
+}
+
 // ------------------------------------------------------------------ dispatch: unpack
 // Receiver half at rank d.  A block takes a chunk of received rows, waits
 // (bounded) for the arrival counters of the sources those rows came from, and
 // writes every row once per local expert that wants it, at
 //   base_x[d][local expert][source] + rank carried in the sidecar,
 // which is the (expert, source rank, token) order of the grouped layout.
+//
+// FENCED (unordered fabric): the kernel may have been started before any payload
+// exists, on a grid that is a fraction of the machine, so a block walks many
+// chunks.  It keeps the set of sources it has seen complete: a chunk whose
+// sources are all in the set costs no poll; otherwise one wave polls the
+// counters of ALL sources at once (one load per lane), waits until the chunk's
+// own sources are complete, and invalidates the caches once, because it is about
+// to rely on arrivals it had not seen before.  That is the whole visibility
+// rule: payload and sidecar of a source are read only after its counter was
+// seen complete and the caches were invalidated after that observation (a line
+// fetched earlier, for a neighbouring row, may hold this source's bytes from
+// before they landed; a line fetched later cannot).  The chunk's first payload
+// loads are issued before its sidecars are decoded, so a chunk costs one memory
+// round trip, not four.
 template <bool FENCED, bool PRIVATE>   // PRIVATE: the receive buffer has private slots (P > 0)
 __global__ __launch_bounds__(kCopyThreads) void dispatch_unpack_kernel(
     Dims D, Tables W, int rank_begin, char *__restrict__ expert_x,
-    float *__restrict__ expert_scales, int *__restrict__ tokens_per_expert, int rows_per_block) {
+    float *__restrict__ expert_scales, int *__restrict__ tokens_per_expert, int rows_per_block,
+    const int *__restrict__ gate /* [N] or null: a gate kernel's verdict, 0 = its wait gave up */) {
     const int d = rank_begin + blockIdx.y, tid = threadIdx.x, N = D.N, El = D.El, K = D.K;
     __shared__ int off[FL_MAX_RANKS + 1];
     __shared__ int dst_rows[kMaxRowsPerBlock][FL_MAX_TOPK];
     __shared__ int dst_cnt[kMaxRowsPerBlock];
     __shared__ int src_phys[kMaxRowsPerBlock];      // with private slots: buffer row of each received row
     __shared__ int timed_out;
+    __shared__ unsigned long long seen_pub;         // FENCED: wave 0 publishes the set of complete sources
     if (!W.plan_ok[d]) return;
+    if (gate && !gate[d]) return;                   // the arrival wait timed out (status already latched)
     if (blockIdx.x == 0)
         for (int j = tid; j < El; j += kCopyThreads)
             tokens_per_expert[(size_t)d * El + j] = W.G[(size_t)d * El + j];
@@ -477,47 +538,52 @@ __global__ __launch_bounds__(kCopyThreads) void dispatch_unpack_kernel(
     const int nvec = (int)(D.Be / 16);
     const bool scales_as_vectors = D.scales_per_row > 0 && D.scales_per_row % 4 == 0;
     const int rowvec = nvec + (scales_as_vectors ? D.scales_per_row / 4 : 0);
+    unsigned long long seen = 0;                    // FENCED: sources seen complete (same in every thread)
+    unsigned my_expect = 0;                         // FENCED, wave 0: lane i holds what source i must deliver
+    if (FENCED && tid < N) my_expect = W.expect_disp[(size_t)d * N + tid];
     // capacities are upper bounds, so the grid may be smaller than the rows in use
     for (int r0 = blockIdx.x * rows_per_block; r0 < total; r0 += gridDim.x * rows_per_block) {
         const int r1 = min(r0 + rows_per_block, total);
         const int s0 = seg_of(off, N, r0), s1 = seg_of(off, N, r1 - 1);
-        if (tid < kWave) {
+        if (FENCED) {
+            const unsigned long long range = ((s1 - s0 == 63) ? ~0ull : ((1ull << (s1 - s0 + 1)) - 1)) << s0;
+            if (tid < kWave) {
+                if (range & ~seen) {                // uniform: every thread holds the same `seen`
+                    long long spins = 0;
+                    for (;;) {
+                        bool ok = false;
+                        if (tid < N) ok = (int)(ld_relaxed(W.arrive_disp + (size_t)d * N + tid) - my_expect) >= 0;
+                        seen |= __ballot(ok);
+                        if (!(range & ~seen)) break;
+                        if (++spins > D.spin_limit) {
+                            if (tid == 0) { timed_out = 1; latch_status(W.status, FL_STATUS_TIMEOUT); }
+                            break;
+                        }
+                        __builtin_amdgcn_s_sleep(64);
+                    }
+                    acquire_payload<FENCED>();      // arrivals not relied on before: drop what the caches hold
+                }
+                if (tid == 0) seen_pub = seen;
+            }
+        } else if (tid < kWave) {
             if (!wave_wait_counters(W.arrive_disp + (size_t)d * N + s0,
                                     W.expect_disp + (size_t)d * N + s0, 0u, s1 - s0 + 1,
                                     D.spin_limit)) {
                 if (tid == 0) { timed_out = 1; latch_status(W.status, FL_STATUS_TIMEOUT); }
             }
-            acquire_payload<FENCED>();
         }
         __syncthreads();
         if (timed_out) return;
-        if (tid < r1 - r0) {                   // plan of one received row: its expert-major rows
-            const int r = r0 + tid;
-            const int s = seg_of(off, N, r);
-            int phys = r;
-            if (PRIVATE) {
-                phys = recv_buffer_row(N, D.P, s, r - off[s], W.recv_shared_off[(size_t)d * N + s]);
-                src_phys[tid] = phys;
-            }
-            const unsigned *meta = W.recv_meta + ((size_t)d * D.recv_rows + phys) * D.MW;
-            int n = 0;
-            for (int k = 0; k < K; ++k) {
-                const unsigned m = meta[k];
-                if (m == kNoEntry) break;
-                const int j = (int)(m >> 24), i = (int)(m & 0xFFFFFFu);
-                dst_rows[tid][n++] = W.base_x[((size_t)d * El + j) * N + s] + i;
-            }
-            dst_cnt[tid] = n;
-        }
-        __syncthreads();
+        if (FENCED) seen = seen_pub;
         // e4m3: when the scales of a row are a whole number of 16-byte vectors they are
         // moved by the same loop (the vectors after the code bytes go to expert_scales)
         const int chunk = (r1 - r0) * rowvec;
-        for (int b = tid; b < chunk; b += 4 * kCopyThreads) {
-            v4u val[4];
-            int row[4], col[4];
+        // U loads per thread in flight.  A full grid keeps the memory system busy with 4; the
+        // capped grid of polling receivers has fewer waves per compute unit and needs 8.
+        constexpr int U = FENCED ? 8 : 4;
+        auto load_batch = [&](int b, v4u *val, int *row, int *col) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
+            for (int i = 0; i < U; ++i) {
                 const int v = b + i * kCopyThreads;
                 if (v < chunk) {
                     row[i] = v / rowvec;
@@ -526,8 +592,30 @@ __global__ __launch_bounds__(kCopyThreads) void dispatch_unpack_kernel(
                     val[i] = ld_stream((const v4u *)(recv + (size_t)pr * D.Bw) + col[i]);
                 }
             }
+        };
+        auto plan_rows = [&]() {
+            if (tid < r1 - r0) {               // plan of one received row: its expert-major rows
+                const int r = r0 + tid;
+                const int s = seg_of(off, N, r);
+                int phys = r;
+                if (PRIVATE) {
+                    phys = recv_buffer_row(N, D.P, s, r - off[s], W.recv_shared_off[(size_t)d * N + s]);
+                    src_phys[tid] = phys;
+                }
+                const unsigned *meta = W.recv_meta + ((size_t)d * D.recv_rows + phys) * D.MW;
+                int n = 0;
+                for (int k = 0; k < K; ++k) {
+                    const unsigned m = meta[k];
+                    if (m == kNoEntry) break;
+                    const int j = (int)(m >> 24), i = (int)(m & 0xFFFFFFu);
+                    dst_rows[tid][n++] = W.base_x[((size_t)d * El + j) * N + s] + i;
+                }
+                dst_cnt[tid] = n;
+            }
+        };
+        auto store_batch = [&](int b, const v4u *val, const int *row, const int *col) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
+            for (int i = 0; i < U; ++i) {
                 const int v = b + i * kCopyThreads;
                 if (v < chunk) {
                     const int n = dst_cnt[row[i]];
@@ -540,6 +628,29 @@ __global__ __launch_bounds__(kCopyThreads) void dispatch_unpack_kernel(
                                                                   D.scales_per_row) + (col[i] - nvec), val[i]);
                     }
                 }
+            }
+        };
+        if (FENCED && !PRIVATE) {
+            // the first batch's loads go out before the sidecars are decoded: a chunk then
+            // costs one memory round trip instead of three in a row
+            v4u val[U];
+            int row[U], col[U];
+            load_batch(tid, val, row, col);
+            plan_rows();
+            __syncthreads();
+            store_batch(tid, val, row, col);
+            for (int b = tid + U * kCopyThreads; b < chunk; b += U * kCopyThreads) {
+                load_batch(b, val, row, col);
+                store_batch(b, val, row, col);
+            }
+        } else {
+            plan_rows();
+            __syncthreads();
+            for (int b = tid; b < chunk; b += U * kCopyThreads) {
+                v4u val[U];
+                int row[U], col[U];
+                load_batch(b, val, row, col);
+                store_batch(b, val, row, col);
             }
         }
         if (D.scales_per_row && !scales_as_vectors) {   // odd scale counts: element by element
@@ -582,7 +693,7 @@ __global__ __launch_bounds__(kCopyThreads) void combine_pack_kernel(
     if (tid <= N) off[tid] = W.cs_off[(size_t)d * (N + 1) + tid];
     __syncthreads();
     const int nvec = (int)(D.Bc / 16);
-    if (PUSH && !FENCED && blockIdx.x == 0)
+    if (PUSH && !FENCED && (D.flags & FL_FLAG_STREAM_ORDERED) && blockIdx.x == 0)
         announce_transfers(off, W.arrive_comb, (unsigned)nvec, d, N, tid, kCopyThreads);
     const char *yd = expert_y + (size_t)d * D.expert_cap * D.Bc;
     // capacities are upper bounds, so the grid may be smaller than the rows in use
@@ -655,7 +766,7 @@ __global__ __launch_bounds__(kCopyThreads) void combine_partial_pack_kernel(
     if (tid <= N) off[tid] = W.recv_off[(size_t)d * (N + 1) + tid];
     __syncthreads();
     const int nvec = (int)(D.Bc / 16);
-    if (PUSH && !FENCED && blockIdx.x == 0)
+    if (PUSH && !FENCED && (D.flags & FL_FLAG_STREAM_ORDERED) && blockIdx.x == 0)
         announce_transfers(off, W.arrive_comb, (unsigned)nvec, d, N, tid, kCopyThreads);
     const char *yd = expert_y + (size_t)d * D.expert_cap * D.Bc;
     for (int r0 = blockIdx.x * rows_per_block; r0 < total; r0 += gridDim.x * rows_per_block) {
@@ -793,17 +904,47 @@ constexpr int kReduceMaxThreads = 1024;
 template <bool FENCED, bool PARTIAL>
 __global__ __launch_bounds__(kReduceMaxThreads, 7) void combine_reduce_kernel(
     Dims D, Tables W, int rank_begin, const float *__restrict__ weights, char *__restrict__ out,
-    const int *__restrict__ num_tokens) {
+    const int *__restrict__ num_tokens, const int *__restrict__ gate /* as in dispatch_unpack_kernel */) {
     const int s = rank_begin + blockIdx.y, tid = threadIdx.x, N = D.N, K = D.K;
-    __shared__ int pos[FL_MAX_TOPK];
-    __shared__ float w[FL_MAX_TOPK];
+    // two sets of positions and weights: while the block sums one token, wave 1 already
+    // fetches the next one's (a block only walks several tokens when the grid is smaller
+    // than the token count, as it is for polling receivers in unordered mode)
+    __shared__ int pos[2][FL_MAX_TOPK];
+    __shared__ float w[2][FL_MAX_TOPK];
+    __shared__ int n_shares[2];
     __shared__ int timed_out;
-    __shared__ int n_shares;
     if (!W.plan_ok[s]) return;
+    if (gate && !gate[s]) return;
     const int Ts = num_tokens[s];
     if ((int)blockIdx.x >= Ts) return;
     if (tid == 0) timed_out = 0;
     __syncthreads();
+    const bool fetcher = tid >= kWave && tid < 2 * kWave;     // wave 1
+    const int k = tid - kWave;
+    int pf_pos = -1;
+    float pf_w = 1.0f;
+    // token t's row positions (and weights): the load, then, once it has landed, the LDS copy
+    auto fetch = [&](int t) {
+        if (k >= K) { pf_pos = -1; return; }
+        const size_t pair = ((size_t)s * D.T + t) * K + k;
+        if (PARTIAL) pf_pos = W.send_row[pair];               // share rows: first k of each expert rank
+        else { pf_pos = W.comb_pos[pair]; pf_w = weights[pair]; }
+    };
+    auto publish = [&](int buf) {
+        if (PARTIAL) {                                        // compacted in k order, weight 1: an exact add
+            const unsigned long long have = __ballot(pf_pos >= 0);
+            if (pf_pos >= 0) {
+                const int at = __popcll(have & ((1ull << k) - 1));
+                pos[buf][at] = pf_pos;
+                w[buf][at] = 1.0f;
+            }
+            if (k == 0) n_shares[buf] = __popcll(have);
+        } else if (k < K) {
+            pos[buf][k] = pf_pos;
+            w[buf][k] = pf_w;
+        }
+    };
+    if (fetcher) { fetch(blockIdx.x); publish(0); }
     if (tid < kWave) {
         if (!wave_wait_counters(W.arrive_comb + (size_t)s * N, W.expect_comb + (size_t)s * N, 0u, N,
                                 D.spin_limit)) {
@@ -811,37 +952,26 @@ __global__ __launch_bounds__(kReduceMaxThreads, 7) void combine_reduce_kernel(
         }
         acquire_payload<FENCED>();
     }
+    __syncthreads();
+    if (timed_out) return;
     const char *recv = W.bufA + (size_t)s * D.bufA_rank_bytes;
     const int nvec = (int)(D.Bc / 16);
     const int kt = D.tune_reduce ? D.tune_reduce : K;
     // one token per block unless the grid was made smaller than the token count
+    int cur = 0;
     for (int t = blockIdx.x; t < Ts; t += gridDim.x) {
-        if (PARTIAL) {
-            if (tid >= kWave && tid < 2 * kWave) {     // wave 1 compacts the token's share rows
-                const int k = tid - kWave;
-                const int p = k < K ? W.send_row[((size_t)s * D.T + t) * K + k] : -1;
-                const unsigned long long have = __ballot(p >= 0);
-                if (p >= 0) {
-                    const int at = __popcll(have & ((1ull << k) - 1));
-                    pos[at] = p;
-                    w[at] = 1.0f;
-                }
-                if (k == 0) n_shares = __popcll(have);
-            }
-        } else if (tid >= kWave && tid < kWave + K) {
-            const int k = tid - kWave;
-            pos[k] = W.comb_pos[((size_t)s * D.T + t) * K + k];
-            w[k] = weights[((size_t)s * D.T + t) * K + k];
-        }
-        __syncthreads();
-        if (timed_out) return;
+        const int next = t + gridDim.x;
+        if (fetcher && next < Ts) fetch(next);                // in flight while the rows are summed
         v4u *o = (v4u *)(out + ((size_t)s * D.T + t) * D.Bc);
-        if (PARTIAL) reduce_row_counted(recv, pos, w, n_shares, D.Bc, nvec, o, tid);
-        else if (kt >= 8) reduce_row<8>(recv, pos, w, K, D.Bc, nvec, o, tid);
-        else if (kt >= 4) reduce_row<4>(recv, pos, w, K, D.Bc, nvec, o, tid);
-        else if (kt >= 2) reduce_row<2>(recv, pos, w, K, D.Bc, nvec, o, tid);
-        else reduce_row<1>(recv, pos, w, K, D.Bc, nvec, o, tid);
-        __syncthreads();                       // positions and weights are rewritten for the next token
+        if (PARTIAL) reduce_row_counted(recv, pos[cur], w[cur], n_shares[cur], D.Bc, nvec, o, tid);
+        else if (kt >= 8) reduce_row<8>(recv, pos[cur], w[cur], K, D.Bc, nvec, o, tid);
+        else if (kt >= 4) reduce_row<4>(recv, pos[cur], w[cur], K, D.Bc, nvec, o, tid);
+        else if (kt >= 2) reduce_row<2>(recv, pos[cur], w[cur], K, D.Bc, nvec, o, tid);
+        else reduce_row<1>(recv, pos[cur], w[cur], K, D.Bc, nvec, o, tid);
+        if (next >= Ts) break;
+        if (fetcher) publish(cur ^ 1);
+        __syncthreads();                       // the other set is complete; this one may be rewritten
+        cur ^= 1;
     }
 }
 

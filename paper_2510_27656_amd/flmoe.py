@@ -19,10 +19,11 @@ FL_STATIC_SCRATCH_BYTES = 8 << 20
 FL_STATUS_BAD_INDEX, FL_STATUS_CAPACITY, FL_STATUS_TIMEOUT = 1, 2, 4
 FL_DTYPE_BF16, FL_DTYPE_E4M3_BLOCK128 = 0, 1
 FL_FLAG_ZERO_PAD = 1
-FL_FLAG_UNORDERED_FABRIC = 2
+FL_FLAG_STREAM_ORDERED = 2
 FL_FLAG_PEER_PUSH = 4
 FL_FLAG_PARTIAL_SUMS = 8
-FL_KERNEL_COUNT = 10
+FL_FLAG_PROGRESSIVE_RECV = 16
+FL_KERNEL_COUNT = 14
 
 
 class fl_moe_config(C.Structure):
@@ -273,16 +274,17 @@ class MoEShuffle:
 
     def __init__(self, n_ranks, n_experts, max_tokens, top_k, hidden, dispatch_dtype="bf16",
                  expert_align=1, zero_pad=False, recv_capacity_rows=0, expert_capacity_rows=0,
-                 spin_limit=0, unordered_fabric=False, max_private_rows=0, peer_push=False,
-                 partial_sums=False, device="cuda:0"):
+                 spin_limit=0, stream_ordered=False, max_private_rows=0, peer_push=False,
+                 partial_sums=False, progressive_recv=False, device="cuda:0"):
         self.device = torch.device(device)
         self.cfg = fl_moe_config(
             n_ranks, n_experts, max_tokens, top_k, hidden,
             FL_DTYPE_BF16 if dispatch_dtype == "bf16" else FL_DTYPE_E4M3_BLOCK128,
             expert_align, (FL_FLAG_ZERO_PAD if zero_pad else 0)
-            | (FL_FLAG_UNORDERED_FABRIC if unordered_fabric else 0)
+            | (FL_FLAG_STREAM_ORDERED if stream_ordered else 0)
             | (FL_FLAG_PEER_PUSH if peer_push else 0)
-            | (FL_FLAG_PARTIAL_SUMS if partial_sums else 0),
+            | (FL_FLAG_PARTIAL_SUMS if partial_sums else 0)
+            | (FL_FLAG_PROGRESSIVE_RECV if progressive_recv else 0),
             recv_capacity_rows, expert_capacity_rows, spin_limit, max_private_rows, 0)
         self.partial_sums = bool(partial_sums)
         self.sizes = fl_moe_query_sizes(self.cfg)

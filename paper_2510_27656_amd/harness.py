@@ -21,8 +21,8 @@ def to_device(inp: Inputs, device="cuda:0"):
 
 
 def make_shuffle(inp: Inputs, expert_align=1, zero_pad=False, capacity_factor=None,
-                 spin_limit=0, unordered_fabric=False, max_private_rows=0, peer_push=False,
-                 partial_sums=False, device="cuda:0"):
+                 spin_limit=0, stream_ordered=False, max_private_rows=0, peer_push=False,
+                 partial_sums=False, progressive_recv=False, device="cuda:0"):
     """capacity_factor None = worst-case capacities, else factor x the mean rows per rank."""
     wl = inp.wl
     recv_cap = expert_cap = 0
@@ -34,9 +34,9 @@ def make_shuffle(inp: Inputs, expert_align=1, zero_pad=False, capacity_factor=No
                             dispatch_dtype=wl.dispatch_dtype, expert_align=expert_align,
                             zero_pad=zero_pad, recv_capacity_rows=recv_cap,
                             expert_capacity_rows=expert_cap, spin_limit=spin_limit,
-                            unordered_fabric=unordered_fabric,
+                            stream_ordered=stream_ordered,
                             max_private_rows=max_private_rows, peer_push=peer_push,
-                            partial_sums=partial_sums, device=device)
+                            partial_sums=partial_sums, progressive_recv=progressive_recv, device=device)
 
 
 def row_gain(sh: flmoe.MoEShuffle, gain: torch.Tensor):
@@ -105,10 +105,11 @@ def run_hot_path(sh: flmoe.MoEShuffle, dev, expert_y=None, ready=None):
 
 def run_step_two_streams(sh: flmoe.MoEShuffle, dev, identity=False, send_order=None, expert_y=None,
                          streams=None):
-    """One step with senders and receivers overlapping in time (needs a context created
-    with unordered_fabric=True).  Receive kernels are enqueued on stream A right after
-    the layout, send kernels on stream B: the receivers poll the arrival counters while
-    the fabric copy is still running (or has not started).  Events order only what the
+    """One step with senders and receivers on different streams (not for a context created
+    with stream_ordered=True).  Receive calls are enqueued on stream A right after the
+    layout, send calls on stream B: the receivers' gate kernels (or, with
+    progressive_recv, the receive kernels themselves) poll the arrival counters while
+    the fabric copy is still running or has not started.  Events order only what the
     re-use of the two staging buffers needs.  send_order: list of (rank_begin,
     rank_count) launches for the send calls, default one launch for all ranks."""
     N = sh.N

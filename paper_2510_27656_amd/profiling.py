@@ -7,7 +7,7 @@ than the ones being timed is recognised as stale.
     python -m paper_2510_27656_amd.profiling kernel-trace <kt_kernel_stats.csv> <bench log> <out.md> \\
         --title "workload dsv3_decode" --command "rocprofv3 --kernel-trace ... -- python3 bench.py ..."
     python -m paper_2510_27656_amd.profiling traffic <workload> <fetch csv> <write csv> <counters log> \\
-        [--tag unordered] [--flags "--unordered"]
+        [--tag stream_ordered] [--flags "--stream-ordered"]
     python -m paper_2510_27656_amd.profiling counters <counter csv> <out.md> --title ... --command ...
 
 The counter CSVs are `*_counter_collection.csv` of `rocprofv3 --pmc ... --output-format csv`;

@@ -82,7 +82,8 @@ def test_private_rows_extend_the_receive_buffer():
     (dict(hidden=192, dispatch_dtype=1), flmoe.FL_ERR_ALIGNMENT),
     (dict(dispatch_dtype=7), flmoe.FL_ERR_INVALID_ARG),
     (dict(expert_align=0), flmoe.FL_ERR_INVALID_ARG),
-    (dict(flags=16), flmoe.FL_ERR_INVALID_ARG),
+    (dict(flags=32), flmoe.FL_ERR_INVALID_ARG),
+    (dict(flags=flmoe.FL_FLAG_STREAM_ORDERED | flmoe.FL_FLAG_PROGRESSIVE_RECV), flmoe.FL_ERR_INVALID_ARG),
     (dict(max_tokens=0), flmoe.FL_ERR_INVALID_ARG),
     (dict(max_private_rows=-1), flmoe.FL_ERR_INVALID_ARG),
     (dict(reserved=1), flmoe.FL_ERR_INVALID_ARG),
@@ -122,7 +123,8 @@ def test_large_calls_are_cut_into_rank_groups_small_ones_are_not():
     assert groups(cfg(max_tokens=4096, **dsv3), 32, 0) == 32      # knob 0: never cut
     assert groups(cfg(max_tokens=128, **dsv3), 32, 1) == 1        # tiny target: one rank per launch
     assert groups(cfg(max_tokens=1 << 20, **dsv3), 32) == 1       # never below one rank
-    assert groups(cfg(max_tokens=4096, flags=flmoe.FL_FLAG_UNORDERED_FABRIC, **dsv3), 32) == 32   # not in that mode
+    assert groups(cfg(max_tokens=4096, flags=flmoe.FL_FLAG_STREAM_ORDERED, **dsv3), 32) == 2
+    assert groups(cfg(max_tokens=4096, flags=flmoe.FL_FLAG_PROGRESSIVE_RECV, **dsv3), 32) == 32   # polling receivers: never cut
     # e4m3 dispatch: the combine row (bf16) is the larger one and decides
     assert groups(cfg(max_tokens=4096, dispatch_dtype=flmoe.FL_DTYPE_E4M3_BLOCK128, **dsv3), 32) == 2
     lib = flmoe.lib()

@@ -44,7 +44,10 @@ def check_tables(sh, ref, N):
 
 
 def run_and_compare(inp, align=1, zero_pad=False, capacity_factor=None, ranks_split=False,
-                    unordered=False, private_rows=0, push=False, partial=False, launch_mb=None):
+                    ordering="counters", private_rows=0, push=False, partial=False, launch_mb=None):
+    """ordering: "counters" = the default mode (the arrival counters are the only ordering:
+    announce and gate kernels), "stream" = FL_FLAG_STREAM_ORDERED, "progressive" =
+    FL_FLAG_PROGRESSIVE_RECV."""
     wl = inp.wl
     N, T = wl.n_ranks, wl.tokens
     ref = oracle_step(inp, align, zero_pad=True, partial=partial)
@@ -52,7 +55,8 @@ def run_and_compare(inp, align=1, zero_pad=False, capacity_factor=None, ranks_sp
         ref.out = ref.out_partial
     dev = harness.to_device(inp)
     sh = harness.make_shuffle(inp, expert_align=align, zero_pad=zero_pad, partial_sums=partial,
-                              capacity_factor=capacity_factor, unordered_fabric=unordered,
+                              capacity_factor=capacity_factor, stream_ordered=ordering == "stream",
+                              progressive_recv=ordering == "progressive",
                               max_private_rows=private_rows, peer_push=push)
     try:
         if launch_mb is not None:        # payload per launch above which a call is cut into rank groups
@@ -156,11 +160,14 @@ def test_parity_with_padding(align, zero_pad):
     sh.close()
 
 
+@pytest.mark.parametrize("form", ["stream", "progressive"])
 @pytest.mark.parametrize("name", ["ragged_520", "multi_tile", "k16"])
-def test_parity_unordered_fabric_mode(name):
-    """Same results when the counters carry release/acquire (FL_FLAG_UNORDERED_FABRIC)."""
+def test_parity_in_the_other_ordering_modes(name, form):
+    """Same results when the caller orders sends before receives itself and the library
+    skips the announce and gate kernels (FL_FLAG_STREAM_ORDERED), and with receive
+    kernels that poll themselves (FL_FLAG_PROGRESSIVE_RECV)."""
     inp = wlmod.make_inputs(CASES[name]())
-    sh, _, _ = run_and_compare(inp, unordered=True)
+    sh, _, _ = run_and_compare(inp, ordering=form)
     sh.close()
 
 
@@ -195,7 +202,8 @@ def test_repeated_steps_are_deterministic_and_counters_monotone():
         sh.close()
 
 
-@pytest.mark.parametrize("kw", [dict(), dict(unordered_fabric=True), dict(peer_push=True, partial_sums=True)])
+@pytest.mark.parametrize("kw", [dict(), dict(stream_ordered=True), dict(peer_push=True, partial_sums=True),
+                                dict(progressive_recv=True)])
 def test_counters_wrap_around_32_bits(kw):
     """The arrival and expectation counters are monotone 32-bit words compared
     wrap-safely: set just below 2^32 (consistently, as after very many steps), the
@@ -317,7 +325,7 @@ def test_parity_e4m3_dispatch_every_finite_bf16_value():
     sh.close()
 
 
-@pytest.mark.parametrize("kw", [dict(), dict(peer_push=True), dict(unordered_fabric=True)])
+@pytest.mark.parametrize("kw", [dict(), dict(peer_push=True), dict(stream_ordered=True)])
 def test_parity_e4m3_dispatch_blocks_with_inf_and_nan(kw):
     """Blocks that hold Inf or NaN (every non-finite bf16 pattern, quiet and signalling,
     both signs): codes and scales equal the oracle's, code for code and scale for scale.
@@ -475,13 +483,13 @@ def test_parity_random_shapes():
         inp = wlmod.make_inputs(wl)
         print(f"trial {trial}: N={N} El={El} K={K} T={T} H={H} fp8={fp8}", flush=True)
         sh, _, _ = run_and_compare(inp, align=int(rng.choice([1, 1, 4, 7])), zero_pad=True,
-                                   unordered=bool(trial % 3 == 0))
+                                   ordering=["counters", "stream", "progressive"][trial % 3])
         sh.close()
 
 
 def test_parity_random_shapes_and_mode_combinations():
     """Forty more seeded random shapes, each with a random combination of the optional
-    modes: private slots, peer push, partial sums, unordered fabric, calls split by rank."""
+    modes: private slots, peer push, partial sums, the three ordering modes, calls split by rank."""
     rng = np.random.default_rng(4242)
     for trial in range(40):
         N = int(rng.choice([1, 2, 3, 4, 8, 16, 32]))
@@ -492,7 +500,7 @@ def test_parity_random_shapes_and_mode_combinations():
         fp8 = trial % 4 == 3
         H = int(rng.integers(1, 7)) * 128 if fp8 else int(rng.integers(1, 200)) * 8
         modes = dict(private_rows=int(rng.choice([0, 0, 1, 5, 40, 1000])), push=bool(rng.integers(2)),
-                     partial=bool(rng.integers(2)), unordered=bool(rng.integers(2)),
+                     partial=bool(rng.integers(2)), ordering=["counters", "stream", "progressive"][int(rng.integers(3))],
                      ranks_split=bool(N >= 2 and rng.integers(2)))
         wl = wlmod.custom(f"mix{trial}", N, E, T, H, K, seed=5000 + trial, ragged=bool(trial % 2),
                           dispatch_dtype="e4m3" if fp8 else "bf16")
@@ -502,14 +510,15 @@ def test_parity_random_shapes_and_mode_combinations():
         sh.close()
 
 
-@pytest.mark.parametrize("kw", [dict(), dict(unordered=True), dict(push=True), dict(ranks_split=True),
+@pytest.mark.parametrize("kw", [dict(), dict(ordering="stream"), dict(push=True), dict(ranks_split=True),
                                 dict(partial=True, private_rows=20), dict(fp8=True, align=4),
-                                dict(unordered=True, push=True, partial=True, fp8=True)])
+                                dict(ordering="progressive"),
+                                dict(ordering="progressive", push=True, partial=True, fp8=True)])
 def test_large_calls_are_issued_as_several_launches_over_rank_groups(kw):
     """A call that moves several times the per-launch target enqueues its kernels once
     per group of ranks; here the target is set to 1 MiB so that a small step is cut into
-    one launch per rank (contexts with the unordered flag are never cut).  Same results,
-    and the launch counts show the cut happened."""
+    one launch per rank (contexts whose receive kernels poll themselves are never cut).
+    Same results, and the launch counts show the cut happened."""
     kw = dict(kw)
     fp8 = kw.pop("fp8", False)
     wl = wlmod.custom("groups", 8, 32, 128, 1024, 4, seed=77, ragged=True,
@@ -526,7 +535,7 @@ def test_large_calls_are_issued_as_several_launches_over_rank_groups(kw):
         after = flmoe.fl_moe_profile_read(sh.ctx)
         assert sh.status() == 0
         launches = {k: after[k][1] - before[k][1] for k in after}
-        cut = 1 if kw.get("unordered") else wl.n_ranks      # unordered contexts are never cut
+        cut = 1 if kw.get("ordering") == "progressive" else wl.n_ranks
         assert launches["route_layout_kernel"] == 1
         assert launches["dispatch_unpack_kernel"] == cut
         assert launches["combine_reduce_kernel"] == cut
@@ -543,7 +552,7 @@ def test_large_calls_are_issued_as_several_launches_over_rank_groups(kw):
 
 
 @pytest.mark.parametrize("kw", [dict(), dict(push=True), dict(partial=True, private_rows=50),
-                                dict(unordered=True)])
+                                dict(ordering="stream"), dict(ordering="progressive")])
 def test_every_token_to_one_rank_is_served_by_the_row_loops(kw):
     """Grids are sized for twice the rows uniform routing would bring; here one rank
     hosts every chosen expert and receives N*T rows and N*T*K pairs, several times
@@ -624,19 +633,21 @@ def test_hip_graph_replay_with_new_inputs():
         sh.close()
 
 
-def test_unordered_mode_with_e4m3_dispatch():
+@pytest.mark.parametrize("form", ["stream", "progressive"])
+def test_other_ordering_modes_with_e4m3_dispatch(form):
     inp = wlmod.make_inputs(FP8_CASES["fp8_small"]())
-    sh, _, _ = run_and_compare(inp, unordered=True, zero_pad=True, align=4)
+    sh, _, _ = run_and_compare(inp, ordering=form, zero_pad=True, align=4)
     sh.close()
 
 
 # ------------------------------------------------------------------ senders and receivers overlapping in time
+@pytest.mark.parametrize("progressive", [False, True])
 @pytest.mark.parametrize("name,shuffled,push", [("ragged_520", False, False), ("ragged_520", True, False),
                                                 ("overlap_7168", False, False), ("overlap_7168", True, False),
                                                 ("dsv3_decode", False, False),
                                                 ("ragged_520", True, True), ("overlap_7168", False, True),
                                                 ("dsv3_decode", True, True)])
-def test_unordered_fabric_with_concurrent_send_and_receive(name, shuffled, push):
+def test_concurrent_send_and_receive_on_two_streams(name, shuffled, push, progressive):
     if name == "overlap_7168":
         wl = wlmod.custom("overlap_7168", 8, 64, 128, 7168, 8, seed=61)
     elif name == "dsv3_decode":
@@ -647,8 +658,8 @@ def test_unordered_fabric_with_concurrent_send_and_receive(name, shuffled, push)
     N = wl.n_ranks
     ref = oracle_step(inp)
     dev = harness.to_device(inp)
-    sh = harness.make_shuffle(inp, unordered_fabric=True, capacity_factor=2.0 if N >= 8 else None,
-                              peer_push=push)
+    sh = harness.make_shuffle(inp, capacity_factor=2.0 if N >= 8 else None,
+                              peer_push=push, progressive_recv=progressive)
     try:
         order = None
         if shuffled:      # one launch per sender, in a seeded random order
@@ -691,12 +702,12 @@ def test_parity_with_private_slots(name, P):
     sh.close()
 
 
-def test_private_slots_with_e4m3_and_unordered_fabric():
+def test_private_slots_with_e4m3_and_the_other_ordering_modes():
     inp = wlmod.make_inputs(FP8_CASES["fp8_small"]())
-    sh, _, _ = run_and_compare(inp, private_rows=9, unordered=True)
+    sh, _, _ = run_and_compare(inp, private_rows=9, ordering="stream")
     sh.close()
     inp = wlmod.make_inputs(CASES["multi_tile"]())
-    sh, _, _ = run_and_compare(inp, private_rows=300, unordered=True, ranks_split=True)
+    sh, _, _ = run_and_compare(inp, private_rows=300, ordering="progressive", ranks_split=True)
     sh.close()
 
 
@@ -789,8 +800,9 @@ def test_parity_peer_push_small(name):
     sh.close()
 
 
-@pytest.mark.parametrize("kw", [dict(unordered=True), dict(private_rows=7), dict(ranks_split=True),
-                                dict(unordered=True, private_rows=1000, ranks_split=True),
+@pytest.mark.parametrize("kw", [dict(ordering="stream"), dict(private_rows=7), dict(ranks_split=True),
+                                dict(ordering="progressive"),
+                                dict(ordering="stream", private_rows=1000, ranks_split=True),
                                 dict(capacity_factor=2.0)])
 def test_parity_peer_push_with_the_other_modes(kw):
     inp = wlmod.make_inputs(CASES["ragged_520"]())
@@ -799,10 +811,10 @@ def test_parity_peer_push_with_the_other_modes(kw):
 
 
 @pytest.mark.parametrize("name", list(FP8_CASES))
-@pytest.mark.parametrize("unordered", [False, True])
-def test_parity_peer_push_e4m3(name, unordered):
+@pytest.mark.parametrize("ordering", ["counters", "stream", "progressive"])
+def test_parity_peer_push_e4m3(name, ordering):
     inp = wlmod.make_inputs(FP8_CASES[name]())
-    sh, _, _ = run_and_compare(inp, push=True, unordered=unordered)
+    sh, _, _ = run_and_compare(inp, push=True, ordering=ordering)
     sh.close()
 
 
@@ -859,8 +871,9 @@ def test_parity_partial_sums_small(name):
     sh.close()
 
 
-@pytest.mark.parametrize("kw", [dict(unordered=True), dict(private_rows=7), dict(ranks_split=True),
-                                dict(push=True), dict(push=True, unordered=True, private_rows=3),
+@pytest.mark.parametrize("kw", [dict(ordering="stream"), dict(private_rows=7), dict(ranks_split=True),
+                                dict(ordering="progressive"),
+                                dict(push=True), dict(push=True, ordering="stream", private_rows=3),
                                 dict(capacity_factor=2.0, ranks_split=True, push=True)])
 def test_parity_partial_sums_with_the_other_modes(kw):
     inp = wlmod.make_inputs(CASES["ragged_520"]())
@@ -963,7 +976,7 @@ def test_chunked_steps_give_the_same_combined_output(chunk):
 
 # ------------------------------------------------------------------ tokens the caller quantised itself
 @pytest.mark.parametrize("name", list(FP8_CASES))
-@pytest.mark.parametrize("kw", [dict(), dict(peer_push=True), dict(unordered_fabric=True, peer_push=True),
+@pytest.mark.parametrize("kw", [dict(), dict(peer_push=True), dict(stream_ordered=True, peer_push=True),
                                 dict(partial_sums=True, max_private_rows=5)])
 def test_dispatch_of_ready_made_e4m3_tokens(name, kw):
     """fl_moe_dispatch_send_e4m3 (section Kernel Microbenchmarks: the dispatched token is
@@ -1033,7 +1046,7 @@ def small_shuffle(spin_limit=0, **kw):
     return inp, dev, sh
 
 
-@pytest.mark.parametrize("kw", [dict(), dict(peer_push=True), dict(unordered_fabric=True, max_private_rows=4)])
+@pytest.mark.parametrize("kw", [dict(), dict(peer_push=True), dict(stream_ordered=True, max_private_rows=4)])
 def test_bad_expert_id_skips_the_step_everywhere(kw):
     inp, dev, sh = small_shuffle(**kw)
     try:
@@ -1073,7 +1086,7 @@ def test_bad_expert_id_skips_the_step_everywhere(kw):
 
 
 @pytest.mark.parametrize("kw", [dict(), dict(peer_push=True), dict(partial_sums=True, max_private_rows=2),
-                                dict(unordered_fabric=True, peer_push=True)])
+                                dict(stream_ordered=True, peer_push=True)])
 def test_capacity_overflow_is_reported_not_written(kw):
     inp = wlmod.make_inputs(CASES["ragged_520"]())
     dev = harness.to_device(inp)
@@ -1164,8 +1177,10 @@ def test_layout_split_over_two_streams_meets_in_the_exchange():
         sh.close()
 
 
-def test_withheld_arrival_counter_times_out_then_recovers():
-    inp, dev, sh = small_shuffle(spin_limit=200)
+@pytest.mark.parametrize("kw", [dict(), dict(stream_ordered=True),
+                                dict(progressive_recv=True)])
+def test_withheld_arrival_counter_times_out_then_recovers(kw):
+    inp, dev, sh = small_shuffle(spin_limit=200, **kw)
     try:
         ref = oracle_step(inp)
         sh.layout(dev["indices"], dev["num_tokens"])

@@ -17,6 +17,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0
+WRITES = {}          # per kernel: bytes written per step (filled by algorithmic_bytes)
 
 
 def algorithmic_bytes(wl, ttot, D, P, sizes, push=False, partial=False, ready=False):
@@ -47,6 +48,13 @@ def algorithmic_bytes(wl, ttot, D, P, sizes, push=False, partial=False, ready=Fa
         del k["fabric_copy_kernel(dispatch)"], k["fabric_copy_kernel(combine)"]
     if wl.dispatch_dtype != "bf16" and not ready:
         k["dispatch_pack_e4m3_kernel"] = k.pop("dispatch_pack_kernel")
+    # bytes each kernel writes (the rest it reads): for the one-directional ceilings
+    WRITES.clear()
+    WRITES.update({"dispatch_pack_kernel": D * Bw, "dispatch_pack_e4m3_kernel": D * Bw,
+                   "fabric_copy_kernel(dispatch)": D * Bw, "dispatch_unpack_kernel": P * Be,
+                   "combine_pack_kernel": P * Bc, "combine_partial_pack_kernel": D * Bc,
+                   "fabric_copy_kernel(combine)": (D if partial else P) * Bc,
+                   "combine_reduce_kernel": ttot * Bc})
     dispatch = sum(v for n, v in k.items() if n.startswith(("dispatch", "fabric_copy_kernel(d")))
     combine = sum(v for n, v in k.items() if n.startswith(("combine", "fabric_copy_kernel(c")))
     return k, dispatch, combine
@@ -391,7 +399,25 @@ def main():
         ce.append(e)
     torch.cuda.synchronize()
     copy_gbps = 2 * (1 << 30) / (float(np.median([a.elapsed_time(b) for a, b in ce[2:]])) * 1e-3) / 1e9
+    # one-directional ceilings, same launch shape: write-only (fill) and read-only, 1 GiB each
+    sink = torch.zeros(4, dtype=torch.int32, device="cuda:0")
+
+    def ceiling(fn):
+        evs = []
+        for i in range(12):
+            e = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+            e[0].record(); fn(); e[1].record()
+            evs.append(e)
+        torch.cuda.synchronize()
+        return (1 << 30) / (float(np.median([a.elapsed_time(b) for a, b in evs[2:]])) * 1e-3) / 1e9
+    write_gbps = ceiling(lambda: flmoe.fl_moe_debug_fill(flush_dst, 1 << 30))
+    read_gbps = ceiling(lambda: flmoe.fl_moe_debug_read(flush_src, 1 << 30, sink))
     del flush_src, flush_dst
+    # A kernel that reads r and writes w bytes cannot beat r / read ceiling + w / write ceiling
+    # (for r = w this is the measured copy ceiling to within a few percent): each kernel's
+    # time against that bound
+    rw_bound_us = {k: ((per_kernel[k] - WRITES[k]) / read_gbps + WRITES[k] / write_gbps) / 1e3 / kern_launches[k]
+                   for k in kern_us if k in per_kernel and k in WRITES}
 
     # The same step captured once in a HIP graph and replayed (the five calls only
     # enqueue kernels); what it saves is host launch work, which shows on small shapes.
@@ -517,6 +543,8 @@ def main():
         "cold_step_us": round(cold_us, 1),
         "cold_gbps": round(bytes_step / (cold_us * 1e-6) / 1e9, 1),
         "copy_ceiling_gbps": round(copy_gbps, 1),
+        "write_ceiling_gbps": round(write_gbps, 1), "read_ceiling_gbps": round(read_gbps, 1),
+        "kernel_frac_of_read_write_bound": {k: round(v / kern_us[k], 4) for k, v in rw_bound_us.items()},
         "frac_of_copy_ceiling": round(value / copy_gbps, 4),
         "latency_us": latency_us,
         "call_us": {k: round(v, 1) for k, v in call_us.items()},

@@ -387,7 +387,10 @@ int fl_moe_debug_views(fl_moe_ctx *ctx, fl_moe_debug_view *out /*host*/);
  * groups of about this size (default 860; 0 = always one launch per kernel;
  * contexts with FL_FLAG_PROGRESSIVE_RECV are never cut), knob 7 = eighths of the
  * machine's resident-workgroup slots the polling receive kernels of
- * FL_FLAG_PROGRESSIVE_RECV may take (default 3).  A value of -1 restores a knob's default. */
+ * FL_FLAG_PROGRESSIVE_RECV may take (default 3), knob 8 = order in which the fabric kernel
+ * takes the destinations of a sender (0 = ascending, 1 = descending, 2 = starting with
+ * the sender's right-hand neighbour and wrapping round; a test switch: nothing may depend
+ * on the order in which transfers are carried out).  A value of -1 restores a knob's default. */
 int fl_moe_debug_tune(fl_moe_ctx *ctx, int knob, int value);
 
 /* Diagnostic, host only (no GPU needed): how a payload call over `rank_count` ranks of
@@ -401,6 +404,14 @@ int fl_moe_debug_launch_groups(const fl_moe_config *cfg /*host*/, int rank_count
  * (multiple of 16, both pointers 16-byte aligned).  Used to measure the copy ceiling of the
  * machine and to calibrate hardware byte counters against a known size. */
 int fl_moe_debug_copy(void *dst, const void *src, size_t bytes, void *stream);
+
+/* Diagnostic: the write-only and read-only counterparts of fl_moe_debug_copy, same launch
+ * shape (fill: 16-byte streaming stores of a constant; read: 16-byte streaming loads whose
+ * values are folded and, practically never, written to the 4-byte word `sink`).  They
+ * measure the machine's one-directional ceilings, against which kernels that mostly
+ * write (dispatch pack) or mostly read (combine reduce) are judged. */
+int fl_moe_debug_fill(void *dst, size_t bytes, void *stream);
+int fl_moe_debug_read(const void *src, size_t bytes, void *sink, void *stream);
 
 /* Per-kernel timing with HIP events on the caller's stream.  While enabled,
  * every kernel launch of the shuffle calls is bracketed by an event pair;

@@ -128,6 +128,7 @@ int resolve(const fl_moe_config *c, Dims *D) {
     D->tune_stream_mb = 2560;
     D->tune_grid_pct = 200;
     D->tune_cap8 = 3;
+    D->tune_order = 0;
     {   // a token reaches a given rank with probability 1 - (1 - 1/N)^K when experts are drawn uniformly
         double miss = 1.0;
         for (int k = 0; k < D->K; ++k) miss *= 1.0 - 1.0 / D->N;
@@ -563,6 +564,7 @@ static int dispatch_send_range(fl_moe_ctx *ctx, int rb, int rc, const void *x, c
     A.dst_meta = W.recv_meta; A.dst_meta_rank_stride = D.recv_rows * D.MW;
     A.dst_row_lo = 0;
     A.announce = 0;
+    A.order = D.tune_order;
     A.arrive = W.arrive_disp;
     A.row_bytes = D.Bw; A.waves_per_row = waves_per_row(D.Bw, D.tune_waves);
     const int wpb = kCopyThreads / kWave;
@@ -737,6 +739,7 @@ static int combine_send_range(fl_moe_ctx *ctx, int rb, int rc, const void *exper
     A.dst_meta = nullptr; A.dst_meta_rank_stride = 0;
     A.dst_row_lo = 0;
     A.announce = in_kernel;
+    A.order = D.tune_order;
     A.arrive = W.arrive_comb;
     A.row_bytes = D.Bc; A.waves_per_row = waves_per_row(D.Bc, D.tune_waves);
     const int wpb = kCopyThreads / kWave;
@@ -868,6 +871,7 @@ int fl_moe_debug_tune(fl_moe_ctx *ctx, int knob, int value) {
         case 5: if (value > 1000) return FL_ERR_INVALID_ARG; ctx->D.tune_grid_pct = dflt ? 200 : value; break;
         case 6: ctx->launch_mb = dflt ? kLaunchMiB : value; break;
         case 7: if (value > 8 || value == 0) return FL_ERR_INVALID_ARG; ctx->D.tune_cap8 = dflt ? 3 : value; break;
+        case 8: if (value > 2) return FL_ERR_INVALID_ARG; ctx->D.tune_order = dflt ? 0 : value; break;
         default: return FL_ERR_INVALID_ARG;
     }
     return FL_OK;
@@ -891,6 +895,27 @@ int fl_moe_debug_copy(void *dst, const void *src, size_t bytes, void *stream) {
     if (blocks >= (1ull << 31)) return FL_ERR_INVALID_ARG;
     plain_copy_kernel<<<dim3((unsigned)blocks), dim3(kCopyThreads), 0, (hipStream_t)stream>>>(
         (v4u *)dst, (const v4u *)src, nvec);
+    return launch_status();
+}
+
+int fl_moe_debug_fill(void *dst, size_t bytes, void *stream) {
+    if (!dst || bytes == 0 || bytes % 16 != 0) return FL_ERR_INVALID_ARG;
+    if (!aligned16(dst)) return FL_ERR_ALIGNMENT;
+    const size_t nvec = bytes / 16;
+    const size_t blocks = (nvec + kCopyThreads * 4 - 1) / (kCopyThreads * 4);
+    if (blocks >= (1ull << 31)) return FL_ERR_INVALID_ARG;
+    plain_fill_kernel<<<dim3((unsigned)blocks), dim3(kCopyThreads), 0, (hipStream_t)stream>>>((v4u *)dst, nvec, 0x3C3C3C3Cu);
+    return launch_status();
+}
+
+int fl_moe_debug_read(const void *src, size_t bytes, void *sink, void *stream) {
+    if (!src || !sink || bytes == 0 || bytes % 16 != 0) return FL_ERR_INVALID_ARG;
+    if (!aligned16(src) || ((uintptr_t)sink & 3)) return FL_ERR_ALIGNMENT;
+    const size_t nvec = bytes / 16;
+    const size_t blocks = (nvec + kCopyThreads * 4 - 1) / (kCopyThreads * 4);
+    if (blocks >= (1ull << 31)) return FL_ERR_INVALID_ARG;
+    plain_read_kernel<<<dim3((unsigned)blocks), dim3(kCopyThreads), 0, (hipStream_t)stream>>>(
+        (const v4u *)src, nvec, (unsigned *)sink);
     return launch_status();
 }
 

@@ -346,6 +346,9 @@ struct FabricArgs {
     int waves_per_row;    // 1..16
     int dst_row_lo;       // rows whose target row is below this belong to the private-slot scatter
     int announce;         // stream-ordered mode: this launch also advances arrive[.][s] (announce_transfers)
+    int order;            // test switch: order in which a sender's rows (sorted by destination) are
+                          // taken: 0 = as stored, 1 = last destination first, 2 = starting with the
+                          // sender's right-hand neighbour and wrapping round
 };
 
 // One wave's share of one row: slice `sub` of `G` (vectors v with (v / 64) % G ==
@@ -398,13 +401,22 @@ __global__ __launch_bounds__(kCopyThreads) void fabric_copy_kernel(Dims D, Table
     // The first row's target is fetched together with the two loads above; capacities
     // are upper bounds, so the grid may be smaller than the rows in use and a wave loops.
     int i = wave / G;
-    int2 t = make_int2(0, 0);
-    if (i < A.row_cap) t = A.row_dst[(size_t)s * A.row_cap + i];
-    while (i < total) {
-        if (t.y >= A.dst_row_lo)           // rows below went out with the private-slot scatter
-            fabric_send_row<FENCED, STREAMING>(D, A, s, i, t.x, t.y, sub, lane);
-        i += row_stride;
-        if (i < total) t = A.row_dst[(size_t)s * A.row_cap + i];
+    if (A.order == 0) {
+        int2 t = make_int2(0, 0);
+        if (i < A.row_cap) t = A.row_dst[(size_t)s * A.row_cap + i];
+        while (i < total) {
+            if (t.y >= A.dst_row_lo)       // rows below went out with the private-slot scatter
+                fabric_send_row<FENCED, STREAMING>(D, A, s, i, t.x, t.y, sub, lane);
+            i += row_stride;
+            if (i < total) t = A.row_dst[(size_t)s * A.row_cap + i];
+        }
+    } else {                               // the same rows, visited in another order of destinations
+        const int shift = A.order == 2 ? A.seg_off[(size_t)s * (N + 1) + (s + 1) % N] : 0;
+        for (; i < total; i += row_stride) {
+            const int row = A.order == 1 ? total - 1 - i : (i + shift) % total;
+            const int2 t = A.row_dst[(size_t)s * A.row_cap + row];
+            if (t.y >= A.dst_row_lo) fabric_send_row<FENCED, STREAMING>(D, A, s, row, t.x, t.y, sub, lane);
+        }
     }
     if (!FENCED && A.announce && wave == 0 && ok)
         announce_transfers(A.seg_off + (size_t)s * (N + 1), A.arrive, (unsigned)(A.row_bytes / 16), s, N, lane, kWave);
@@ -989,6 +1001,33 @@ __global__ __launch_bounds__(kCopyThreads) void plain_copy_kernel(v4u *__restric
 #pragma unroll
     for (int i = 0; i < 4; ++i)
         if (base + (size_t)i * kCopyThreads < nvec) st_stream(dst + base + (size_t)i * kCopyThreads, r[i]);
+}
+
+
+// Write-only and read-only companions of plain_copy_kernel, same shape (16 KB per block,
+// four 16-byte accesses per thread): the two one-directional ceilings of the machine,
+// against which kernels that mostly write (dispatch pack) or mostly read (combine
+// reduce) are to be judged.
+__global__ __launch_bounds__(kCopyThreads) void plain_fill_kernel(v4u *__restrict__ dst, size_t nvec,
+                                                                  unsigned value) {
+    const size_t base = (size_t)blockIdx.x * kCopyThreads * 4 + threadIdx.x;
+    const v4u v = {value, value, value, value};
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+        if (base + (size_t)i * kCopyThreads < nvec) st_stream(dst + base + (size_t)i * kCopyThreads, v);
+}
+
+__global__ __launch_bounds__(kCopyThreads) void plain_read_kernel(const v4u *__restrict__ src, size_t nvec,
+                                                                  unsigned *__restrict__ sink) {
+    const size_t base = (size_t)blockIdx.x * kCopyThreads * 4 + threadIdx.x;
+    v4u r[4] = {};
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+        if (base + (size_t)i * kCopyThreads < nvec) r[i] = ld_stream(src + base + (size_t)i * kCopyThreads);
+    unsigned x = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) x ^= r[i].x ^ r[i].y ^ r[i].z ^ r[i].w;
+    if (x == 0x9E3779B9u) *sink = x;      // keeps the loads alive; practically never taken
 }
 
 }  // namespace flmoe

@@ -72,7 +72,7 @@ EXPORTS = ["fl_moe_query_sizes", "fl_moe_create", "fl_moe_destroy", "fl_moe_layo
            "fl_moe_dispatch_recv",
            "fl_moe_combine_send",
            "fl_moe_combine_reduce", "fl_moe_status", "fl_moe_reset", "fl_moe_strerror", "fl_moe_debug_views",
-           "fl_moe_debug_tune", "fl_moe_debug_launch_groups", "fl_moe_debug_copy", "fl_moe_profile_enable", "fl_moe_profile_collect", "fl_moe_profile_read",
+           "fl_moe_debug_tune", "fl_moe_debug_launch_groups", "fl_moe_debug_copy", "fl_moe_debug_fill", "fl_moe_debug_read", "fl_moe_profile_enable", "fl_moe_profile_collect", "fl_moe_profile_read",
            "fl_moe_kernel_name", "fl_moe_build_id"]
 
 _lib = None
@@ -114,6 +114,8 @@ def lib():
         L.fl_moe_debug_tune.argtypes = [vp, i32, i32]
         L.fl_moe_debug_launch_groups.argtypes = [C.POINTER(fl_moe_config), i32, i32, C.POINTER(C.c_int)]
         L.fl_moe_debug_copy.argtypes = [vp, vp, C.c_size_t, vp]
+        L.fl_moe_debug_fill.argtypes = [vp, C.c_size_t, vp]
+        L.fl_moe_debug_read.argtypes = [vp, C.c_size_t, vp, vp]
         L.fl_moe_profile_enable.argtypes = [vp, i32]
         L.fl_moe_profile_collect.argtypes = [vp, vp]
         L.fl_moe_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i64)]
@@ -246,6 +248,14 @@ def fl_moe_debug_launch_groups(cfg: fl_moe_config, rank_count: int, launch_mb: i
 def fl_moe_debug_copy(dst, src, nbytes, stream=None):
     _check(lib().fl_moe_debug_copy(_ptr(dst), _ptr(src), nbytes, _stream(stream)),
            "fl_moe_debug_copy")
+
+
+def fl_moe_debug_fill(dst, nbytes, stream=None):
+    _check(lib().fl_moe_debug_fill(_ptr(dst), nbytes, _stream(stream)), "fl_moe_debug_fill")
+
+
+def fl_moe_debug_read(src, nbytes, sink, stream=None):
+    _check(lib().fl_moe_debug_read(_ptr(src), nbytes, _ptr(sink), _stream(stream)), "fl_moe_debug_read")
 
 
 def fl_moe_build_id() -> str:

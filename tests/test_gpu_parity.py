@@ -666,6 +666,7 @@ def test_concurrent_send_and_receive_on_two_streams(name, shuffled, push, progre
             perm = np.random.default_rng(5).permutation(N)
             order = [(int(r), 1) for r in perm]
         for rep in range(3):
+            flmoe.fl_moe_debug_tune(sh.ctx, 8, rep)    # the fabric takes each sender's destinations in another order
             sh.out.view(torch.int16).fill_(POISON)
             out = harness.run_step_two_streams(sh, dev, wl.expert == "identity", order)
             torch.cuda.synchronize()
@@ -678,6 +679,58 @@ def test_concurrent_send_and_receive_on_two_streams(name, shuffled, push, progre
             for s in range(N):
                 n = inp.num_tokens[s]
                 assert (ob[s, :n] == ref.out[s, :n]).all(), (rep, s)
+        dbg = sh.debug()
+        assert (dbg["arrive_disp"] == dbg["expect_disp"]).all()
+        assert (dbg["arrive_comb"] == dbg["expect_comb"]).all()
+    finally:
+        sh.close()
+
+
+@pytest.mark.parametrize("progressive,steps", [(False, 1200), (True, 800)])
+def test_soak_two_streams_shuffled_senders_every_step_checked(progressive, steps):
+    """Bounded soak of the path where only the arrival counters order senders and
+    receivers: the decode workload, receive calls on one stream, one send call per
+    sender on another in a freshly shuffled order every step, the fabric kernel taking
+    each sender's destinations in a different order from step to step.  The first step
+    is compared with the oracle; every later step must reproduce its expert rows and
+    its combined output bit for bit (outputs are poisoned before each step, so a
+    receiver that ran ahead of its data cannot pass), with a clean status word."""
+    from dataclasses import replace
+    wl = replace(wlmod.WORKLOADS["dsv3_decode"], name="soak", expert="identity")
+    inp = wlmod.make_inputs(wl)
+    N = wl.n_ranks
+    ref = oracle_step(inp)
+    dev = harness.to_device(inp)
+    sh = harness.make_shuffle(inp, capacity_factor=1.5, progressive_recv=progressive)
+    streams = (torch.cuda.Stream(), torch.cuda.Stream())
+    rng = np.random.default_rng(2024)
+    try:
+        first_x = first_out = None
+        for step in range(steps):
+            order = [(int(r), 1) for r in rng.permutation(N)]
+            flmoe.fl_moe_debug_tune(sh.ctx, 8, step % 3)
+            sh.expert_x.view(torch.int16).fill_(POISON)
+            sh.out.view(torch.int16).fill_(POISON)
+            out = harness.run_step_two_streams(sh, dev, send_order=order, expert_y=sh.expert_x,
+                                               streams=streams)
+            if step == 0:
+                torch.cuda.synchronize()
+                assert sh.status() == 0
+                ex, ob = bits(sh.expert_x[:, :ref.stride]), bits(out)
+                for d in range(N):
+                    n = ref.expert_rows[d].shape[0]
+                    assert (ex[d, :n] == ref.expert_rows[d]).all(), d
+                for r in range(N):
+                    assert (ob[r] == ref.out[r]).all(), r
+                first_x, first_out = sh.expert_x.clone(), out.clone()
+            else:
+                same = (torch.equal(sh.expert_x.view(torch.int16), first_x.view(torch.int16))      # as bits:
+                        and torch.equal(out.view(torch.int16), first_out.view(torch.int16)))    # the poison is a NaN
+                assert same, f"step {step} differs from the oracle-checked first step"
+                if step % 100 == 0:
+                    assert sh.status() == 0, step
+                    print(f"  soak step {step} ok", flush=True)
+        assert sh.status() == 0
         dbg = sh.debug()
         assert (dbg["arrive_disp"] == dbg["expect_disp"]).all()
         assert (dbg["arrive_comb"] == dbg["expect_comb"]).all()

@@ -100,6 +100,55 @@ def step_time(workloads, harness, torch, name, steps, warmup, two_streams=False,
             "frac_of_hbm_peak": round(gbps / HBM_PEAK_GBPS, 4)}
 
 
+def compare_modes(workloads, harness, torch, name, variants, steps, rounds=4):
+    """Step times of several modes of one workload measured in turns (round-robin, `rounds`
+    rounds of `steps` steps each, median over the rounds), all contexts alive at once: the
+    machine's speed drifts by a few percent over seconds, so modes measured one after the
+    other cannot be compared, modes measured in turns can.  variants: {label: kwargs of
+    make_shuffle, plus two_streams=True for senders and receivers on two streams}."""
+    import numpy as np
+    wl = workloads.WORKLOADS[name]
+    inp = workloads.make_inputs(wl)
+    st = workloads.describe(inp)
+    dev = harness.to_device(inp, "cuda:0")
+    cf = None if wl.zipf_alpha > 0 else (1.1 if wl.tokens >= 2048 else 1.5)
+    streams = (torch.cuda.Stream(), torch.cuda.Stream())
+    runs = {}
+    for label, kw in variants.items():
+        kw = dict(kw)
+        two = kw.pop("two_streams", False)
+        sh = harness.make_shuffle(inp, capacity_factor=cf, **kw)
+        _, bd, bc = algorithmic_bytes(wl, st["tokens_total"], st["dedup_rows"], st["pairs"], sh.sizes,
+                                      kw.get("peer_push", False), kw.get("partial_sums", False))
+        if two:
+            fn = lambda sh=sh: harness.run_step_two_streams(sh, dev, expert_y=sh.expert_x, streams=streams)
+        else:
+            fn = lambda sh=sh: harness.run_hot_path(sh, dev)
+        runs[label] = (sh, fn, bd + bc, [])
+    for rnd in range(rounds + 1):                # round 0 warms up
+        for label, (sh, fn, nbytes, times) in runs.items():
+            for _ in range(5):
+                fn()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(steps):
+                fn()
+            torch.cuda.synchronize()
+            if rnd:
+                times.append((time.perf_counter() - t0) * 1e3 / steps)
+    out = {}
+    for label, (sh, fn, nbytes, times) in runs.items():
+        assert sh.status() == 0, f"device status not clean: {label}"
+        sh.close()
+        ms = float(np.median(times))
+        gbps = nbytes / (ms * 1e-3) / 1e9
+        out[label] = {"step_us": round(ms * 1e3, 1), "step_us_rounds": [round(t * 1e3, 1) for t in times],
+                      "algorithmic_bytes": nbytes, "value": round(gbps, 1), "unit": "GB/s",
+                      "frac_of_hbm_peak": round(gbps / HBM_PEAK_GBPS, 4)}
+    torch.cuda.empty_cache()
+    return out
+
+
 def ordering_name(args):
     if args.stream_ordered:
         return "stream order supplied by the caller (no announce, no gate kernels)"
@@ -467,16 +516,19 @@ def main():
     side = args.workload == "dsv3_decode" and not args.headline_only and not (
         args.push or args.stream_ordered or args.progressive or args.partial_sums or args.private_rows
         or args.ready_e4m3)
-    stream_line = two_stream_line = prog_line = prog_two_line = others = None
+    modes = others = None
     if side:
         sh.close()
         n = max(20, min(args.steps, 300))
         w = max(5, min(args.warmup, 50))
-        two_stream_line = step_time(workloads, harness, torch, "dsv3_decode", n, w, two_streams=True)
-        stream_line = step_time(workloads, harness, torch, "dsv3_decode", n, w, stream_ordered=True)
-        prog_line = step_time(workloads, harness, torch, "dsv3_decode", n, w, progressive_recv=True)
-        prog_two_line = step_time(workloads, harness, torch, "dsv3_decode", n, w, two_streams=True,
-                                  progressive_recv=True)
+        modes = compare_modes(workloads, harness, torch, "dsv3_decode", {
+            "default (counters order everything; one stream)": {},
+            "default, senders and receivers on two streams": {"two_streams": True},
+            "FL_FLAG_STREAM_ORDERED (no announce, no gate kernels)": {"stream_ordered": True},
+            "FL_FLAG_PROGRESSIVE_RECV, one stream": {"progressive_recv": True},
+            "FL_FLAG_PROGRESSIVE_RECV, two streams": {"progressive_recv": True, "two_streams": True},
+            "FL_FLAG_PEER_PUSH (fewer bytes by construction)": {"peer_push": True},
+        }, steps=max(20, min(args.steps, 100)))
         others = {}
         for name, note in [("tiny", "launch-bound: seven kernels on a few KB"),
                            ("qwen3_skew", "cache-assisted: the working set partly fits the 256 MB last-level cache"),
@@ -559,10 +611,7 @@ def main():
         "gbps_note": "GB/s divides each method's OWN algorithmic bytes by its step time: compare methods "
                      "by step_us, not by GB/s (peer push moves fewer bytes and is the faster method)",
         "peer_push_variant": push_line,
-        "two_stream_variant": two_stream_line,
-        "stream_ordered_variant": stream_line,
-        "progressive_recv_variant": prog_line,
-        "progressive_recv_two_stream_variant": prog_two_line,
+        "modes_measured_in_turns": modes,
         "other_workloads": others,
         "roofline": roofline, "cpu_baseline": cpu,
     }

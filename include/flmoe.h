@@ -390,7 +390,9 @@ int fl_moe_debug_views(fl_moe_ctx *ctx, fl_moe_debug_view *out /*host*/);
  * FL_FLAG_PROGRESSIVE_RECV may take (default 3), knob 8 = order in which the fabric kernel
  * takes the destinations of a sender (0 = ascending, 1 = descending, 2 = starting with
  * the sender's right-hand neighbour and wrapping round; a test switch: nothing may depend
- * on the order in which transfers are carried out).  A value of -1 restores a knob's default. */
+ * on the order in which transfers are carried out), knob 9 = workgroups that share one
+ * token in combine_reduce, each summing a slice of the row (0 = chosen from the row
+ * size).  A value of -1 restores a knob's default. */
 int fl_moe_debug_tune(fl_moe_ctx *ctx, int knob, int value);
 
 /* Diagnostic, host only (no GPU needed): how a payload call over `rank_count` ranks of

@@ -32,6 +32,7 @@ struct Dims {
     int tune_grid_pct;    // row-kernel grids cover this percentage of the rows uniform routing would
                           // bring (0 = the whole capacity); kernels loop over whatever is beyond
     long long typ_recv_rows, typ_pair_rows;   // per rank, under uniform routing: received rows, pairs
+    int tune_parts;       // workgroups per token in the reduce kernel (0 = by row size)
     int tune_order;       // test switch: order in which the fabric kernel takes a sender's destinations
     int tune_cap8;        // progressive receivers: eighths of the machine's block slots their grids may take
 };

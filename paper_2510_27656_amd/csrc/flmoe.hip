@@ -129,6 +129,7 @@ int resolve(const fl_moe_config *c, Dims *D) {
     D->tune_grid_pct = 200;
     D->tune_cap8 = 3;
     D->tune_order = 0;
+    D->tune_parts = 0;
     {   // a token reaches a given rank with probability 1 - (1 - 1/N)^K when experts are drawn uniformly
         double miss = 1.0;
         for (int k = 0; k < D->K; ++k) miss *= 1.0 - 1.0 / D->N;
@@ -785,21 +786,30 @@ static int combine_reduce_range(fl_moe_ctx *ctx, int rb, int rc, const float *we
     }
     {
         LaunchTimer t(ctx, KID_COMBINE_REDUCE, st);
-        int nt = (int)((D.Bc / 16 + kWave - 1) / kWave * kWave);
+        // `parts` workgroups share a token, each taking a slice of the row
+        const int nvec = (int)(D.Bc / 16);
+        // measured: long rows are summed fastest by many small workgroups, one payload wave each
+        // (7168-wide rows: 14 workgroups of 2 waves 86 us, 2 of 7 waves 90 us, 1 of 14 waves 92 us);
+        // rows of 4 KB and less gain nothing; capped polling grids keep one workgroup per token
+        int parts = D.tune_parts > 0 ? D.tune_parts : (nvec >= 512 && !progressive ? (nvec + kWave - 1) / kWave : 1);
+        if (parts > nvec) parts = nvec;
+        const int per = (nvec + parts - 1) / parts;
+        int nt = (per + kWave - 1) / kWave * kWave;
         if (nt > kReduceMaxThreads) nt = kReduceMaxThreads;
         if (nt < 2 * kWave) nt = 2 * kWave;      // wave 0 waits, wave 1 fetches positions and weights
         // progressive (polling) receivers take at most three eighths of the machine's wave slots
-        const dim3 grid(progressive ? capped_grid(D.T, rc, (long long)ctx->cu_count * 256 * D.tune_cap8 / nt)
-                                    : (unsigned)D.T, rc);
+        const unsigned gx = progressive ? capped_grid(D.T, rc, (long long)ctx->cu_count * 256 * D.tune_cap8 / nt / parts)
+                                        : (unsigned)D.T;
+        const dim3 grid(gx * parts, rc);
         char *o = (char *)out;
         if (progressive && partial)
-            combine_reduce_kernel<true, true><<<grid, dim3(nt), 0, st>>>(D, ctx->W, rb, weights, o, ctx->num_tokens, gate);
+            combine_reduce_kernel<true, true><<<grid, dim3(nt), 0, st>>>(D, ctx->W, rb, weights, o, ctx->num_tokens, gate, parts);
         else if (progressive)
-            combine_reduce_kernel<true, false><<<grid, dim3(nt), 0, st>>>(D, ctx->W, rb, weights, o, ctx->num_tokens, gate);
+            combine_reduce_kernel<true, false><<<grid, dim3(nt), 0, st>>>(D, ctx->W, rb, weights, o, ctx->num_tokens, gate, parts);
         else if (partial)
-            combine_reduce_kernel<false, true><<<grid, dim3(nt), 0, st>>>(D, ctx->W, rb, weights, o, ctx->num_tokens, gate);
+            combine_reduce_kernel<false, true><<<grid, dim3(nt), 0, st>>>(D, ctx->W, rb, weights, o, ctx->num_tokens, gate, parts);
         else
-            combine_reduce_kernel<false, false><<<grid, dim3(nt), 0, st>>>(D, ctx->W, rb, weights, o, ctx->num_tokens, gate);
+            combine_reduce_kernel<false, false><<<grid, dim3(nt), 0, st>>>(D, ctx->W, rb, weights, o, ctx->num_tokens, gate, parts);
     }
     return launch_status();
 }
@@ -872,6 +882,7 @@ int fl_moe_debug_tune(fl_moe_ctx *ctx, int knob, int value) {
         case 6: ctx->launch_mb = dflt ? kLaunchMiB : value; break;
         case 7: if (value > 8 || value == 0) return FL_ERR_INVALID_ARG; ctx->D.tune_cap8 = dflt ? 3 : value; break;
         case 8: if (value > 2) return FL_ERR_INVALID_ARG; ctx->D.tune_order = dflt ? 0 : value; break;
+        case 9: if (value > 64) return FL_ERR_INVALID_ARG; ctx->D.tune_parts = dflt ? 0 : value; break;
         default: return FL_ERR_INVALID_ARG;
     }
     return FL_OK;

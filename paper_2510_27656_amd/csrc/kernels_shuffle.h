@@ -522,8 +522,12 @@ __global__ __launch_bounds__(kCopyThreads) void dispatch_unpack_kernel(
     __shared__ int src_phys[kMaxRowsPerBlock];      // with private slots: buffer row of each received row
     __shared__ int timed_out;
     __shared__ unsigned long long seen_pub;         // FENCED: wave 0 publishes the set of complete sources
-    if (!W.plan_ok[d]) return;
-    if (gate && !gate[d]) return;                   // the arrival wait timed out (status already latched)
+    // first round of loads, all independent: the verdicts, the rows in use, the source offsets
+    const int plan_ok = W.plan_ok[d], gate_ok = gate ? gate[d] : 1;
+    const int total = W.recv_off[(size_t)d * (N + 1) + N];
+    const int off_mine = tid <= N ? W.recv_off[(size_t)d * (N + 1) + tid] : 0;
+    if (!plan_ok) return;
+    if (!gate_ok) return;                           // the arrival wait timed out (status already latched)
     if (blockIdx.x == 0)
         for (int j = tid; j < El; j += kCopyThreads)
             tokens_per_expert[(size_t)d * El + j] = W.G[(size_t)d * El + j];
@@ -541,9 +545,8 @@ __global__ __launch_bounds__(kCopyThreads) void dispatch_unpack_kernel(
         }
     }
     // grids are sized from capacities: blocks beyond the rows in use leave at once
-    const int total = W.recv_off[(size_t)d * (N + 1) + N];
     if ((int)blockIdx.x * rows_per_block >= total) return;
-    if (tid <= N) off[tid] = W.recv_off[(size_t)d * (N + 1) + tid];
+    if (tid <= N) off[tid] = off_mine;
     if (tid == 0) timed_out = 0;
     __syncthreads();
     const char *recv = W.bufB + (size_t)d * D.bufB_rank_bytes;
@@ -577,7 +580,7 @@ __global__ __launch_bounds__(kCopyThreads) void dispatch_unpack_kernel(
                 }
                 if (tid == 0) seen_pub = seen;
             }
-        } else if (tid < kWave) {
+        } else if (!gate && tid < kWave) {          // behind a gate kernel the counters were seen complete
             if (!wave_wait_counters(W.arrive_disp + (size_t)d * N + s0,
                                     W.expect_disp + (size_t)d * N + s0, 0u, s1 - s0 + 1,
                                     D.spin_limit)) {
@@ -644,7 +647,9 @@ __global__ __launch_bounds__(kCopyThreads) void dispatch_unpack_kernel(
         };
         if (FENCED && !PRIVATE) {
             // the first batch's loads go out before the sidecars are decoded: a chunk then
-            // costs one memory round trip instead of three in a row
+            // costs one memory round trip instead of three in a row (polling receivers run with
+            // few waves per compute unit; with a full grid the extra registers cost more occupancy
+            // than the shorter chain gains: 156 against 154 us)
             v4u val[U];
             int row[U], col[U];
             load_batch(tid, val, row, col);
@@ -856,8 +861,8 @@ __global__ __launch_bounds__(kCopyThreads) void combine_partial_pack_kernel(
 // itself always runs k = 0..K-1.
 template <int KT>
 __device__ inline void reduce_row(const char *__restrict__ recv, const int *pos, const float *w,
-                                  int K, long long Bc, int nvec, v4u *__restrict__ out, int tid) {
-    for (int v = tid; v < nvec; v += (int)blockDim.x) {
+                                  int K, long long Bc, int v0, int nvec, v4u *__restrict__ out, int tid) {
+    for (int v = v0 + tid; v < nvec; v += (int)blockDim.x) {
         float acc[8];
 #pragma unroll
         for (int i = 0; i < 8; ++i) acc[i] = 0.f;
@@ -882,9 +887,9 @@ __device__ inline void reduce_row(const char *__restrict__ recv, const int *pos,
 // The same sum for a row count only known on the device (partial sums: one row per
 // distinct expert rank of the token): batches of up to 8 loads, predicated.
 __device__ inline void reduce_row_counted(const char *__restrict__ recv, const int *pos,
-                                          const float *w, int n, long long Bc, int nvec,
+                                          const float *w, int n, long long Bc, int v0, int nvec,
                                           v4u *__restrict__ out, int tid) {
-    for (int v = tid; v < nvec; v += (int)blockDim.x) {
+    for (int v = v0 + tid; v < nvec; v += (int)blockDim.x) {
         float acc[8];
 #pragma unroll
         for (int i = 0; i < 8; ++i) acc[i] = 0.f;
@@ -916,8 +921,10 @@ constexpr int kReduceMaxThreads = 1024;
 template <bool FENCED, bool PARTIAL>
 __global__ __launch_bounds__(kReduceMaxThreads, 7) void combine_reduce_kernel(
     Dims D, Tables W, int rank_begin, const float *__restrict__ weights, char *__restrict__ out,
-    const int *__restrict__ num_tokens, const int *__restrict__ gate /* as in dispatch_unpack_kernel */) {
+    const int *__restrict__ num_tokens, const int *__restrict__ gate /* as in dispatch_unpack_kernel */,
+    int parts /* workgroups that share one token, each taking a slice of the row */) {
     const int s = rank_begin + blockIdx.y, tid = threadIdx.x, N = D.N, K = D.K;
+    const int t0 = blockIdx.x / parts, part = blockIdx.x - t0 * parts, t_step = gridDim.x / parts;
     // two sets of positions and weights: while the block sums one token, wave 1 already
     // fetches the next one's (a block only walks several tokens when the grid is smaller
     // than the token count, as it is for polling receivers in unordered mode)
@@ -925,12 +932,9 @@ __global__ __launch_bounds__(kReduceMaxThreads, 7) void combine_reduce_kernel(
     __shared__ float w[2][FL_MAX_TOPK];
     __shared__ int n_shares[2];
     __shared__ int timed_out;
-    if (!W.plan_ok[s]) return;
-    if (gate && !gate[s]) return;
-    const int Ts = num_tokens[s];
-    if ((int)blockIdx.x >= Ts) return;
-    if (tid == 0) timed_out = 0;
-    __syncthreads();
+    // every load the block needs before its rows go out in ONE round: the verdicts, the token
+    // count and (wave 1) the first token's positions and weights, which exist for every t < T
+    const int plan_ok = W.plan_ok[s], gate_ok = gate ? gate[s] : 1, Ts = num_tokens[s];
     const bool fetcher = tid >= kWave && tid < 2 * kWave;     // wave 1
     const int k = tid - kWave;
     int pf_pos = -1;
@@ -956,8 +960,12 @@ __global__ __launch_bounds__(kReduceMaxThreads, 7) void combine_reduce_kernel(
             w[buf][k] = pf_w;
         }
     };
-    if (fetcher) { fetch(blockIdx.x); publish(0); }
-    if (tid < kWave) {
+    if (fetcher) fetch(t0);
+    if (!plan_ok || !gate_ok || t0 >= Ts) return;
+    if (tid == 0) timed_out = 0;               // wave 0 itself is the only one that may raise it
+    if (fetcher) publish(0);
+    // behind a gate kernel the counters were already seen complete, for every source of this rank
+    if (!gate && tid < kWave) {
         if (!wave_wait_counters(W.arrive_comb + (size_t)s * N, W.expect_comb + (size_t)s * N, 0u, N,
                                 D.spin_limit)) {
             if (tid == 0) { timed_out = 1; latch_status(W.status, FL_STATUS_TIMEOUT); }
@@ -967,19 +975,21 @@ __global__ __launch_bounds__(kReduceMaxThreads, 7) void combine_reduce_kernel(
     __syncthreads();
     if (timed_out) return;
     const char *recv = W.bufA + (size_t)s * D.bufA_rank_bytes;
-    const int nvec = (int)(D.Bc / 16);
+    const int nvec_row = (int)(D.Bc / 16);
+    const int per = (nvec_row + parts - 1) / parts;            // this block's slice: [v0, nvec)
+    const int v0 = part * per, nvec = min(v0 + per, nvec_row);
     const int kt = D.tune_reduce ? D.tune_reduce : K;
     // one token per block unless the grid was made smaller than the token count
     int cur = 0;
-    for (int t = blockIdx.x; t < Ts; t += gridDim.x) {
-        const int next = t + gridDim.x;
+    for (int t = t0; t < Ts; t += t_step) {
+        const int next = t + t_step;
         if (fetcher && next < Ts) fetch(next);                // in flight while the rows are summed
         v4u *o = (v4u *)(out + ((size_t)s * D.T + t) * D.Bc);
-        if (PARTIAL) reduce_row_counted(recv, pos[cur], w[cur], n_shares[cur], D.Bc, nvec, o, tid);
-        else if (kt >= 8) reduce_row<8>(recv, pos[cur], w[cur], K, D.Bc, nvec, o, tid);
-        else if (kt >= 4) reduce_row<4>(recv, pos[cur], w[cur], K, D.Bc, nvec, o, tid);
-        else if (kt >= 2) reduce_row<2>(recv, pos[cur], w[cur], K, D.Bc, nvec, o, tid);
-        else reduce_row<1>(recv, pos[cur], w[cur], K, D.Bc, nvec, o, tid);
+        if (PARTIAL) reduce_row_counted(recv, pos[cur], w[cur], n_shares[cur], D.Bc, v0, nvec, o, tid);
+        else if (kt >= 8) reduce_row<8>(recv, pos[cur], w[cur], K, D.Bc, v0, nvec, o, tid);
+        else if (kt >= 4) reduce_row<4>(recv, pos[cur], w[cur], K, D.Bc, v0, nvec, o, tid);
+        else if (kt >= 2) reduce_row<2>(recv, pos[cur], w[cur], K, D.Bc, v0, nvec, o, tid);
+        else reduce_row<1>(recv, pos[cur], w[cur], K, D.Bc, v0, nvec, o, tid);
         if (next >= Ts) break;
         if (fetcher) publish(cur ^ 1);
         __syncthreads();                       // the other set is complete; this one may be rewritten

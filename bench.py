@@ -304,6 +304,7 @@ def main():
                           "value": round(bytes_step / (ms * 1e-3) / 1e9, 1), "unit": "GB/s",
                           "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
                           "ms_per_step": round(ms, 4), "higher_is_better": True,
+                          "library_build_id": flmoe.fl_moe_build_id(),
                           "config": {"workload": wl.name, "ordering": ordering_name(args), "streams": 2}}))
         sh.close()
         return

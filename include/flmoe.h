@@ -100,13 +100,20 @@ extern "C" {
  *     rank's counters with acquire semantics until every source has delivered what
  *     the exchanged counts promised (bounded: FL_STATUS_TIMEOUT), and behind it the
  *     receive kernel proper, on a full grid.  Waiting occupies one wave per rank.
- * What the caller still orders itself is the RE-USE of the two staging buffers of a
- * context: every dispatch_send and dispatch_recv of a step before any combine_send of
- * that step (combine replies land in the senders' dispatch send buffers, and the
- * dispatch receive buffers become the combine send buffers), and every combine_reduce
- * of a step before the next step's dispatch_send (one stream does that by itself;
- * across streams, events - the paper's barrier before buffers are re-used, section
- * Combine).
+ * What a rank still orders itself is its OWN five calls of a step, and one step after
+ * the other (one stream per rank does that, or events).  That also covers the re-use of
+ * the two staging buffers of a context (combine replies land in the senders' dispatch
+ * send buffers, the dispatch receive buffers become the combine send buffers; the paper
+ * puts a barrier before buffers are re-used, section Combine): rank d issues
+ * combine_send after its dispatch_recv, whose gate passed only after EVERY peer's
+ * announce kernel had run, and a peer's announce kernel runs only after all of that
+ * peer's dispatch payload kernels have ended, so nobody reads a send buffer any more
+ * when the first reply is written into it; and rank s issues the next step's
+ * dispatch_send after its combine_reduce, whose gate passed only after every peer's
+ * combine payload kernels had ended, so nobody reads a combine send buffer any more
+ * when the next step's rows are written into it.  (On one GPU a waiting gate kernel
+ * occupies its hardware queue: enqueue the sends of a phase before the receives that
+ * wait for them whenever streams may share a queue.)
  *
  * FL_FLAG_STREAM_ORDERED: the caller promises that each send call precedes the matching
  * receive call in stream order (one stream, or events between streams).  The library
@@ -150,7 +157,10 @@ extern "C" {
  * whenever they come to rely on arrivals they had not seen before, and run on grids
  * capped to a fraction of the machine so that pollers can never keep senders from
  * being scheduled.  The form for receivers whose sources land far apart in time; on
- * one GPU, where all simulated senders finish together, it only costs.  Its
+ * one GPU, where all simulated senders finish together, it only costs.  A counter then
+ * says "this transfer has landed", not "this sender has finished", so here the caller
+ * must itself keep every dispatch call of a step before any combine_send, and every
+ * combine call before the next step's dispatch_send (events between streams).  Its
  * visibility argument is about the hardware (a device-scope store that was
  * acknowledged is in memory; a cache invalidated after the counter was observed
  * cannot hold older bytes), not about the HIP memory model alone. */

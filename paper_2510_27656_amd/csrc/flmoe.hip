@@ -575,7 +575,7 @@ static int dispatch_send_range(fl_moe_ctx *ctx, int rb, int rc, const void *x, c
     if (D.P > 0) {
         // First scatter: the rows bound for private slots.  Their targets follow from the
         // sender's own counts alone, so this launch reads nothing a peer produced.
-        A.announce = in_kernel && D.P >= D.T; // the call's last copy kernel announces the transfers
+        A.announce = D.P >= D.T ? (in_kernel ? 1 : fenced ? 2 : 0) : 0;   // the call's last copy kernel announces
         LaunchTimer t(ctx, KID_DISPATCH_FABRIC_PRIVATE, st);
         const unsigned g1 = capped_grid(((long long)D.N * D.P * A.waves_per_row + wpb - 1) / wpb, rc,
                                         kMaxFabricBlocks, A.waves_per_row);
@@ -588,7 +588,7 @@ static int dispatch_send_range(fl_moe_ctx *ctx, int rb, int rc, const void *x, c
         A.dst_row_lo = D.N * D.P;             // second scatter: the rest, into the shared range
     }
     if (D.P < D.T) {                          // with P = T every row has a private slot
-        A.announce = in_kernel;
+        A.announce = in_kernel ? 1 : fenced ? 2 : 0;
         LaunchTimer t(ctx, KID_DISPATCH_FABRIC, st);
         if (fenced)
             fabric_copy_kernel<true, 0, true><<<dim3(gx, rc), dim3(kCopyThreads), 0, st>>>(D, W, A, rb);
@@ -739,7 +739,7 @@ static int combine_send_range(fl_moe_ctx *ctx, int rb, int rc, const void *exper
     A.src_meta = nullptr; A.src_meta_rank_stride = 0;
     A.dst_meta = nullptr; A.dst_meta_rank_stride = 0;
     A.dst_row_lo = 0;
-    A.announce = in_kernel;
+    A.announce = in_kernel ? 1 : fenced ? 2 : 0;
     A.order = D.tune_order;
     A.arrive = W.arrive_comb;
     A.row_bytes = D.Bc; A.waves_per_row = waves_per_row(D.Bc, D.tune_waves);

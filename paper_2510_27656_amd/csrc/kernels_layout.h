@@ -249,7 +249,9 @@ __device__ __forceinline__ void route_plan_block(const Dims &D, const Tables &W,
         // lane = source s: receive offsets and combine-send offsets of rank r
         const int s = lane;
         const int m = s < N ? Mall[s * N + r] : 0;
-        exp_units = (unsigned)m * (unsigned)(D.Bw / 16);
+        // what source s will have added once its transfer to this rank is complete: the
+        // payload in 16-byte units, plus one for the transfer itself (an empty one still counts)
+        exp_units = (unsigned)m * (unsigned)(D.Bw / 16) + 1u;
         int inc = wave_incl_scan(m);
         if (s < N) W.recv_off[(size_t)r * (N + 1) + s] = inc - m;
         if (s == N - 1) W.recv_off[(size_t)r * (N + 1) + N] = inc;
@@ -283,7 +285,7 @@ __device__ __forceinline__ void route_plan_block(const Dims &D, const Tables &W,
             int mine = 0;
             for (int j = 0; j < El; ++j) mine += rt[(size_t)r * RL + d * El + j];
             if (D.flags & FL_FLAG_PARTIAL_SUMS) mine = Mall[r * N + d];   // one share per row r sent to d
-            exp_units = (unsigned)mine * (unsigned)(D.Bc / 16);
+            exp_units = (unsigned)mine * (unsigned)(D.Bc / 16) + 1u;
             long long p = 0;
             for (int j = 0; j < El; ++j) {
                 const int g = G_all[d * El + j];

@@ -15,22 +15,30 @@ constexpr int kCopyThreads = 256;
 constexpr int kPackThreads = 128;
 constexpr int kMaxRowsPerBlock = 64;
 
+// What a completed (sender, receiver) transfer adds to the receiver's counter: its
+// payload in 16-byte units plus one for the transfer itself, so that an EMPTY transfer
+// is announced too (section TransferEngine: an immediate is delivered even for a
+// zero-size write) and a receiver that has seen all its counters complete knows that
+// every peer's send call has got as far as announcing - which is what makes the re-use
+// of the staging buffers safe without a separate barrier.
+//
 // Stream-ordered mode: one add per (sender, receiver) announces the whole
 // transfer, like the single immediate a NIC delivers after a WRITE (section
 // TransferEngine, ImmCounter).  It is issued once per sender inside the kernel of
 // the send call that writes into the receivers' buffers (the scatter kernel, or
 // with PUSH the pack kernel): receivers are ordered after that kernel by the
 // stream, so they find counters and payload complete together, and no extra
-// launch is spent.  (Per-wave announcements, as in unordered mode, cost more than
+// launch is spent.  (Per-wave announcements, as in progressive mode, cost more than
 // they give here: adds to one counter from many compute dies serialise at about
 // 0.2 us each, which made skewed routing several times slower.)
 // off = the sender's row of the segment table ([N + 1] row offsets by receiver);
-// threads first, first + step, ... each take one receiver.
+// threads first, first + step, ... each take one receiver.  only_the_ones: the
+// payload units are reported by the waves that deliver them (progressive mode).
 __device__ inline void announce_transfers(const int *off, unsigned *arrive, unsigned units_per_row,
-                                          int sender, int N, int first, int step) {
+                                          int sender, int N, int first, int step, bool only_the_ones = false) {
     for (int p = first; p < N; p += step) {
         const int rows = off[p + 1] - off[p];
-        if (rows) add_counter(arrive + (size_t)p * N + sender, (unsigned)rows * units_per_row);
+        add_counter(arrive + (size_t)p * N + sender, only_the_ones ? 1u : (unsigned)rows * units_per_row + 1u);
     }
 }
 
@@ -70,7 +78,13 @@ __global__ __launch_bounds__(kPackThreads) void dispatch_pack_kernel(
 #pragma unroll
     for (int i = 0; i < 4; ++i)
         if (v0 + tid + i * kPackThreads < v1) r[i] = ld_stream(src + v0 + tid + i * kPackThreads);
-    if (!W.plan_ok[s] || t >= num_tokens[s]) return;
+    const int plan_ok = W.plan_ok[s];
+    // with PUSH no scatter kernel follows: the sender's first block announces the transfers (a
+    // sender without tokens still announces its empty ones), unless an announce kernel will
+    if (PUSH && (FENCED || (D.flags & FL_FLAG_STREAM_ORDERED)) && blockIdx.x == 0 && plan_ok)
+        announce_transfers(W.send_off + (size_t)s * (D.N + 1), W.arrive_disp, (unsigned)(D.Bw / 16), s, D.N,
+                           tid, kPackThreads, FENCED);
+    if (!plan_ok || t >= num_tokens[s]) return;
     __shared__ int s_row[FL_MAX_TOPK];
     __shared__ int s_dst[FL_MAX_TOPK];
     __shared__ unsigned s_meta[FL_MAX_TOPK];
@@ -153,9 +167,6 @@ __global__ __launch_bounds__(kPackThreads) void dispatch_pack_kernel(
         if (tid < K && my_row >= 0 && units > 0)
             add_counter(W.arrive_disp + (size_t)my_d * D.N + s, units);
     }
-    if (PUSH && !FENCED && (D.flags & FL_FLAG_STREAM_ORDERED) && blockIdx.x == 0)    // stream-ordered: the sender's first block announces
-        announce_transfers(W.send_off + (size_t)s * (D.N + 1), W.arrive_disp, (unsigned)(D.Bw / 16), s, D.N,
-                           tid, kPackThreads);
 }
 
 // ------------------------------------------------------------------ dispatch: pack with e4m3 quantisation
@@ -222,7 +233,11 @@ __global__ __launch_bounds__(kQuantThreads) void dispatch_pack_e4m3_kernel(
         in0 = ld_stream(src);
         in1 = ld_stream(src + 1);
     }
-    if (!W.plan_ok[s] || t >= num_tokens[s]) return;
+    const int plan_ok = W.plan_ok[s];
+    if (PUSH && (FENCED || (D.flags & FL_FLAG_STREAM_ORDERED)) && blockIdx.x == 0 && plan_ok)   // as in dispatch_pack_kernel
+        announce_transfers(W.send_off + (size_t)s * (D.N + 1), W.arrive_disp, (unsigned)(D.Bw / 16), s, D.N,
+                           tid, kQuantThreads, FENCED);
+    if (!plan_ok || t >= num_tokens[s]) return;
     __shared__ int s_row[FL_MAX_TOPK];
     __shared__ int s_dst[FL_MAX_TOPK];
     __shared__ unsigned s_meta[FL_MAX_TOPK];
@@ -314,9 +329,6 @@ __global__ __launch_bounds__(kQuantThreads) void dispatch_pack_e4m3_kernel(
             add_counter(W.arrive_disp + (size_t)my_d * D.N + s,
                         (unsigned)(n_live * 8 + (n_live + 3) / 4 + (slice == 0 ? pad_units : 0)));
     }
-    if (PUSH && !FENCED && (D.flags & FL_FLAG_STREAM_ORDERED) && blockIdx.x == 0)
-        announce_transfers(W.send_off + (size_t)s * (D.N + 1), W.arrive_disp, (unsigned)(D.Bw / 16), s, D.N,
-                           tid, kQuantThreads);
 }
 
 // ------------------------------------------------------------------ fabric copy
@@ -345,7 +357,9 @@ struct FabricArgs {
     long long row_bytes;
     int waves_per_row;    // 1..16
     int dst_row_lo;       // rows whose target row is below this belong to the private-slot scatter
-    int announce;         // stream-ordered mode: this launch also advances arrive[.][s] (announce_transfers)
+    int announce;         // this launch also advances arrive[.][s] (announce_transfers): 1 = by the whole
+                          // transfers (stream-ordered mode), 2 = by the ones only (progressive mode, where
+                          // the waves report the payload they deliver)
     int order;            // test switch: order in which a sender's rows (sorted by destination) are
                           // taken: 0 = as stored, 1 = last destination first, 2 = starting with the
                           // sender's right-hand neighbour and wrapping round
@@ -418,8 +432,9 @@ __global__ __launch_bounds__(kCopyThreads) void fabric_copy_kernel(Dims D, Table
             if (t.y >= A.dst_row_lo) fabric_send_row<FENCED, STREAMING>(D, A, s, row, t.x, t.y, sub, lane);
         }
     }
-    if (!FENCED && A.announce && wave == 0 && ok)
-        announce_transfers(A.seg_off + (size_t)s * (N + 1), A.arrive, (unsigned)(A.row_bytes / 16), s, N, lane, kWave);
+    if (A.announce && wave == 0 && ok)
+        announce_transfers(A.seg_off + (size_t)s * (N + 1), A.arrive, (unsigned)(A.row_bytes / 16), s, N, lane, kWave,
+                           A.announce == 2);
 }
 
 // First scatter of a dispatch with private slots (section Dispatch: tokens up to
@@ -442,8 +457,9 @@ __global__ __launch_bounds__(kCopyThreads) void fabric_private_kernel(Dims D, Ta
         const int lo = A.seg_off[(size_t)s * (N + 1) + d], hi = A.seg_off[(size_t)s * (N + 1) + d + 1];
         if (i < hi - lo) fabric_send_row<FENCED, STREAMING>(D, A, s, lo + i, d, s * P + i, sub, lane);
     }
-    if (!FENCED && A.announce && wave == 0)
-        announce_transfers(A.seg_off + (size_t)s * (N + 1), A.arrive, (unsigned)(A.row_bytes / 16), s, N, lane, kWave);
+    if (A.announce && wave == 0)
+        announce_transfers(A.seg_off + (size_t)s * (N + 1), A.arrive, (unsigned)(A.row_bytes / 16), s, N, lane, kWave,
+                           A.announce == 2);
 }
 
 // ------------------------------------------------------------------ announce
@@ -459,11 +475,10 @@ __global__ __launch_bounds__(kWave) void announce_kernel(Dims D, Tables W, int r
     const int s = rank_begin + blockIdx.x, N = D.N;
     if (!W.plan_ok[s]) return;                      // step skipped: nothing was sent
     const int p = threadIdx.x;
-    if (p < N) {
+    if (p < N) {       // payload units plus one per transfer, empty transfers included (announce_transfers)
         const int rows = off[(size_t)s * (N + 1) + p + 1] - off[(size_t)s * (N + 1) + p];
-        if (rows)
-            (void)__hip_atomic_fetch_add(arrive + (size_t)p * N + s, (unsigned)rows * units_per_row,
-                                         __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+        (void)__hip_atomic_fetch_add(arrive + (size_t)p * N + s, (unsigned)rows * units_per_row + 1u,
+                                     __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
     }
 }
 
@@ -704,14 +719,16 @@ __global__ __launch_bounds__(kCopyThreads) void combine_pack_kernel(
     __shared__ int src_row[kMaxRowsPerBlock];
     __shared__ int2 push_to[kMaxRowsPerBlock];     // PUSH: (source rank, row of its combine receive buffer)
     if (!W.plan_ok[d]) return;
+    const int nvec = (int)(D.Bc / 16);
+    // with PUSH the rank's first block announces the replies (a rank without rows its empty ones)
+    if (PUSH && (FENCED || (D.flags & FL_FLAG_STREAM_ORDERED)) && blockIdx.x == 0)
+        announce_transfers(W.cs_off + (size_t)d * (N + 1), W.arrive_comb, (unsigned)nvec, d, N, tid, kCopyThreads,
+                           FENCED);
     // grids are sized from capacities: blocks beyond the rows in use leave at once
     const int total = W.cs_off[(size_t)d * (N + 1) + N];
     if ((int)blockIdx.x * rows_per_block >= total) return;
     if (tid <= N) off[tid] = W.cs_off[(size_t)d * (N + 1) + tid];
     __syncthreads();
-    const int nvec = (int)(D.Bc / 16);
-    if (PUSH && !FENCED && (D.flags & FL_FLAG_STREAM_ORDERED) && blockIdx.x == 0)
-        announce_transfers(off, W.arrive_comb, (unsigned)nvec, d, N, tid, kCopyThreads);
     const char *yd = expert_y + (size_t)d * D.expert_cap * D.Bc;
     // capacities are upper bounds, so the grid may be smaller than the rows in use
     for (int q0 = blockIdx.x * rows_per_block; q0 < total; q0 += gridDim.x * rows_per_block) {
@@ -778,13 +795,14 @@ __global__ __launch_bounds__(kCopyThreads) void combine_partial_pack_kernel(
     __shared__ int src_cnt[kMaxRowsPerBlock];
     __shared__ int2 share_to[kMaxRowsPerBlock];
     if (!W.plan_ok[d]) return;
+    const int nvec = (int)(D.Bc / 16);
+    if (PUSH && (FENCED || (D.flags & FL_FLAG_STREAM_ORDERED)) && blockIdx.x == 0)   // as in combine_pack_kernel
+        announce_transfers(W.recv_off + (size_t)d * (N + 1), W.arrive_comb, (unsigned)nvec, d, N, tid, kCopyThreads,
+                           FENCED);
     const int total = W.recv_off[(size_t)d * (N + 1) + N];
     if ((int)blockIdx.x * rows_per_block >= total) return;
     if (tid <= N) off[tid] = W.recv_off[(size_t)d * (N + 1) + tid];
     __syncthreads();
-    const int nvec = (int)(D.Bc / 16);
-    if (PUSH && !FENCED && (D.flags & FL_FLAG_STREAM_ORDERED) && blockIdx.x == 0)
-        announce_transfers(off, W.arrive_comb, (unsigned)nvec, d, N, tid, kCopyThreads);
     const char *yd = expert_y + (size_t)d * D.expert_cap * D.Bc;
     for (int r0 = blockIdx.x * rows_per_block; r0 < total; r0 += gridDim.x * rows_per_block) {
         const int r1 = min(r0 + rows_per_block, total);

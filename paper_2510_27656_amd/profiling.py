@@ -9,6 +9,7 @@ than the ones being timed is recognised as stale.
     python -m paper_2510_27656_amd.profiling traffic <workload> <fetch csv> <write csv> <counters log> \\
         [--tag stream_ordered] [--flags "--stream-ordered"]
     python -m paper_2510_27656_amd.profiling counters <counter csv> <out.md> --title ... --command ...
+    python -m paper_2510_27656_amd.profiling timeline <kernel_trace.csv> <bench log> <out.md> --title ... --command ...
 
 The counter CSVs are `*_counter_collection.csv` of `rocprofv3 --pmc ... --output-format csv`;
 the logs are the stdout of the profiled bench.py (its JSON line is read from them).
@@ -157,6 +158,46 @@ def counters(counter_csv, out_md, title, command, per_kernel_note=""):
     print("\n".join(out))
 
 
+def timeline(trace_csv, bench_log, out_md, title, command):
+    """One step of a two-stream run as a table of kernel start and end times per queue, and
+    how often, over all traced steps, a receive-side kernel (gate or polling receive kernel)
+    was already running when the send kernels it waits for started."""
+    rows = [r for r in csv.DictReader(open(trace_csv)) if "flmoe" in r["Kernel_Name"]]
+    rows.sort(key=lambda r: int(r["Start_Timestamp"]))
+    starts = [i for i, r in enumerate(rows) if "route_layout" in r["Kernel_Name"]]
+    steps = [rows[a:b] for a, b in zip(starts, starts[1:] + [len(rows)])]
+    steps = [st for st in steps if len(st) == len(steps[len(steps) // 2])]       # whole steps only
+    mid = steps[len(steps) // 2]
+    t0 = int(mid[0]["Start_Timestamp"])
+    out = [f"# {title}\n", "Command (from /tmp with TMPDIR=/tmp on the MI355X box):\n", f"    {command}\n",
+           "Timeline of one step from the kernel trace (us since the step's first kernel; the queues are the "
+           "stream with the layout and the receive calls, and the stream with the send calls):\n",
+           "| kernel | queue | start | end |", "|---|---|---|---|"]
+    for r in mid:
+        out.append(f"| {_short(r['Kernel_Name'])} | {r['Queue_Id']} | {(int(r['Start_Timestamp']) - t0) / 1e3:.1f} | "
+                   f"{(int(r['End_Timestamp']) - t0) / 1e3:.1f} |")
+
+    def span(step, pred):
+        ks = [r for r in step if pred(r["Kernel_Name"])]
+        return (min(int(r["Start_Timestamp"]) for r in ks), max(int(r["End_Timestamp"]) for r in ks)) if ks else None
+    early = late = 0
+    for st in steps:
+        waiter = span(st, lambda n: "arrival_gate" in n or "dispatch_unpack_kernel<true" in n)
+        sender = span(st, lambda n: "fabric_copy_kernel" in n and ", 0," in n)
+        if waiter and sender:
+            early += waiter[0] < sender[0]
+            late += waiter[1] > sender[0]
+    out.append(f"\nIn {early} of {len(steps)} traced steps the first waiting receive-side kernel of the dispatch "
+               f"(gate kernel, or the polling unpack kernel) started before the dispatch fabric kernel did, and in "
+               f"{late} it was still running when that kernel started: the receivers were waiting on the counters, "
+               "not on stream order.")
+    j = _json_line(bench_log)
+    out.append(f"\nStep time of that run (profiler attached): {j['ms_per_step'] * 1e3:.0f} us; library build id "
+               f"{j.get('library_build_id', 'not recorded')}.")
+    open(out_md, "w").write("\n".join(out) + "\n")
+    print("\n".join(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     sub = ap.add_subparsers(dest="cmd", required=True)
@@ -170,8 +211,13 @@ def main():
     c.add_argument("counter_csv"); c.add_argument("out_md")
     c.add_argument("--title", required=True); c.add_argument("--command", required=True)
     c.add_argument("--note", default="")
+    t = sub.add_parser("timeline")
+    t.add_argument("trace_csv"); t.add_argument("bench_log"); t.add_argument("out_md")
+    t.add_argument("--title", required=True); t.add_argument("--command", required=True)
     args = ap.parse_args()
-    if args.cmd == "kernel-trace":
+    if args.cmd == "timeline":
+        timeline(args.trace_csv, args.bench_log, args.out_md, args.title, args.command)
+    elif args.cmd == "kernel-trace":
         kernel_trace(args.stats_csv, args.bench_log, args.out_md, args.title, args.command)
     elif args.cmd == "traffic":
         traffic(args.workload, args.fetch_csv, args.write_csv, args.counters_log, args.tag, args.flags)

@@ -188,15 +188,16 @@ def test_repeated_steps_are_deterministic_and_counters_monotone():
         dbg = sh.debug()
         assert (dbg["epoch_route"].cpu().numpy() == 4).all()
         assert (dbg["arrive_route"].cpu().numpy() == 4).all()
-        # payload counters: delivered == expected, 4 steps x rows x 16-byte units per row
+        # payload counters: delivered == expected, 4 steps x (rows x 16-byte units per row, plus
+        # one per transfer, empty ones included)
         units = inp.wl.hidden * 2 // 16
         ref = oracle_step(inp)
-        want_disp = 4 * ref.lay.M.T.astype(np.int64) * units            # [dst][src]
+        want_disp = 4 * (ref.lay.M.T.astype(np.int64) * units + 1)      # [dst][src]
         pairs = ref.lay.C.reshape(inp.wl.n_ranks, inp.wl.n_ranks, -1).sum(2)   # [src][owner]
         assert (dbg["arrive_disp"].cpu().numpy() == want_disp).all()
         assert (dbg["expect_disp"].cpu().numpy() == want_disp).all()
-        assert (dbg["arrive_comb"].cpu().numpy() == 4 * pairs * units).all()
-        assert (dbg["expect_comb"].cpu().numpy() == 4 * pairs * units).all()
+        assert (dbg["arrive_comb"].cpu().numpy() == 4 * (pairs * units + 1)).all()
+        assert (dbg["expect_comb"].cpu().numpy() == 4 * (pairs * units + 1)).all()
         assert sh.status() == 0
     finally:
         sh.close()
@@ -567,11 +568,15 @@ def test_every_token_to_one_rank_is_served_by_the_row_loops(kw):
     sh.close()
 
 
-def test_no_tokens_anywhere_is_a_clean_no_op():
+@pytest.mark.parametrize("kw", [dict(), dict(stream_ordered=True), dict(progressive_recv=True), dict(peer_push=True),
+                                dict(peer_push=True, stream_ordered=True),
+                                dict(peer_push=True, progressive_recv=True),
+                                dict(peer_push=True, partial_sums=True, progressive_recv=True)])
+def test_no_tokens_anywhere_is_a_clean_no_op(kw):
     inp = wlmod.make_inputs(CASES["ragged_520"]())
     inp.num_tokens[:] = 0
     dev = harness.to_device(inp)
-    sh = harness.make_shuffle(inp)
+    sh = harness.make_shuffle(inp, **kw)
     try:
         sh.expert_x.view(torch.int16).fill_(POISON)
         sh.out.view(torch.int16).fill_(POISON)
@@ -584,8 +589,9 @@ def test_no_tokens_anywhere_is_a_clean_no_op():
         assert (tabs["C"].cpu().numpy() == 0).all() and (tabs["expert_off"].cpu().numpy() == 0).all()
         assert (bits(sh.expert_x) == POISON).all() and (bits(sh.out) == POISON).all()
         dbg = sh.debug()
-        assert (dbg["arrive_disp"].cpu().numpy() == 0).all()
-        assert (dbg["expect_disp"].cpu().numpy() == 0).all()
+        # every transfer was empty, and every one was announced and expected all the same
+        for name in ("arrive_disp", "expect_disp", "arrive_comb", "expect_comb"):
+            assert (dbg[name].cpu().numpy() == 1).all(), name
     finally:
         sh.close()
 
@@ -683,6 +689,71 @@ def test_concurrent_send_and_receive_on_two_streams(name, shuffled, push, progre
         assert (dbg["arrive_disp"] == dbg["expect_disp"]).all()
         assert (dbg["arrive_comb"] == dbg["expect_comb"]).all()
     finally:
+        sh.close()
+
+
+@pytest.mark.parametrize("push", [False, True])
+def test_one_stream_per_rank_no_cross_rank_events(push):
+    """Every simulated rank issues its payload calls (rank_count = 1) on a stream of its
+    own, as ranks on separate GPUs would; between the ranks there is no event and no
+    common stream, only the arrival counters.  Each rank keeps its own calls in order
+    (its stream), which in the default mode is also all the re-use of the staging
+    buffers needs: a rank's gate passes only after every peer's announce kernel ran,
+    and that kernel runs only after the peer's payload kernels have ended.  Steps
+    follow each other without a device synchronisation; each step's results are
+    copied aside on the rank's own stream and compared with the oracle at the end.
+    (The layout step is one call for all ranks, since its kernels wait for each other
+    inside the call.  Host issue order puts all sends of a phase before its receives,
+    so that no gate kernel can sit in front of a send in a shared hardware queue.)"""
+    inp = wlmod.make_inputs(wlmod.custom("per_rank_streams", 4, 32, 100, 1024, 4, seed=71, ragged=True,
+                                         expert="identity"))
+    N = inp.wl.n_ranks
+    ref = oracle_step(inp)
+    dev = harness.to_device(inp)
+    sh = harness.make_shuffle(inp, peer_push=push)
+    streams = [torch.cuda.Stream() for _ in range(N)]
+    lay_stream = torch.cuda.Stream()
+    steps, kept = 12, []
+    rng = np.random.default_rng(71)
+    try:
+        torch.cuda.synchronize()
+        done = []
+        for step in range(steps):
+            for e in done:                              # a rank plans its next step after its own reduce
+                lay_stream.wait_event(e)
+            with torch.cuda.stream(lay_stream):
+                sh.expert_x.view(torch.int16).fill_(POISON)
+                sh.out.view(torch.int16).fill_(POISON)
+                sh.layout(dev["indices"], dev["num_tokens"], stream=lay_stream)
+                planned = torch.cuda.Event()
+                planned.record(lay_stream)
+            order = [int(r) for r in rng.permutation(N)]
+            for r in order:
+                streams[r].wait_event(planned)
+                sh.dispatch_send(dev["x"], (r, 1), stream=streams[r])
+            for r in reversed(order):
+                sh.dispatch_recv((r, 1), stream=streams[r])
+            for r in order:
+                sh.combine_send(sh.expert_x, (r, 1), stream=streams[r])      # identity expert
+            done, snap = [], []
+            for r in reversed(order):
+                sh.combine_reduce(dev["weights"], (r, 1), stream=streams[r])
+                with torch.cuda.stream(streams[r]):
+                    snap.append((r, sh.expert_x[r, :ref.stride].clone(), sh.out[r].clone()))
+                    e = torch.cuda.Event()
+                    e.record(streams[r])
+                    done.append(e)
+            kept.append(snap)
+        torch.cuda.synchronize()
+        assert sh.status() == 0
+        for step, snap in enumerate(kept):
+            for r, ex, out in snap:
+                n = ref.expert_rows[r].shape[0]
+                assert (bits(ex)[:n] == ref.expert_rows[r]).all(), (step, r)
+                k = inp.num_tokens[r]
+                assert (bits(out)[:k] == ref.out[r, :k]).all(), (step, r)
+    finally:
+        torch.cuda.synchronize()
         sh.close()
 
 
@@ -903,12 +974,12 @@ def test_peer_push_counters_and_untouched_send_buffer(name):
         assert sh.status() == 0
         dbg = sh.debug()
         units = int(sh.sizes.wire_row_bytes) // 16
-        assert (dbg["arrive_disp"].cpu().numpy() == ref.lay.M.T.astype(np.int64) * units).all()
-        assert (dbg["expect_disp"].cpu().numpy() == ref.lay.M.T.astype(np.int64) * units).all()
+        assert (dbg["arrive_disp"].cpu().numpy() == ref.lay.M.T.astype(np.int64) * units + 1).all()
+        assert (dbg["expect_disp"].cpu().numpy() == ref.lay.M.T.astype(np.int64) * units + 1).all()
         pairs = ref.lay.C.reshape(wl.n_ranks, wl.n_ranks, -1).sum(2)
         cunits = wl.hidden * 2 // 16
-        assert (dbg["arrive_comb"].cpu().numpy() == pairs * cunits).all()
-        assert (dbg["expect_comb"].cpu().numpy() == pairs * cunits).all()
+        assert (dbg["arrive_comb"].cpu().numpy() == pairs * cunits + 1).all()
+        assert (dbg["expect_comb"].cpu().numpy() == pairs * cunits + 1).all()
     finally:
         sh.close()
 
@@ -967,8 +1038,8 @@ def test_partial_sums_differ_from_the_exact_combine_and_need_the_weighted_dispat
         dbg = sh.debug()
         units = wl.hidden * 2 // 16
         # one share per de-duplicated row: arrive_comb[s][d] counts M[s][d] rows
-        assert (dbg["arrive_comb"].cpu().numpy() == ref.lay.M.astype(np.int64) * units).all()
-        assert (dbg["expect_comb"].cpu().numpy() == ref.lay.M.astype(np.int64) * units).all()
+        assert (dbg["arrive_comb"].cpu().numpy() == ref.lay.M.astype(np.int64) * units + 1).all()
+        assert (dbg["expect_comb"].cpu().numpy() == ref.lay.M.astype(np.int64) * units + 1).all()
         with pytest.raises(flmoe.FlMoeError) as ei:       # refused on the host, nothing enqueued
             sh.dispatch_send(dev["x"])
         assert ei.value.code == flmoe.FL_ERR_INVALID_ARG

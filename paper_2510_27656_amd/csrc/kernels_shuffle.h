@@ -473,10 +473,12 @@ __global__ __launch_bounds__(kCopyThreads) void fabric_private_kernel(Dims D, Ta
 __global__ __launch_bounds__(kWave) void announce_kernel(Dims D, Tables W, int rank_begin, const int *off,
                                                          unsigned *arrive, unsigned units_per_row) {
     const int s = rank_begin + blockIdx.x, N = D.N;
-    if (!W.plan_ok[s]) return;                      // step skipped: nothing was sent
     const int p = threadIdx.x;
+    const int plan_ok = W.plan_ok[s];               // one round of loads: the verdict and the segment table
+    const int lo = p < N ? off[(size_t)s * (N + 1) + p] : 0, hi = p < N ? off[(size_t)s * (N + 1) + p + 1] : 0;
+    if (!plan_ok) return;                           // step skipped: nothing was sent
     if (p < N) {       // payload units plus one per transfer, empty transfers included (announce_transfers)
-        const int rows = off[(size_t)s * (N + 1) + p + 1] - off[(size_t)s * (N + 1) + p];
+        const int rows = hi - lo;
         (void)__hip_atomic_fetch_add(arrive + (size_t)p * N + s, (unsigned)rows * units_per_row + 1u,
                                      __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
     }
@@ -495,9 +497,18 @@ __global__ __launch_bounds__(kWave) void announce_kernel(Dims D, Tables W, int r
 __global__ __launch_bounds__(kWave) void arrival_gate_kernel(Dims D, Tables W, int rank_begin,
                                                              const unsigned *arrive, const unsigned *expect,
                                                              int *gate) {
-    const int r = rank_begin + blockIdx.x, N = D.N;
-    if (!W.plan_ok[r]) return;                      // step skipped: the receive kernel leaves on plan_ok too
-    const bool ok = wave_wait_counters(arrive + (size_t)r * N, expect + (size_t)r * N, 0u, N, D.spin_limit);
+    const int r = rank_begin + blockIdx.x, N = D.N, lane = threadIdx.x;
+    // one round of loads: the verdict, what to expect, and the first look at the counters
+    const int plan_ok = W.plan_ok[r];
+    const unsigned want = lane < N ? expect[(size_t)r * N + lane] : 0u;
+    unsigned have = lane < N ? ld_relaxed(arrive + (size_t)r * N + lane) : 0u;
+    if (!plan_ok) return;                           // step skipped: the receive kernel leaves on plan_ok too
+    bool ok = true;
+    for (long long spins = 0; !__all((int)(have - want) >= 0); ++spins) {      // wrap-safe, bounded
+        if (spins >= D.spin_limit) { ok = false; break; }
+        __builtin_amdgcn_s_sleep(64);
+        if (lane < N) have = ld_relaxed(arrive + (size_t)r * N + lane);
+    }
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");     // pairs with the senders' release adds
     if (threadIdx.x == 0) {
         gate[r] = ok ? 1 : 0;

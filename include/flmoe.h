@@ -243,8 +243,8 @@ typedef struct fl_moe_debug_view {
     int64_t buf_b_rank_bytes;
     uint32_t *arrive_route;   /* [N][N] route records received, [destination][source]      */
     uint32_t *epoch_route;    /* [N] number of layout calls of each rank                   */
-    uint32_t *arrive_disp;    /* [N][N] monotone payload counters, [destination][source],  */
-    uint32_t *arrive_comb;    /*        in 16-byte units delivered by the fabric           */
+    uint32_t *arrive_disp;    /* [N][N] monotone payload counters, [destination][source]:  */
+    uint32_t *arrive_comb;    /*        16-byte units delivered, plus one per transfer     */
     uint32_t *expect_disp;    /* [N][N] what the receiver expects, from the counts it got  */
     uint32_t *expect_comb;
     int32_t *status;          /* the device status word                                    */
@@ -314,8 +314,8 @@ int fl_moe_layout_static(const fl_moe_config *cfg /*host*/, const int32_t *indic
  * must be addressable (rows of absent tokens may be read, they are never used).
  * Packs one copy of each token per distinct destination rank (quantising to
  * e4m3 when configured), copies every (source, destination) segment into the
- * destination's receive buffer and adds what was delivered (in 16-byte units)
- * to arrive_disp[destination][source]. */
+ * destination's receive buffer and announces every transfer, empty ones included,
+ * on arrive_disp[destination][source]: its payload in 16-byte units plus one. */
 int fl_moe_dispatch_send(fl_moe_ctx *ctx, int rank_begin, int rank_count, const void *x,
                          void *stream);
 
@@ -350,8 +350,9 @@ int fl_moe_dispatch_recv(fl_moe_ctx *ctx, int rank_begin, int rank_count, void *
 /* Step 4 (section Combine: a single scatter per peer re-using the routing
  * information).  expert_y [N][expert_capacity_rows][H] bf16, same row layout as
  * expert_x.  Packs each peer's rows contiguously, copies them into the peer's
- * combine receive buffer and adds what was delivered to arrive_comb[peer][this
- * rank].  Call it once per fl_moe_layout, after fl_moe_dispatch_recv. */
+ * combine receive buffer and announces every reply, empty ones included, on
+ * arrive_comb[peer][this rank] (units plus one, as in dispatch).  Call it once per
+ * fl_moe_layout, after fl_moe_dispatch_recv. */
 int fl_moe_combine_send(fl_moe_ctx *ctx, int rank_begin, int rank_count, const void *expert_y,
                         void *stream);
 

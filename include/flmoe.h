@@ -181,8 +181,8 @@ typedef struct fl_moe_config {
     int32_t hidden;         /* H, 8..2^20, 2*H a multiple of 16                           */
     int32_t dispatch_dtype; /* FL_DTYPE_*: payload type of dispatch; combine is bf16      */
     int32_t expert_align;   /* every local expert but the first starts on a multiple of
-                               this many rows ("optional padding between experts",
-                               section Dispatch); >= 1                                    */
+                               this many rows (the padding between experts that section
+                               Dispatch leaves optional); >= 1                            */
     int32_t flags;          /* FL_FLAG_*                                                  */
     int64_t recv_capacity_rows;   /* per rank: deduplicated rows it can receive; 0 = N*T  */
     int64_t expert_capacity_rows; /* per rank: rows of its expert-major layout, padding

@@ -51,11 +51,11 @@ struct Tables {
     int *status;
     unsigned *epoch_route;                                    // [N] layout calls of each rank
     unsigned *arrive_route;                                   // [N dst][N src] route records received
-    // Payload counters, monotone, in 16-byte units: arrive_* advances when data has
-    // landed (stream-ordered: once per transfer, by the kernel that follows the copy;
-    // unordered: by every copying wave), expect_* is advanced by the receiver's own
-    // planning kernel from the counts it was sent, so a receiver waits for
-    // arrive >= expect per source.
+    // Payload counters, monotone: a completed transfer adds its payload in 16-byte units
+    // plus one (default: by the announce kernel behind the payload kernels; stream-ordered
+    // callers: by one wave of the last payload kernel; progressive mode: the units by every
+    // copying wave); expect_* is advanced by the receiver's own planning block from the
+    // counts it was sent, so a receiver waits for arrive >= expect per source.
     unsigned *arrive_disp, *arrive_comb;                      // [N dst][N src]
     unsigned *expect_disp, *expect_comb;                      // [N dst][N src]
     int *routes;          // [N receiver][N source][route_len]
@@ -82,7 +82,7 @@ struct Tables {
     int *cs_base;         // [N][N][El]       first combine-send row of (source, local expert)
     int *cs_off;          // [N][N+1]         first combine-send row of each source
     int *plan_ok;         // [N]
-    int *gate_disp;       // [N] unordered mode: 1 once every source's dispatch payload was seen complete
+    int *gate_disp;       // [N] default mode: 1 once the gate kernel saw every source's dispatch payload complete
     int *gate_comb;       // [N] the same for the combine replies
     unsigned *send_meta;  // [N][send_cap][MW]
     unsigned *recv_meta;  // [N][recv_rows][MW]
@@ -95,19 +95,20 @@ struct Tables {
 constexpr unsigned kNoEntry = 0xFFFFFFFFu;
 
 // ---------------------------------------------------------------- atomics
-// Two ways to run the fabric.  Stream-ordered (FENCED = false): the caller keeps
-// every send kernel before the matching receive kernel in stream order, so the
-// kernel boundary already makes payloads visible; payload stores are ordinary
-// streaming stores and the counters are relaxed atomics.  Unordered (FENCED =
-// true): senders and receivers may overlap in time.  On gfx950 each XCD has its
-// own L2, so a payload only becomes visible to a receiver on another XCD once it
-// has left the sender's L2.  An agent-scope release fence would write back the
-// whole L2 (measured: 5x to 25x slower fabric kernel, depending on how many
-// waves fence).  Instead the sender writes the payload with device-scope stores
-// (sc1: written through to memory), waits until its own stores are acknowledged,
-// and only then updates the counter; the receiver polls the counter with
-// device-scope loads and, once it has arrived, invalidates its caches once
-// (agent-scope acquire) before touching the payload.
+// FENCED names the progressive mode, in which senders and receivers overlap in time
+// inside their kernels: every sending wave reports the units it delivered and the
+// receive kernels poll.  On gfx950 each XCD has its own L2, so a payload only
+// becomes visible to a receiver on another XCD once it has left the sender's L2.
+// An agent-scope release fence would write back the whole L2 (measured: 5x to 25x
+// slower fabric kernel, depending on how many waves fence).  Instead the sender
+// writes the payload with device-scope stores (sc1: written through to memory),
+// waits until its own stores are acknowledged, and only then updates the counter;
+// the receiver polls the counter with device-scope loads and, once it has arrived,
+// invalidates its caches (agent-scope acquire) before touching the payload.
+// FENCED = false covers the other two modes, where whole kernels order payload and
+// counters: the announce kernel behind the payload kernels (default), or the
+// caller's stream order (FL_FLAG_STREAM_ORDERED); payload stores are then ordinary
+// stores and the in-kernel counter accesses relaxed atomics.
 __device__ inline unsigned ld_relaxed(const unsigned *p) {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
@@ -116,7 +117,7 @@ __device__ inline unsigned ld_relaxed(const unsigned *p) {
 __device__ inline void add_counter(unsigned *p, unsigned v) {
     (void)__hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-// After a wave's last payload store and before its add_counter: in unordered mode,
+// After a wave's last payload store and before its add_counter: in progressive mode,
 // wait until every store of this wave (including the device-scope ones issued
 // from inline assembly, which the compiler does not count) has been acknowledged.
 template <bool FENCED>
@@ -233,8 +234,8 @@ __device__ inline int seg_of_short(const int *off, int n, int x, int *start) {
 typedef unsigned v4u __attribute__((ext_vector_type(4)));
 __device__ inline v4u ld_stream(const v4u *p) { return __builtin_nontemporal_load(p); }
 __device__ inline void st_stream(v4u *p, v4u v) { __builtin_nontemporal_store(v, p); }
-// Fabric payload store.  Unordered mode: device scope, written through to memory so
-// that another XCD can see it without an L2 write-back.  Stream-ordered mode: an
+// Fabric payload store.  Progressive mode: device scope, written through to memory so
+// that another XCD can see it without an L2 write-back.  Otherwise: an
 // ordinary cached store while the receive buffers are small enough for the caches
 // to absorb a good part of them (measured: 17 % faster fabric kernel at the decode
 // shape, the kernels after it 4 % slower, the step 5 % faster), a streaming store

@@ -281,9 +281,8 @@ int launch_status() { return hipGetLastError() == hipSuccess ? FL_OK : FL_ERR_HI
 // 4096-token step: 8 % faster in 2-rank launches), while cutting a launch that is
 // small already only adds launch tails.  So a call whose ranks move more than three
 // times the target is cut into rank groups of about the target size.  Not in
-// unordered mode: its receive kernels run on capped grids and its copies write
-// through, and there the cut measured 3 % slower (and the caller who overlaps
-// senders and receivers chooses the granularity of the send calls itself).
+// progressive mode: its receive kernels run on capped grids and its copies write
+// through, and there the cut measured 3 % slower.
 int ranks_per_launch(const Dims &D, int launch_mb, int rc) {
     if (launch_mb <= 0 || (D.flags & FL_FLAG_PROGRESSIVE_RECV)) return rc;
     const long long row = D.Bw > D.Bc ? D.Bw : D.Bc;

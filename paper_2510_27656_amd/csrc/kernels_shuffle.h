@@ -53,7 +53,7 @@ __device__ inline void announce_transfers(const int *off, unsigned *arrive, unsi
 // PUSH (every peer's receive buffer can be stored to, section Dispatch: within a
 // node payloads are pushed from the send kernel): the copies and their sidecars
 // go straight into the destinations' receive buffers; no send buffer is filled
-// and no scatter follows.  FENCED (unordered fabric, PUSH only): device-scope
+// and no scatter follows.  FENCED (progressive mode, PUSH only): device-scope
 // stores, and the block adds the 16-byte units it wrote to
 // arrive[destination][source] itself once they are acknowledged; stream-ordered
 // with PUSH, the sender's first block announces the whole transfers.
@@ -339,12 +339,13 @@ __global__ __launch_bounds__(kQuantThreads) void dispatch_pack_e4m3_kernel(
 // that searched the offset tables per wave measured 25 % slower).  Waves work on
 // their own: a row is shared by `waves_per_row` waves, each copies its slice
 // with four loads in flight.  No barrier, no shared memory, no ticket.  In
-// unordered mode (FENCED) a wave then adds the number of 16-byte units it
+// progressive mode (FENCED) a wave then adds the number of 16-byte units it
 // delivered to arrive[destination][source] with an atomic whose result nobody
 // waits for: the counters only ever say "this much of source s's payload has
-// landed", in whatever order waves finish.  In stream-ordered mode nobody may
-// look before the kernel has ended, and one wave per sender announces each whole
-// transfer (announce_transfers).
+// landed", in whatever order waves finish.  Otherwise nobody may look before the
+// kernel has ended: the whole transfers are announced by the announce kernel
+// behind it (default) or, for stream-ordered callers, by one wave per sender
+// inside it (announce_transfers).
 struct FabricArgs {
     const char *src_base; long long src_rank_stride;
     char *dst_base;       long long dst_rank_stride;
@@ -366,7 +367,7 @@ struct FabricArgs {
 };
 
 // One wave's share of one row: slice `sub` of `G` (vectors v with (v / 64) % G ==
-// sub), the sidecar when it is slice 0, and in unordered mode the count of
+// sub), the sidecar when it is slice 0, and in progressive mode the count of
 // 16-byte units it delivered, added to arrive[destination][source].
 template <bool FENCED, bool STREAMING>
 __device__ inline void fabric_send_row(const Dims &D, const FabricArgs &A, int s, int src_row,
@@ -485,15 +486,16 @@ __global__ __launch_bounds__(kWave) void announce_kernel(Dims D, Tables W, int r
 }
 
 // ------------------------------------------------------------------ arrival gate
-// Unordered fabric, receiving side: one wave per rank polls the rank's arrival
+// Default mode, receiving side: one wave per rank polls the rank's arrival
 // counters (bounded) until every source has delivered what the exchanged counts
-// promised, which is the paper's receive half ("waits for the completion of all
-// transfers", section Dispatch: the proxy raises a flag once the ImmCounter has
-// reached its expectation).  The receive kernel proper follows in the same
-// stream: it starts after this kernel has ended, with clean caches, so everything
-// the counters vouched for (written through to memory before they advanced) is
-// what it reads.  Waiting costs one wave per rank instead of a grid of pollers,
-// so senders that run at the same time keep the machine.
+// promised.  That is how the paper's receive half begins as well (section
+// Dispatch: it first waits until all transfers are complete, the proxy raising a
+// flag once the ImmCounter has reached its expectation).  The receive kernel
+// proper follows in the same stream: it starts after this kernel has ended, with
+// clean caches, so what it reads is what the counters vouched for (the senders'
+// payload kernels had ended, their stores written back, before the release adds).
+// Waiting costs one wave per rank instead of a grid of pollers, so senders that
+// run at the same time keep the machine.
 __global__ __launch_bounds__(kWave) void arrival_gate_kernel(Dims D, Tables W, int rank_begin,
                                                              const unsigned *arrive, const unsigned *expect,
                                                              int *gate) {
@@ -523,7 +525,7 @@ __global__ __launch_bounds__(kWave) void arrival_gate_kernel(Dims D, Tables W, i
 //   base_x[d][local expert][source] + rank carried in the sidecar,
 // which is the (expert, source rank, token) order of the grouped layout.
 //
-// FENCED (unordered fabric): the kernel may have been started before any payload
+// FENCED (progressive mode): the kernel may have been started before any payload
 // exists, on a grid that is a fraction of the machine, so a block walks many
 // chunks.  It keeps the set of sources it has seen complete: a chunk whose
 // sources are all in the set costs no poll; otherwise one wave polls the
@@ -956,7 +958,7 @@ __global__ __launch_bounds__(kReduceMaxThreads, 7) void combine_reduce_kernel(
     const int t0 = blockIdx.x / parts, part = blockIdx.x - t0 * parts, t_step = gridDim.x / parts;
     // two sets of positions and weights: while the block sums one token, wave 1 already
     // fetches the next one's (a block only walks several tokens when the grid is smaller
-    // than the token count, as it is for polling receivers in unordered mode)
+    // than the token count, as it is for the polling receivers of progressive mode)
     __shared__ int pos[2][FL_MAX_TOPK];
     __shared__ float w[2][FL_MAX_TOPK];
     __shared__ int n_shares[2];

@@ -645,13 +645,17 @@ __global__ __launch_bounds__(kCopyThreads) void dispatch_unpack_kernel(
                     phys = recv_buffer_row(N, D.P, s, r - off[s], W.recv_shared_off[(size_t)d * N + s]);
                     src_phys[tid] = phys;
                 }
+                // entry k + 1 is fetched before entry k is looked at, so that it travels together
+                // with the base row of entry k (most rows have one entry: two round trips, not three)
                 const unsigned *meta = W.recv_meta + ((size_t)d * D.recv_rows + phys) * D.MW;
                 int n = 0;
+                unsigned m = meta[0];
                 for (int k = 0; k < K; ++k) {
-                    const unsigned m = meta[k];
+                    const unsigned m_next = k + 1 < K ? meta[k + 1] : kNoEntry;
                     if (m == kNoEntry) break;
                     const int j = (int)(m >> 24), i = (int)(m & 0xFFFFFFu);
                     dst_rows[tid][n++] = W.base_x[((size_t)d * El + j) * N + s] + i;
+                    m = m_next;
                 }
                 dst_cnt[tid] = n;
             }

@@ -1,5 +1,5 @@
 // A caller of the C ABI that knows nothing of Python or torch: plain hipMalloc'd
-// buffers, the five shuffle calls, and two checks that need no second
+// buffers, the five shuffle calls, and checks that need no second
 // implementation of the method.
 //   1. Layout (section Dispatch, grouped layout): walking experts, source ranks and
 //      tokens in that order and taking every token routed to the expert IS the
@@ -148,6 +148,52 @@ int main() {
                 std::fprintf(stderr, "rank %d: a row of an absent token was written\n", s);
                 return 9;
             }
+    }
+
+    // 3. The layout step without context or workspace (fl_moe_layout_static, for callers that
+    //    cannot allocate): its tokens_per_expert must equal the context's, its counts a plain
+    //    histogram of the indices; called twice, the array inside the library being re-used.
+    {
+        const size_t sizes[10] = {(size_t)N * E, (size_t)N * N, (size_t)N * El, (size_t)N * (N + 1),
+                                  (size_t)N * (N + 1), (size_t)N * (El + 1), (size_t)N * (N + 1),
+                                  (size_t)N * T * K, (size_t)N, 1};
+        size_t total = 0;
+        for (size_t v : sizes) total += v;
+        int32_t *d_tab = nullptr;
+        HIP_OK(hipMalloc((void **)&d_tab, total * 4));
+        int32_t *p[10];
+        size_t at = 0;
+        for (int i = 0; i < 10; ++i) { p[i] = d_tab + at; at += sizes[i]; }
+        const fl_moe_layout_out lo = {p[0], p[1], p[2], p[3], p[4], p[5], p[6], p[7], p[8], p[9]};
+        std::vector<int32_t> tab(total);
+        for (int call = 0; call < 2; ++call) {
+            HIP_OK(hipMemsetAsync(d_tab, 0x5a, total * 4, st));
+            FL_CALL(fl_moe_layout_static(&cfg, d_idx, d_nt, &lo, st));
+            HIP_OK(hipStreamSynchronize(st));
+            HIP_OK(hipMemcpy(tab.data(), d_tab, total * 4, hipMemcpyDeviceToHost));
+            const int32_t *counts = tab.data(), *tpe2 = tab.data() + (p[2] - d_tab);
+            if (tab[p[9] - d_tab] != 0) { std::fprintf(stderr, "static layout: status %d\n", tab[p[9] - d_tab]); return 10; }
+            for (int r = 0; r < N; ++r)
+                if (tab[(p[8] - d_tab) + r] != 1) { std::fprintf(stderr, "static layout: plan_ok[%d]\n", r); return 11; }
+            if (std::memcmp(tpe2, tpe.data(), tpe.size() * 4) != 0) {
+                std::fprintf(stderr, "static layout: tokens_per_expert differs from the context's\n");
+                return 12;
+            }
+            for (int s = 0; s < N; ++s)
+                for (int e = 0; e < E; ++e) {
+                    int c = 0;
+                    for (int t = 0; t < nt[s]; ++t)
+                        for (int k = 0; k < K; ++k) c += indices[((size_t)s * T + t) * K + k] == e;
+                    if (counts[s * E + e] != c) { std::fprintf(stderr, "static layout: counts[%d][%d]\n", s, e); return 13; }
+                }
+        }
+        fl_moe_config huge = cfg;
+        huge.n_ranks = 32; huge.n_experts = 256; huge.max_tokens = 4096; huge.top_k = 8;
+        if (fl_moe_layout_static(&huge, d_idx, d_nt, &lo, st) != FL_ERR_STATIC_LIMIT) {
+            std::fprintf(stderr, "static layout: a configuration beyond the array was accepted\n");
+            return 14;
+        }
+        HIP_OK(hipFree(d_tab));
     }
 
     FL_CALL(fl_moe_destroy(ctx));

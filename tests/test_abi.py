@@ -133,3 +133,33 @@ def test_large_calls_are_cut_into_rank_groups_small_ones_are_not():
     assert lib.fl_moe_debug_launch_groups(C.byref(c), 0, -1, C.byref(out)) == flmoe.FL_ERR_INVALID_ARG
     assert lib.fl_moe_debug_launch_groups(C.byref(c), 33, -1, C.byref(out)) == flmoe.FL_ERR_INVALID_ARG
     assert lib.fl_moe_debug_launch_groups(C.byref(c), 32, -1, None) == flmoe.FL_ERR_INVALID_ARG
+
+
+def test_static_layout_entry_point_checks_its_arguments_before_touching_a_gpu():
+    """fl_moe_layout_static validates on the host first: null or misaligned pointers, bad
+    configurations and configurations beyond its static scratch array are refused without
+    any device call (so this runs without a GPU)."""
+    L = flmoe.lib()
+    small = cfg(n_ranks=4, n_experts=32, max_tokens=64, top_k=4, hidden=256)
+    fake = 0x1000                                   # never dereferenced: every call below fails earlier
+    out = flmoe.fl_moe_layout_out(*([fake] * len(flmoe.LAYOUT_OUT_FIELDS)))
+    assert L.fl_moe_layout_static(None, fake, fake, C.byref(out), None) == flmoe.FL_ERR_INVALID_ARG
+    assert L.fl_moe_layout_static(C.byref(small), None, fake, C.byref(out), None) == flmoe.FL_ERR_INVALID_ARG
+    assert L.fl_moe_layout_static(C.byref(small), fake, fake, None, None) == flmoe.FL_ERR_INVALID_ARG
+    hole = flmoe.fl_moe_layout_out(*([fake] * (len(flmoe.LAYOUT_OUT_FIELDS) - 1) + [None]))
+    assert L.fl_moe_layout_static(C.byref(small), fake, fake, C.byref(hole), None) == flmoe.FL_ERR_INVALID_ARG
+    odd = flmoe.fl_moe_layout_out(*([fake + 2] + [fake] * (len(flmoe.LAYOUT_OUT_FIELDS) - 1)))
+    assert L.fl_moe_layout_static(C.byref(small), fake, fake, C.byref(odd), None) == flmoe.FL_ERR_ALIGNMENT
+    assert L.fl_moe_layout_static(C.byref(small), fake + 1, fake, C.byref(out), None) == flmoe.FL_ERR_ALIGNMENT
+    bad = cfg(n_ranks=4, n_experts=30)
+    assert L.fl_moe_layout_static(C.byref(bad), fake, fake, C.byref(out), None) == flmoe.FL_ERR_INVALID_ARG
+    # the decode shape fits the array, the 4096-token shape does not (per-pair tables of 8 MB)
+    big = cfg(max_tokens=4096)
+    assert L.fl_moe_layout_static(C.byref(big), fake, fake, C.byref(out), None) == flmoe.FL_ERR_STATIC_LIMIT
+    assert b"static" in L.fl_moe_strerror(flmoe.FL_ERR_STATIC_LIMIT)
+    assert flmoe.FL_STATIC_SCRATCH_BYTES == 8 << 20
+
+
+def test_loaded_library_was_built_from_the_sources_in_the_tree():
+    from paper_2510_27656_amd import build
+    assert flmoe.fl_moe_build_id() == build.source_hash() and len(build.source_hash()) == 16

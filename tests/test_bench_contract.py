@@ -43,6 +43,12 @@ def test_bench_prints_one_json_line_with_the_agreed_keys():
         assert key in cpu, key
     assert cpu["kind"] == "oracle" and cpu["cores"] >= 1 and cpu["value"] > 0
     assert line["value"] > 0 and line["ms_per_step"] > 0
+    # either HBM bytes measured with this very build of the library, or null with the reason
+    assert (roof["traffic"] is None) == ("traffic_stale" in roof)
+    assert line["library_build_id"] and line["step_us"] > 0
+    for key in ("write_ceiling_gbps", "read_ceiling_gbps", "kernel_frac_of_read_write_bound",
+                "modes_measured_in_turns", "other_workloads"):
+        assert key in line, key                 # the last two are filled on the headline workload only
 
 
 @pytest.mark.gpu

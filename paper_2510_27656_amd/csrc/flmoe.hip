@@ -6,6 +6,7 @@
 #include <cstring>
 #include <mutex>
 #include <new>
+#include <type_traits>
 
 #include "../../include/flmoe.h"
 #include "common.h"
@@ -516,19 +517,24 @@ static int dispatch_send_range(fl_moe_ctx *ctx, int rb, int rc, const void *x, c
     const bool in_kernel = D.flags & FL_FLAG_STREAM_ORDERED;
     if (D.dtype == FL_DTYPE_E4M3_BLOCK128 && !ready_scales) {
         LaunchTimer t(ctx, KID_DISPATCH_PACK_E4M3, st);
-        const int per_block = kQuantThreads / kQuantLanes;       // quantisation blocks per workgroup
-        const int slices = (D.scales_per_row + per_block - 1) / per_block;
-        const dim3 grid((unsigned)D.T * slices, rc), block(kQuantThreads);
         const char *xp = (const char *)x;
-        if (push && fenced)
-            dispatch_pack_e4m3_kernel<true, true><<<grid, block, 0, st>>>(D, W, rb, xp, ctx->indices,
-                                                                          ctx->num_tokens, slices, weights);
-        else if (push)
-            dispatch_pack_e4m3_kernel<true, false><<<grid, block, 0, st>>>(D, W, rb, xp, ctx->indices,
-                                                                           ctx->num_tokens, slices, weights);
-        else
-            dispatch_pack_e4m3_kernel<false, false><<<grid, block, 0, st>>>(D, W, rb, xp, ctx->indices,
-                                                                            ctx->num_tokens, slices, weights);
+        auto go = [&](auto threads) {
+            constexpr int QT = decltype(threads)::value;
+            const int per_block = QT / kQuantLanes;              // quantisation blocks per workgroup
+            const int slices = (D.scales_per_row + per_block - 1) / per_block;
+            const dim3 grid((unsigned)D.T * slices, rc), block(QT);
+            if (push && fenced)
+                dispatch_pack_e4m3_kernel<true, true, QT><<<grid, block, 0, st>>>(D, W, rb, xp, ctx->indices,
+                                                                                  ctx->num_tokens, slices, weights);
+            else if (push)
+                dispatch_pack_e4m3_kernel<true, false, QT><<<grid, block, 0, st>>>(D, W, rb, xp, ctx->indices,
+                                                                                   ctx->num_tokens, slices, weights);
+            else
+                dispatch_pack_e4m3_kernel<false, false, QT><<<grid, block, 0, st>>>(D, W, rb, xp, ctx->indices,
+                                                                                    ctx->num_tokens, slices, weights);
+        };
+        if (D.scales_per_row > 256 / kQuantLanes) go(std::integral_constant<int, 512>{});
+        else go(std::integral_constant<int, 256>{});
     } else {
         LaunchTimer t(ctx, KID_DISPATCH_PACK, st);
         // bf16 rows, or e4m3 codes the caller quantised itself (their scales go along)

@@ -369,6 +369,21 @@ int fl_moe_combine_reduce(fl_moe_ctx *ctx, int rank_begin, int rank_count, const
 /* Reads and clears the device status word (synchronises the stream). */
 int fl_moe_status(fl_moe_ctx *ctx, int32_t *host_out /*host*/, void *stream);
 
+/* What to do about FL_STATUS_CAPACITY (capacities are the caller's choice; the paper
+ * sizes its buffers for the worst case, section Dispatch).  After the layout calls of
+ * a step have covered all N ranks, this call returns the smallest recv_capacity_rows
+ * and expert_capacity_rows with which that same step fits on every rank: the maxima
+ * over ranks of the rows a rank receives beyond the private slots, and of the rows of
+ * its expert-major layout with the padding of expert_align.  A caller whose step was
+ * skipped for capacity creates a context with at least these values (and its own
+ * margin) and repeats the step.  It reads the per-source count tables of the last
+ * layout call (N*E + N*N ints), which the sources write whether or not the plan was
+ * valid; after FL_STATUS_BAD_INDEX or a time-out of the layout call the result is
+ * meaningless.  Set-up work: synchronises `stream`, copies to the host, allocates host
+ * memory; it neither reads nor clears the status word. */
+int fl_moe_required_capacities(fl_moe_ctx *ctx, int64_t *recv_capacity_rows /*host*/,
+                               int64_t *expert_capacity_rows /*host*/, void *stream);
+
 /* After FL_STATUS_TIMEOUT the counters of a context can be out of step for good: a
  * layout call whose peers never ran has advanced its own ranks' epochs and message
  * counters but not theirs, and a payload wait that gave up leaves its expectation ahead

@@ -2,6 +2,7 @@
 // Every shuffle call only enqueues kernels on the caller's stream.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cstdlib>
 #include <cstring>
 #include <mutex>
@@ -846,6 +847,36 @@ int fl_moe_reset(fl_moe_ctx *ctx, void *stream) {
     const size_t bytes = (size_t)((char *)ctx->W.plan_ok - (char *)ctx->W.status);
     if (hipMemsetAsync(ctx->W.status, 0, bytes, st) != hipSuccess) return FL_ERR_HIP;
     if (hipStreamSynchronize(st) != hipSuccess) return FL_ERR_HIP;
+    return FL_OK;
+}
+
+int fl_moe_required_capacities(fl_moe_ctx *ctx, int64_t *recv_capacity_rows, int64_t *expert_capacity_rows,
+                               void *stream) {
+    if (!ctx || !recv_capacity_rows || !expert_capacity_rows) return FL_ERR_INVALID_ARG;
+    const Dims &D = ctx->D;
+    const size_t nC = (size_t)D.N * D.E, nM = (size_t)D.N * D.N;
+    int *host = new (std::nothrow) int[nC + nM];
+    if (!host) return FL_ERR_HIP;
+    int *C = host, *M = host + nC;          // the sources' own tables: valid whether or not the plan was
+    hipError_t e = hipStreamSynchronize((hipStream_t)stream);
+    if (e == hipSuccess) e = hipMemcpy(C, ctx->W.C, nC * sizeof(int), hipMemcpyDeviceToHost);
+    if (e == hipSuccess) e = hipMemcpy(M, ctx->W.M, nM * sizeof(int), hipMemcpyDeviceToHost);
+    if (e != hipSuccess) { delete[] host; return FL_ERR_HIP; }
+    long long need_recv = 1, need_expert = 1;   // 0 would read as "worst case" in a configuration
+    for (int d = 0; d < D.N; ++d) {
+        long long recv = 0, rows = 0;
+        for (int s = 0; s < D.N; ++s) recv += std::max(M[(size_t)s * D.N + d] - D.P, 0);
+        for (int j = 0; j < D.El; ++j) {
+            long long g = 0;
+            for (int s = 0; s < D.N; ++s) g += C[(size_t)s * D.E + (size_t)d * D.El + j];
+            rows += (j + 1 < D.El) ? (g + D.align - 1) / D.align * D.align : g;   // as the planning block pads
+        }
+        need_recv = std::max(need_recv, recv);
+        need_expert = std::max(need_expert, rows);
+    }
+    delete[] host;
+    *recv_capacity_rows = need_recv;
+    *expert_capacity_rows = need_expert;
     return FL_OK;
 }
 

@@ -71,7 +71,8 @@ EXPORTS = ["fl_moe_query_sizes", "fl_moe_create", "fl_moe_destroy", "fl_moe_layo
            "fl_moe_dispatch_send", "fl_moe_dispatch_send_weighted", "fl_moe_dispatch_send_e4m3",
            "fl_moe_dispatch_recv",
            "fl_moe_combine_send",
-           "fl_moe_combine_reduce", "fl_moe_status", "fl_moe_reset", "fl_moe_strerror", "fl_moe_debug_views",
+           "fl_moe_combine_reduce", "fl_moe_status", "fl_moe_reset", "fl_moe_required_capacities",
+           "fl_moe_strerror", "fl_moe_debug_views",
            "fl_moe_debug_tune", "fl_moe_debug_launch_groups", "fl_moe_debug_copy", "fl_moe_debug_fill", "fl_moe_debug_read", "fl_moe_profile_enable", "fl_moe_profile_collect", "fl_moe_profile_read",
            "fl_moe_kernel_name", "fl_moe_build_id"]
 
@@ -108,6 +109,7 @@ def lib():
         L.fl_moe_combine_reduce.argtypes = [vp, i32, i32, vp, vp, vp]
         L.fl_moe_status.argtypes = [vp, C.POINTER(C.c_int32), vp]
         L.fl_moe_reset.argtypes = [vp, vp]
+        L.fl_moe_required_capacities.argtypes = [vp, C.POINTER(C.c_int64), C.POINTER(C.c_int64), vp]
         L.fl_moe_strerror.argtypes = [i32]
         L.fl_moe_strerror.restype = C.c_char_p
         L.fl_moe_debug_views.argtypes = [vp, C.POINTER(fl_moe_debug_view)]
@@ -226,6 +228,14 @@ def fl_moe_status(ctx, stream=None) -> int:
 
 def fl_moe_reset(ctx, stream=None):
     _check(lib().fl_moe_reset(ctx, _stream(stream)), "fl_moe_reset")
+
+
+def fl_moe_required_capacities(ctx, stream=None):
+    """(recv_capacity_rows, expert_capacity_rows) the last step needs."""
+    recv, expert = C.c_int64(), C.c_int64()
+    _check(lib().fl_moe_required_capacities(ctx, C.byref(recv), C.byref(expert), _stream(stream)),
+           "fl_moe_required_capacities")
+    return recv.value, expert.value
 
 
 def fl_moe_debug_views(ctx) -> fl_moe_debug_view:
@@ -367,6 +377,9 @@ class MoEShuffle:
 
     def status(self):
         return fl_moe_status(self.ctx)
+
+    def required_capacities(self):
+        return fl_moe_required_capacities(self.ctx)
 
     def reset(self):
         fl_moe_reset(self.ctx)

@@ -22,11 +22,14 @@ def to_device(inp: Inputs, device="cuda:0"):
 
 def make_shuffle(inp: Inputs, expert_align=1, zero_pad=False, capacity_factor=None,
                  spin_limit=0, stream_ordered=False, max_private_rows=0, peer_push=False,
-                 partial_sums=False, progressive_recv=False, device="cuda:0"):
-    """capacity_factor None = worst-case capacities, else factor x the mean rows per rank."""
+                 partial_sums=False, progressive_recv=False, capacities=None, device="cuda:0"):
+    """capacity_factor None = worst-case capacities, else factor x the mean rows per rank;
+    capacities = (recv_capacity_rows, expert_capacity_rows) given outright."""
     wl = inp.wl
     recv_cap = expert_cap = 0
-    if capacity_factor is not None:
+    if capacities is not None:
+        recv_cap, expert_cap = capacities
+    elif capacity_factor is not None:
         mean_rows = wl.tokens * wl.top_k
         expert_cap = int(mean_rows * capacity_factor) + (wl.experts_per_rank - 1) * (expert_align - 1)
         recv_cap = int(min(mean_rows, wl.n_ranks * wl.tokens) * capacity_factor)

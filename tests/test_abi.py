@@ -101,6 +101,7 @@ def test_null_arguments_are_errors_not_crashes():
     assert L.fl_moe_layout(None, 0, 1, None, None, None, None) == flmoe.FL_ERR_INVALID_ARG
     assert L.fl_moe_dispatch_send(None, 0, 1, None, None) == flmoe.FL_ERR_INVALID_ARG
     assert L.fl_moe_status(None, None, None) == flmoe.FL_ERR_INVALID_ARG
+    assert L.fl_moe_required_capacities(None, None, None, None) == flmoe.FL_ERR_INVALID_ARG
     assert L.fl_moe_strerror(flmoe.FL_ERR_WORKSPACE) == b"workspace too small"
     names = [L.fl_moe_kernel_name(i).decode() for i in range(flmoe.FL_KERNEL_COUNT)]
     assert all(names) and len(set(names)) == flmoe.FL_KERNEL_COUNT

@@ -44,7 +44,8 @@ def check_tables(sh, ref, N):
 
 
 def run_and_compare(inp, align=1, zero_pad=False, capacity_factor=None, ranks_split=False,
-                    ordering="counters", private_rows=0, push=False, partial=False, launch_mb=None):
+                    ordering="counters", private_rows=0, push=False, partial=False, launch_mb=None,
+                    capacities=None):
     """ordering: "counters" = the default mode (the arrival counters are the only ordering:
     announce and gate kernels), "stream" = FL_FLAG_STREAM_ORDERED, "progressive" =
     FL_FLAG_PROGRESSIVE_RECV."""
@@ -55,7 +56,8 @@ def run_and_compare(inp, align=1, zero_pad=False, capacity_factor=None, ranks_sp
         ref.out = ref.out_partial
     dev = harness.to_device(inp)
     sh = harness.make_shuffle(inp, expert_align=align, zero_pad=zero_pad, partial_sums=partial,
-                              capacity_factor=capacity_factor, stream_ordered=ordering == "stream",
+                              capacity_factor=capacity_factor, capacities=capacities,
+                              stream_ordered=ordering == "stream",
                               progressive_recv=ordering == "progressive",
                               max_private_rows=private_rows, peer_push=push)
     try:
@@ -1229,6 +1231,40 @@ def test_capacity_overflow_is_reported_not_written(kw):
         assert (dbg["arrive_disp"] == dbg["expect_disp"]).all() and (dbg["arrive_comb"] == dbg["expect_comb"]).all()
     finally:
         sh.close()
+
+
+@pytest.mark.parametrize("align,private_rows", [(1, 0), (16, 0), (1, 4)])
+def test_required_capacities_after_an_overflow_size_a_context_that_fits(align, private_rows):
+    """A step skipped for capacity tells the caller what it needs: the oracle's per-rank
+    maxima.  A context with exactly these capacities runs the step (full parity); one row
+    less in either of them is an overflow again."""
+    inp = wlmod.make_inputs(CASES["ragged_520"]())
+    ref = oracle_step(inp, align, zero_pad=True)
+    dev = harness.to_device(inp)
+    sh = harness.make_shuffle(inp, expert_align=align, capacities=(4, 4), max_private_rows=private_rows)
+    try:
+        harness.run_hot_path(sh, dev)
+        need = sh.required_capacities()          # synchronises
+        assert sh.status() == flmoe.FL_STATUS_CAPACITY
+    finally:
+        sh.close()
+    M = ref.lay.M.astype(np.int64)               # [source][destination]
+    want = (max(1, int(np.maximum(M - private_rows, 0).sum(axis=0).max())),
+            max(1, int(ref.lay.expert_off[:, -1].max())))
+    assert need == want
+    sh2, _, _ = run_and_compare(inp, align=align, private_rows=private_rows, capacities=need)
+    assert sh2.required_capacities() == want     # the same numbers after a valid step
+    sh2.close()
+    for short in [(need[0] - 1, need[1]), (need[0], need[1] - 1)]:
+        if min(short) < 1:
+            continue
+        sh3 = harness.make_shuffle(inp, expert_align=align, max_private_rows=private_rows, capacities=short)
+        try:
+            harness.run_hot_path(sh3, dev)
+            torch.cuda.synchronize()
+            assert sh3.status() == flmoe.FL_STATUS_CAPACITY, short
+        finally:
+            sh3.close()
 
 
 def test_missing_peers_time_out_instead_of_hanging():

@@ -531,12 +531,14 @@ def main():
             "FL_FLAG_PEER_PUSH (fewer bytes by construction)": {"peer_push": True},
         }, steps=max(20, min(args.steps, 100)))
         others = {}
-        for name, note in [("tiny", "launch-bound: seven kernels on a few KB"),
+        for name, note in [("tiny", "launch-bound: eleven kernels on a few KB"),
                            ("qwen3_skew", "cache-assisted: the working set partly fits the 256 MB last-level cache"),
                            ("dsv3_fp8", "e4m3 dispatch quantised on the fly, bf16 combine"),
                            ("dsv3_prefill", "4096 tokens per rank, payload calls cut into launches of 2 ranks")]:
             big_w = workloads.WORKLOADS[name].tokens >= 2048
-            others[name] = step_time(workloads, harness, torch, name, 5 if big_w else n, 2 if big_w else w)
+            # the short steps need a few hundred repetitions to reach their steady rate
+            others[name] = step_time(workloads, harness, torch, name, 5 if big_w else max(n, 200),
+                                     2 if big_w else max(w, 20))
             others[name]["note"] = note
 
     cpu = None

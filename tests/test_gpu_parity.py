@@ -768,7 +768,9 @@ def test_soak_two_streams_shuffled_senders_every_step_checked(progressive, steps
     is compared with the oracle; every later step must reproduce its expert rows and
     its combined output bit for bit (outputs are poisoned before each step, so a
     receiver that ran ahead of its data cannot pass), with a clean status word."""
+    import os
     from dataclasses import replace
+    steps *= max(1, int(os.environ.get("FLMOE_SOAK_SCALE", "1")))     # a longer run on request
     wl = replace(wlmod.WORKLOADS["dsv3_decode"], name="soak", expert="identity")
     inp = wlmod.make_inputs(wl)
     N = wl.n_ranks

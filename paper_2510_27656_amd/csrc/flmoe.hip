@@ -296,7 +296,16 @@ int ranks_per_launch(const Dims &D, int launch_mb, int rc) {
     return (int)((rc + launches - 1) / launches);
 }
 
-// Runs f(rank_begin, rank_count) over the rank groups of one call.
+// The whole rank range of a call, and where in it the current launch group sits: the
+// gate kernel of a receive call runs once, before the first group, for all its ranks,
+// and the announce kernel of a send call once, behind the last group (a receiver needs
+// every sender's rows anyway, so announcing group by group would let nobody start earlier).
+struct CallSpan {
+    int rank_begin, rank_count;
+    bool first, last;
+};
+
+// Runs f(rank_begin, rank_count, span) over the rank groups of one call.
 template <class F>
 int for_rank_groups(const fl_moe_ctx *ctx, int rb, int rc, F f) {
     int e = check_ranks(ctx, rb, rc);
@@ -304,7 +313,7 @@ int for_rank_groups(const fl_moe_ctx *ctx, int rb, int rc, F f) {
     const int g = ranks_per_launch(ctx->D, ctx->launch_mb, rc);
     for (int r = rb; r < rb + rc; r += g) {
         const int n = rb + rc - r < g ? rb + rc - r : g;
-        e = f(r, n);
+        e = f(r, n, CallSpan{rb, rc, r == rb, r + n == rb + rc});
         if (e != FL_OK) return e;
     }
     return FL_OK;
@@ -499,7 +508,7 @@ int fl_moe_layout_static(const fl_moe_config *cfg, const int32_t *indices, const
     return launch_status();
 }
 
-static int dispatch_send_range(fl_moe_ctx *ctx, int rb, int rc, const void *x, const float *weights,
+static int dispatch_send_range(fl_moe_ctx *ctx, int rb, int rc, CallSpan call, const void *x, const float *weights,
                                const float *ready_scales, bool streaming, void *stream) {
     int e = check_ranks(ctx, rb, rc);
     if (e != FL_OK) return e;
@@ -554,10 +563,10 @@ static int dispatch_send_range(fl_moe_ctx *ctx, int rb, int rc, const void *x, c
                                                                        ctx->num_tokens, slices, weights, src_row, ready_scales);
     }
     auto announce = [&]() {                   // counter-ordered mode: the transfers are announced once
-        if (fenced || in_kernel) return;      // every payload kernel of the call has ended
+        if (fenced || in_kernel || !call.last) return;   // every payload kernel of the call has ended
         LaunchTimer t(ctx, KID_ANNOUNCE_DISPATCH, st);
-        announce_kernel<<<dim3(rc), dim3(kWave), 0, st>>>(D, W, rb, W.send_off, W.arrive_disp,
-                                                           (unsigned)(D.Bw / 16));
+        announce_kernel<<<dim3(call.rank_count), dim3(kWave), 0, st>>>(D, W, call.rank_begin, W.send_off,
+                                                                        W.arrive_disp, (unsigned)(D.Bw / 16));
     };
     if (push) {                               // the rows are already in the peers' receive buffers
         announce();
@@ -612,8 +621,8 @@ static int dispatch_send_impl(fl_moe_ctx *ctx, int rb, int rc, const void *x, co
     if (!ctx) return FL_ERR_INVALID_ARG;
     // cached or streaming stores in the scatter: decided by what the whole call writes
     const bool streaming = (long long)rc * ctx->D.send_cap * ctx->D.Bw > ((long long)ctx->D.tune_stream_mb << 20);
-    return for_rank_groups(ctx, rb, rc, [&](int r, int n) {
-        return dispatch_send_range(ctx, r, n, x, weights, ready_scales, streaming, stream);
+    return for_rank_groups(ctx, rb, rc, [&](int r, int n, CallSpan call) {
+        return dispatch_send_range(ctx, r, n, call, x, weights, ready_scales, streaming, stream);
     });
 }
 
@@ -633,7 +642,7 @@ int fl_moe_dispatch_send_e4m3(fl_moe_ctx *ctx, int rb, int rc, const void *codes
     return dispatch_send_impl(ctx, rb, rc, codes, weights, scales, stream);
 }
 
-static int dispatch_recv_range(fl_moe_ctx *ctx, int rb, int rc, void *expert_x, float *expert_scales,
+static int dispatch_recv_range(fl_moe_ctx *ctx, int rb, int rc, CallSpan call, void *expert_x, float *expert_scales,
                                int32_t *tokens_per_expert, void *stream) {
     int e = check_ranks(ctx, rb, rc);
     if (e != FL_OK) return e;
@@ -663,9 +672,11 @@ static int dispatch_recv_range(fl_moe_ctx *ctx, int rb, int rc, void *expert_x, 
     if (gx < (unsigned)D.El) gx = D.El;      // the first El-1 blocks also clear padding rows
     const int *gate = nullptr;
     if (gated && !progressive) {
-        LaunchTimer t(ctx, KID_GATE_DISPATCH, st);
-        arrival_gate_kernel<<<dim3(rc), dim3(kWave), 0, st>>>(D, ctx->W, rb, ctx->W.arrive_disp,
-                                                               ctx->W.expect_disp, ctx->W.gate_disp);
+        if (call.first) {
+            LaunchTimer t(ctx, KID_GATE_DISPATCH, st);
+            arrival_gate_kernel<<<dim3(call.rank_count), dim3(kWave), 0, st>>>(
+                D, ctx->W, call.rank_begin, ctx->W.arrive_disp, ctx->W.expect_disp, ctx->W.gate_disp);
+        }
         gate = ctx->W.gate_disp;
     }
     {
@@ -690,12 +701,12 @@ static int dispatch_recv_range(fl_moe_ctx *ctx, int rb, int rc, void *expert_x, 
 
 int fl_moe_dispatch_recv(fl_moe_ctx *ctx, int rb, int rc, void *expert_x, float *expert_scales,
                          int32_t *tokens_per_expert, void *stream) {
-    return for_rank_groups(ctx, rb, rc, [&](int r, int n) {
-        return dispatch_recv_range(ctx, r, n, expert_x, expert_scales, tokens_per_expert, stream);
+    return for_rank_groups(ctx, rb, rc, [&](int r, int n, CallSpan call) {
+        return dispatch_recv_range(ctx, r, n, call, expert_x, expert_scales, tokens_per_expert, stream);
     });
 }
 
-static int combine_send_range(fl_moe_ctx *ctx, int rb, int rc, const void *expert_y, void *stream) {
+static int combine_send_range(fl_moe_ctx *ctx, int rb, int rc, CallSpan call, const void *expert_y, void *stream) {
     int e = check_ranks(ctx, rb, rc);
     if (e != FL_OK) return e;
     if (!expert_y) return FL_ERR_INVALID_ARG;
@@ -729,10 +740,10 @@ static int combine_send_range(fl_moe_ctx *ctx, int rb, int rc, const void *exper
         }
     }
     auto announce = [&]() {
-        if (fenced || in_kernel) return;
+        if (fenced || in_kernel || !call.last) return;
         LaunchTimer t(ctx, KID_ANNOUNCE_COMBINE, st);
-        announce_kernel<<<dim3(rc), dim3(kWave), 0, st>>>(D, W, rb, partial ? W.recv_off : W.cs_off,
-                                                           W.arrive_comb, (unsigned)(D.Bc / 16));
+        announce_kernel<<<dim3(call.rank_count), dim3(kWave), 0, st>>>(
+            D, W, call.rank_begin, partial ? W.recv_off : W.cs_off, W.arrive_comb, (unsigned)(D.Bc / 16));
     };
     if (push) {                               // the rows are already in the sources' receive buffers
         announce();
@@ -768,12 +779,12 @@ static int combine_send_range(fl_moe_ctx *ctx, int rb, int rc, const void *exper
 }
 
 int fl_moe_combine_send(fl_moe_ctx *ctx, int rb, int rc, const void *expert_y, void *stream) {
-    return for_rank_groups(ctx, rb, rc, [&](int r, int n) {
-        return combine_send_range(ctx, r, n, expert_y, stream);
+    return for_rank_groups(ctx, rb, rc, [&](int r, int n, CallSpan call) {
+        return combine_send_range(ctx, r, n, call, expert_y, stream);
     });
 }
 
-static int combine_reduce_range(fl_moe_ctx *ctx, int rb, int rc, const float *weights, void *out,
+static int combine_reduce_range(fl_moe_ctx *ctx, int rb, int rc, CallSpan call, const float *weights, void *out,
                                 void *stream) {
     int e = check_ranks(ctx, rb, rc);
     if (e != FL_OK) return e;
@@ -785,9 +796,11 @@ static int combine_reduce_range(fl_moe_ctx *ctx, int rb, int rc, const float *we
     const bool progressive = D.flags & FL_FLAG_PROGRESSIVE_RECV;
     const int *gate = nullptr;
     if (gated && !progressive) {         // as in dispatch_recv: a gate kernel, then the full grid
-        LaunchTimer t(ctx, KID_GATE_COMBINE, st);
-        arrival_gate_kernel<<<dim3(rc), dim3(kWave), 0, st>>>(D, ctx->W, rb, ctx->W.arrive_comb,
-                                                               ctx->W.expect_comb, ctx->W.gate_comb);
+        if (call.first) {
+            LaunchTimer t(ctx, KID_GATE_COMBINE, st);
+            arrival_gate_kernel<<<dim3(call.rank_count), dim3(kWave), 0, st>>>(
+                D, ctx->W, call.rank_begin, ctx->W.arrive_comb, ctx->W.expect_comb, ctx->W.gate_comb);
+        }
         gate = ctx->W.gate_comb;
     }
     {
@@ -822,8 +835,8 @@ static int combine_reduce_range(fl_moe_ctx *ctx, int rb, int rc, const float *we
 
 int fl_moe_combine_reduce(fl_moe_ctx *ctx, int rb, int rc, const float *weights, void *out,
                           void *stream) {
-    return for_rank_groups(ctx, rb, rc, [&](int r, int n) {
-        return combine_reduce_range(ctx, r, n, weights, out, stream);
+    return for_rank_groups(ctx, rb, rc, [&](int r, int n, CallSpan call) {
+        return combine_reduce_range(ctx, r, n, call, weights, out, stream);
     });
 }
 

@@ -149,6 +149,67 @@ def compare_modes(workloads, harness, torch, name, variants, steps, rounds=4):
     return out
 
 
+def interleaved_caller_work(workloads, harness, torch, steps=100, rounds=3):
+    """Section MoE Dispatch/Combine: the send and the receive half of dispatch and of combine are
+    calls of their own so that the caller's other work can run between them.  The decode step in
+    the default mode on one stream, with a compute-bound kernel of the caller (a bf16 matrix
+    product from the BLAS library: the stand-in for shared-expert or attention work of another
+    micro-batch, no part of the shuffle) enqueued on a second stream right after each send call.
+    Measured in turns: the step alone, the two products alone, both together."""
+    import numpy as np
+    wl = workloads.WORKLOADS["dsv3_decode"]
+    inp = workloads.make_inputs(wl)
+    dev = harness.to_device(inp, "cuda:0")
+    sh = harness.make_shuffle(inp, capacity_factor=1.5)
+    a = torch.randn(4096, wl.hidden, device="cuda:0", dtype=torch.bfloat16)
+    b = torch.randn(wl.hidden, 4096, device="cuda:0", dtype=torch.bfloat16)
+    c = torch.empty(4096, 4096, device="cuda:0", dtype=torch.bfloat16)
+    side = torch.cuda.Stream()
+    main_stream = torch.cuda.current_stream()
+
+    def step(shuffle, work):
+        if work:
+            main_stream.wait_stream(side)        # the previous step's products have ended
+            side.wait_stream(main_stream)
+        if shuffle:
+            sh.layout(dev["indices"], dev["num_tokens"])
+            sh.dispatch_send(dev["x"])
+        if work:
+            with torch.cuda.stream(side):
+                torch.matmul(a, b, out=c)
+        if shuffle:
+            sh.dispatch_recv()
+            sh.combine_send(sh.expert_x)
+        if work:
+            with torch.cuda.stream(side):
+                torch.matmul(a, b, out=c)
+        if shuffle:
+            sh.combine_reduce(dev["weights"])
+
+    cases = {"step_alone_us": (True, False), "products_alone_us": (False, True), "together_us": (True, True)}
+    times = {k: [] for k in cases}
+    for rnd in range(rounds + 1):                # round 0 warms up
+        for k, (shuffle, work) in cases.items():
+            for _ in range(5):
+                step(shuffle, work)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(steps):
+                step(shuffle, work)
+            torch.cuda.synchronize()
+            if rnd:
+                times[k].append((time.perf_counter() - t0) * 1e6 / steps)
+    assert sh.status() == 0
+    sh.close()
+    out = {k: round(float(np.median(v)), 1) for k, v in times.items()}
+    out["hidden_us"] = round(out["step_alone_us"] + out["products_alone_us"] - out["together_us"], 1)
+    out["caller_work"] = "two bf16 matrix products [4096 x %d] x [%d x 4096] per step on a second stream, " \
+                         "one enqueued after each send call" % (wl.hidden, wl.hidden)
+    del a, b, c
+    torch.cuda.empty_cache()
+    return out
+
+
 def ordering_name(args):
     if args.stream_ordered:
         return "stream order supplied by the caller (no announce, no gate kernels)"
@@ -199,6 +260,9 @@ def main():
     ap.add_argument("--counters", action="store_true",
                     help="short run for `rocprofv3 --pmc`: a few steps plus one plain 1 GiB copy "
                          "of known size to calibrate the byte counters; no timing output")
+    ap.add_argument("--interleaved", action="store_true",
+                    help="only the decode step with a caller's matrix products on a second stream between "
+                         "the send and receive halves (the side measurement interleaved_caller_work)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs the whole simulated expert-parallel group on ONE GPU; "
@@ -208,6 +272,13 @@ def main():
     import numpy as np
     import torch
     from paper_2510_27656_amd import flmoe, harness, workloads
+
+    if args.interleaved:
+        res = interleaved_caller_work(workloads, harness, torch, steps=max(20, min(args.steps or 100, 100)))
+        print(json.dumps({"metric": "interleaved_caller_work", "ms_per_step": round(res["together_us"] / 1e3, 4),
+                          "config": {"workload": "dsv3_decode"}, "library_build_id": flmoe.fl_moe_build_id(),
+                          "interleaved_caller_work": res}))
+        return
 
     wl = workloads.WORKLOADS[args.workload]
     big = wl.tokens >= 2048
@@ -517,7 +588,7 @@ def main():
     side = args.workload == "dsv3_decode" and not args.headline_only and not (
         args.push or args.stream_ordered or args.progressive or args.partial_sums or args.private_rows
         or args.ready_e4m3)
-    modes = others = None
+    modes = others = interleaved = None
     if side:
         sh.close()
         n = max(20, min(args.steps, 300))
@@ -530,6 +601,7 @@ def main():
             "FL_FLAG_PROGRESSIVE_RECV, two streams": {"progressive_recv": True, "two_streams": True},
             "FL_FLAG_PEER_PUSH (fewer bytes by construction)": {"peer_push": True},
         }, steps=max(20, min(args.steps, 100)))
+        interleaved = interleaved_caller_work(workloads, harness, torch)
         others = {}
         for name, note in [("tiny", "launch-bound: eleven kernels on a few KB"),
                            ("qwen3_skew", "cache-assisted: the working set partly fits the 256 MB last-level cache"),
@@ -616,6 +688,7 @@ def main():
         "peer_push_variant": push_line,
         "modes_measured_in_turns": modes,
         "other_workloads": others,
+        "interleaved_caller_work": interleaved,
         "roofline": roofline, "cpu_baseline": cpu,
     }
     if sh.ctx is not None:

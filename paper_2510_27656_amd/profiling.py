@@ -158,24 +158,42 @@ def counters(counter_csv, out_md, title, command, per_kernel_note=""):
     print("\n".join(out))
 
 
-def timeline(trace_csv, bench_log, out_md, title, command):
+def timeline(trace_csv, bench_log, out_md, title, command, foreign=False):
     """One step of a two-stream run as a table of kernel start and end times per queue, and
     how often, over all traced steps, a receive-side kernel (gate or polling receive kernel)
-    was already running when the send kernels it waits for started."""
-    rows = [r for r in csv.DictReader(open(trace_csv)) if "flmoe" in r["Kernel_Name"]]
+    was already running when the send kernels it waits for started.
+    foreign: also list the kernels that are not the library's (a caller's own work on another
+    stream), by the first 40 characters of their names; the waiting statistic is left out then."""
+    rows = [r for r in csv.DictReader(open(trace_csv)) if foreign or "flmoe" in r["Kernel_Name"]]
+    rows = [r for r in rows if "plain_copy" not in r["Kernel_Name"] and "elementwise" not in r["Kernel_Name"]
+            and "distribution" not in r["Kernel_Name"]]
     rows.sort(key=lambda r: int(r["Start_Timestamp"]))
     starts = [i for i, r in enumerate(rows) if "route_layout" in r["Kernel_Name"]]
     steps = [rows[a:b] for a, b in zip(starts, starts[1:] + [len(rows)])]
-    steps = [st for st in steps if len(st) == len(steps[len(steps) // 2])]       # whole steps only
+    if foreign:                       # the steps that ran together with the caller's kernels
+        steps = [st for st in steps if any("flmoe" not in r["Kernel_Name"] for r in st)]
+        usual = collections.Counter(len(st) for st in steps).most_common(1)[0][0]
+        steps = [st for st in steps if len(st) == usual]
+    else:
+        steps = [st for st in steps if len(st) == len(steps[len(steps) // 2])]   # whole steps only
     mid = steps[len(steps) // 2]
     t0 = int(mid[0]["Start_Timestamp"])
+    queues = ("the stream with the shuffle calls, and the stream with the caller's own kernels" if foreign else
+              "the stream with the layout and the receive calls, and the stream with the send calls")
     out = [f"# {title}\n", "Command (from /tmp with TMPDIR=/tmp on the MI355X box):\n", f"    {command}\n",
-           "Timeline of one step from the kernel trace (us since the step's first kernel; the queues are the "
-           "stream with the layout and the receive calls, and the stream with the send calls):\n",
+           f"Timeline of one step from the kernel trace (us since the step's first kernel; the queues are {queues}):\n",
            "| kernel | queue | start | end |", "|---|---|---|---|"]
     for r in mid:
-        out.append(f"| {_short(r['Kernel_Name'])} | {r['Queue_Id']} | {(int(r['Start_Timestamp']) - t0) / 1e3:.1f} | "
+        name = _short(r["Kernel_Name"]) if "flmoe" in r["Kernel_Name"] else "(caller) " + r["Kernel_Name"][:40]
+        out.append(f"| {name} | {r['Queue_Id']} | {(int(r['Start_Timestamp']) - t0) / 1e3:.1f} | "
                    f"{(int(r['End_Timestamp']) - t0) / 1e3:.1f} |")
+    if foreign:
+        j = _json_line(bench_log)
+        out.append(f"\nbench line of that run (profiler attached): {json.dumps(j.get('interleaved_caller_work'))}; "
+                   f"library build id {j.get('library_build_id', 'not recorded')}.")
+        open(out_md, "w").write("\n".join(out) + "\n")
+        print("\n".join(out))
+        return
 
     def span(step, pred):
         ks = [r for r in step if pred(r["Kernel_Name"])]
@@ -214,9 +232,10 @@ def main():
     t = sub.add_parser("timeline")
     t.add_argument("trace_csv"); t.add_argument("bench_log"); t.add_argument("out_md")
     t.add_argument("--title", required=True); t.add_argument("--command", required=True)
+    t.add_argument("--foreign", action="store_true")
     args = ap.parse_args()
     if args.cmd == "timeline":
-        timeline(args.trace_csv, args.bench_log, args.out_md, args.title, args.command)
+        timeline(args.trace_csv, args.bench_log, args.out_md, args.title, args.command, args.foreign)
     elif args.cmd == "kernel-trace":
         kernel_trace(args.stats_csv, args.bench_log, args.out_md, args.title, args.command)
     elif args.cmd == "traffic":

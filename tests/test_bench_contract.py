@@ -47,8 +47,8 @@ def test_bench_prints_one_json_line_with_the_agreed_keys():
     assert (roof["traffic"] is None) == ("traffic_stale" in roof)
     assert line["library_build_id"] and line["step_us"] > 0
     for key in ("write_ceiling_gbps", "read_ceiling_gbps", "kernel_frac_of_read_write_bound",
-                "modes_measured_in_turns", "other_workloads"):
-        assert key in line, key                 # the last two are filled on the headline workload only
+                "modes_measured_in_turns", "other_workloads", "interleaved_caller_work"):
+        assert key in line, key                 # the last three are filled on the headline workload only
 
 
 @pytest.mark.gpu

@@ -429,13 +429,15 @@ int fl_moe_debug_launch_groups(const fl_moe_config *cfg /*host*/, int rank_count
                                int *ranks_per_group /*host*/);
 
 /* Diagnostic: plain linear device copy of `bytes` bytes with 16-byte accesses
- * (multiple of 16, both pointers 16-byte aligned).  Used to measure the copy ceiling of the
+ * (multiple of 16, both pointers 16-byte aligned), in the launch shape that measured
+ * fastest for a linear copy on this part.  Used to measure the copy ceiling of the
  * machine and to calibrate hardware byte counters against a known size. */
 int fl_moe_debug_copy(void *dst, const void *src, size_t bytes, void *stream);
 
-/* Diagnostic: the write-only and read-only counterparts of fl_moe_debug_copy, same launch
- * shape (fill: 16-byte streaming stores of a constant; read: 16-byte streaming loads whose
- * values are folded and, practically never, written to the 4-byte word `sink`).  They
+/* Diagnostic: the write-only and read-only counterparts of fl_moe_debug_copy, each in its
+ * own fastest launch shape (fill: 16-byte streaming stores of a constant; read: 16-byte
+ * streaming loads whose values are folded and, practically never, written to the 4-byte
+ * word `sink`).  They
  * measure the machine's one-directional ceilings, against which kernels that mostly
  * write (dispatch pack) or mostly read (combine reduce) are judged. */
 int fl_moe_debug_fill(void *dst, size_t bytes, void *stream);

@@ -947,35 +947,42 @@ int fl_moe_debug_launch_groups(const fl_moe_config *cfg, int rank_count, int lau
     return FL_OK;
 }
 
+// launch shapes of the three plain kernels: the fastest measured for each (see the kernels)
+constexpr int kPlainCopyThreads = 64, kPlainCopyVecs = 4;
+constexpr int kPlainFillThreads = 256, kPlainFillVecs = 1;
+constexpr int kPlainReadThreads = 1024, kPlainReadVecs = 1;
+
 int fl_moe_debug_copy(void *dst, const void *src, size_t bytes, void *stream) {
     if (!dst || !src || bytes == 0 || bytes % 16 != 0) return FL_ERR_INVALID_ARG;
     if (!aligned16(dst) || !aligned16(src)) return FL_ERR_ALIGNMENT;
-    const size_t nvec = bytes / 16;
-    const size_t blocks = (nvec + kCopyThreads * 4 - 1) / (kCopyThreads * 4);
+    const size_t nvec = bytes / 16, per = (size_t)kPlainCopyThreads * kPlainCopyVecs;
+    const size_t blocks = (nvec + per - 1) / per;
     if (blocks >= (1ull << 31)) return FL_ERR_INVALID_ARG;
-    plain_copy_kernel<<<dim3((unsigned)blocks), dim3(kCopyThreads), 0, (hipStream_t)stream>>>(
-        (v4u *)dst, (const v4u *)src, nvec);
+    plain_copy_kernel<kPlainCopyThreads, kPlainCopyVecs>
+        <<<dim3((unsigned)blocks), dim3(kPlainCopyThreads), 0, (hipStream_t)stream>>>((v4u *)dst, (const v4u *)src, nvec);
     return launch_status();
 }
 
 int fl_moe_debug_fill(void *dst, size_t bytes, void *stream) {
     if (!dst || bytes == 0 || bytes % 16 != 0) return FL_ERR_INVALID_ARG;
     if (!aligned16(dst)) return FL_ERR_ALIGNMENT;
-    const size_t nvec = bytes / 16;
-    const size_t blocks = (nvec + kCopyThreads * 4 - 1) / (kCopyThreads * 4);
+    const size_t nvec = bytes / 16, per = (size_t)kPlainFillThreads * kPlainFillVecs;
+    const size_t blocks = (nvec + per - 1) / per;
     if (blocks >= (1ull << 31)) return FL_ERR_INVALID_ARG;
-    plain_fill_kernel<<<dim3((unsigned)blocks), dim3(kCopyThreads), 0, (hipStream_t)stream>>>((v4u *)dst, nvec, 0x3C3C3C3Cu);
+    plain_fill_kernel<kPlainFillThreads, kPlainFillVecs>
+        <<<dim3((unsigned)blocks), dim3(kPlainFillThreads), 0, (hipStream_t)stream>>>((v4u *)dst, nvec, 0x3C3C3C3Cu);
     return launch_status();
 }
 
 int fl_moe_debug_read(const void *src, size_t bytes, void *sink, void *stream) {
     if (!src || !sink || bytes == 0 || bytes % 16 != 0) return FL_ERR_INVALID_ARG;
     if (!aligned16(src) || ((uintptr_t)sink & 3)) return FL_ERR_ALIGNMENT;
-    const size_t nvec = bytes / 16;
-    const size_t blocks = (nvec + kCopyThreads * 4 - 1) / (kCopyThreads * 4);
+    const size_t nvec = bytes / 16, per = (size_t)kPlainReadThreads * kPlainReadVecs;
+    const size_t blocks = (nvec + per - 1) / per;
     if (blocks >= (1ull << 31)) return FL_ERR_INVALID_ARG;
-    plain_read_kernel<<<dim3((unsigned)blocks), dim3(kCopyThreads), 0, (hipStream_t)stream>>>(
-        (const v4u *)src, nvec, (unsigned *)sink);
+    plain_read_kernel<kPlainReadThreads, kPlainReadVecs>
+        <<<dim3((unsigned)blocks), dim3(kPlainReadThreads), 0, (hipStream_t)stream>>>((const v4u *)src, nvec,
+                                                                                       (unsigned *)sink);
     return launch_status();
 }
 

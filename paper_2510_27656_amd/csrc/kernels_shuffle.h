@@ -1035,45 +1035,50 @@ __global__ __launch_bounds__(kReduceMaxThreads, 7) void combine_reduce_kernel(
 }
 
 // ------------------------------------------------------------------ diagnostic copy
-// Plain linear copy in the shape that measured fastest on this part: one 16 KB
-// chunk per block, four non-temporal loads per thread in flight, then the stores.
-__global__ __launch_bounds__(kCopyThreads) void plain_copy_kernel(v4u *__restrict__ dst,
-                                                                  const v4u *__restrict__ src,
-                                                                  size_t nvec) {
-    const size_t base = (size_t)blockIdx.x * kCopyThreads * 4 + threadIdx.x;
-    v4u r[4];
+// Plain linear copy, fill and read: the machine's ceilings for a stream of 16-byte
+// accesses, each in the launch shape that measured fastest for it on this part (1 GiB,
+// non-temporal accesses).  Workgroups that move little and end at once do best:
+//   copy  64 threads x 4 vectors (4 KB per workgroup) 6 450 GB/s of read + write traffic;
+//         256 x 1: 6 340; 256 x 4 (16 KB): 5 930; 1024 x 4 (64 KB): 5 290
+//   fill  256 x 1 (4 KB) 6 790 GB/s; 128 x 2: 6 490; 64 x 4: 6 320; 256 x 4 (16 KB): 6 000;
+//         256 x 16 (64 KB): 4 940
+//   read  flat at 7 000 - 7 100 GB/s from 2 KB to 32 KB per workgroup, 1024 x 1: 7 200 - 7 500
+// THREADS threads take U vectors each, all loads before the stores.
+template <int THREADS, int U>
+__global__ __launch_bounds__(THREADS) void plain_copy_kernel(v4u *__restrict__ dst, const v4u *__restrict__ src,
+                                                             size_t nvec) {
+    const size_t base = (size_t)blockIdx.x * THREADS * U + threadIdx.x;
+    v4u r[U];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
-        if (base + (size_t)i * kCopyThreads < nvec) r[i] = ld_stream(src + base + (size_t)i * kCopyThreads);
+    for (int i = 0; i < U; ++i)
+        if (base + (size_t)i * THREADS < nvec) r[i] = ld_stream(src + base + (size_t)i * THREADS);
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
-        if (base + (size_t)i * kCopyThreads < nvec) st_stream(dst + base + (size_t)i * kCopyThreads, r[i]);
+    for (int i = 0; i < U; ++i)
+        if (base + (size_t)i * THREADS < nvec) st_stream(dst + base + (size_t)i * THREADS, r[i]);
 }
 
-
-// Write-only and read-only companions of plain_copy_kernel, same shape (16 KB per block,
-// four 16-byte accesses per thread): the two one-directional ceilings of the machine,
-// against which kernels that mostly write (dispatch pack) or mostly read (combine
-// reduce) are to be judged.
-__global__ __launch_bounds__(kCopyThreads) void plain_fill_kernel(v4u *__restrict__ dst, size_t nvec,
-                                                                  unsigned value) {
-    const size_t base = (size_t)blockIdx.x * kCopyThreads * 4 + threadIdx.x;
+// Write-only and read-only companions: the two one-directional ceilings, against which
+// kernels that mostly write (dispatch pack) or mostly read (combine reduce) are judged.
+template <int THREADS, int U>
+__global__ __launch_bounds__(THREADS) void plain_fill_kernel(v4u *__restrict__ dst, size_t nvec, unsigned value) {
+    const size_t base = (size_t)blockIdx.x * THREADS * U + threadIdx.x;
     const v4u v = {value, value, value, value};
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
-        if (base + (size_t)i * kCopyThreads < nvec) st_stream(dst + base + (size_t)i * kCopyThreads, v);
+    for (int i = 0; i < U; ++i)
+        if (base + (size_t)i * THREADS < nvec) st_stream(dst + base + (size_t)i * THREADS, v);
 }
 
-__global__ __launch_bounds__(kCopyThreads) void plain_read_kernel(const v4u *__restrict__ src, size_t nvec,
-                                                                  unsigned *__restrict__ sink) {
-    const size_t base = (size_t)blockIdx.x * kCopyThreads * 4 + threadIdx.x;
-    v4u r[4] = {};
+template <int THREADS, int U>
+__global__ __launch_bounds__(THREADS) void plain_read_kernel(const v4u *__restrict__ src, size_t nvec,
+                                                             unsigned *__restrict__ sink) {
+    const size_t base = (size_t)blockIdx.x * THREADS * U + threadIdx.x;
+    v4u r[U] = {};
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
-        if (base + (size_t)i * kCopyThreads < nvec) r[i] = ld_stream(src + base + (size_t)i * kCopyThreads);
+    for (int i = 0; i < U; ++i)
+        if (base + (size_t)i * THREADS < nvec) r[i] = ld_stream(src + base + (size_t)i * THREADS);
     unsigned x = 0;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) x ^= r[i].x ^ r[i].y ^ r[i].z ^ r[i].w;
+    for (int i = 0; i < U; ++i) x ^= r[i].x ^ r[i].y ^ r[i].z ^ r[i].w;
     if (x == 0x9E3779B9u) *sink = x;      // keeps the loads alive; practically never taken
 }
 

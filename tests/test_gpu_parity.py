@@ -1374,6 +1374,32 @@ def test_withheld_arrival_counter_times_out_then_recovers(kw):
         sh.close()
 
 
+@pytest.mark.parametrize("nbytes", [16, 4096, 4096 + 16, 65536 - 16, (1 << 20) + 48])
+def test_plain_copy_fill_and_read_kernels_stay_inside_their_buffers(nbytes):
+    """The three diagnostic kernels (machine ceilings, counter calibration) on sizes that
+    end inside a workgroup's share: the copy is exact, the fill writes its constant, and
+    neither touches the bytes on either side of the range it was given."""
+    guard = 4096
+    gen = torch.Generator(device="cuda").manual_seed(nbytes)
+    src = torch.randint(0, 256, (nbytes + 2 * guard,), dtype=torch.uint8, device="cuda", generator=gen)
+    dst = torch.full((nbytes + 2 * guard,), 0xA5, dtype=torch.uint8, device="cuda")
+    flmoe.fl_moe_debug_copy(dst[guard:], src[guard:], nbytes)
+    torch.cuda.synchronize()
+    assert torch.equal(dst[guard:guard + nbytes], src[guard:guard + nbytes])
+    assert bool((dst[:guard] == 0xA5).all()) and bool((dst[guard + nbytes:] == 0xA5).all())
+    flmoe.fl_moe_debug_fill(dst[guard:], nbytes)
+    torch.cuda.synchronize()
+    assert bool((dst[guard:guard + nbytes] == 0x3C).all())
+    assert bool((dst[:guard] == 0xA5).all()) and bool((dst[guard + nbytes:] == 0xA5).all())
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+    before = src.clone()
+    flmoe.fl_moe_debug_read(src[guard:], nbytes, sink)
+    torch.cuda.synchronize()
+    assert torch.equal(src, before)
+    with pytest.raises(flmoe.FlMoeError):
+        flmoe.fl_moe_debug_copy(dst[guard:], src[guard:], 24)          # not a multiple of 16
+
+
 def test_host_visible_argument_errors():
     inp, dev, sh = small_shuffle()
     try:
